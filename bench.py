@@ -1,0 +1,191 @@
+"""Benchmark of one Spec-VLA tree-verification step on one MI355X.
+
+step = 32 x sv_verify_layer -> sv_action_head_argmax -> sv_relaxed_accept for the full
+7B-shaped configuration (60-node tree, 280-token prefix, bf16 weights), all inputs resident
+in HBM.  Prints ONE JSON line: verified tree tokens/s, step latency, the HBM roofline of the
+dominant kernel (the weight-streaming GEMM, timed live with HIP events) and the CPU oracle
+timed on a bounded sample of the same workload.
+"""
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+class HipEvents:
+    """hipEvent_t handles through the HIP runtime's C API (for sv_verify_layer_timed)."""
+
+    def __init__(self, n):
+        self.hip = C.CDLL("libamdhip64.so")
+        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.arr = (C.c_void_p * n)()
+        for i in range(n):
+            ev = C.c_void_p()
+            assert self.hip.hipEventCreate(C.byref(ev)) == 0
+            self.arr[i] = ev.value
+
+    def block(self, first, count):
+        return C.cast(C.byref(self.arr, first * C.sizeof(C.c_void_p)), C.c_void_p)
+
+    def elapsed_ms(self, a, b):
+        out = C.c_float()
+        rc = self.hip.hipEventElapsedTime(C.byref(out), self.arr[a], self.arr[b])
+        assert rc == 0, rc
+        return out.value
+
+
+def cpu_baseline(cfg, wl, n_sample_layers=2):
+    """The oracle as it stands on a bounded sample: n_sample_layers of the 32 layers of the
+    same workload + head + acceptance, scaled to a whole step."""
+    import numpy as np
+    import torch
+    from threadpoolctl import threadpool_info
+    from oracle import verify_oracle as vo
+    f64 = lambda t: t.to(torch.float64).numpy()
+    P = int(wl.prefix_lengths(cfg)[0])
+    parent = wl.episode_tree(cfg, 0)
+    x = f64(wl.hidden_rows(cfg, 0))
+    head = wl.head_weights(cfg)
+    gf, wlm = f64(head["g_final"]), f64(head["w_lm"])
+    t_layers = 0.0
+    for l in range(n_sample_layers):
+        w = {k: f64(v) for k, v in wl.layer_weights(cfg, l).items()}
+        kp, vp = (f64(t) for t in wl.prefix_kv(cfg, 0, l, P))
+        t0 = time.perf_counter()
+        x = vo.verify_layer(x, w, kp, vp, parent, cfg.n_heads, cfg.rms_eps, cfg.rope_theta)["x"]
+        t_layers += time.perf_counter() - t0
+    t0 = time.perf_counter()
+    _, tok = vo.action_head(x, gf, wlm, cfg.action_lo, cfg.rms_eps)
+    draft = wl.noisy_draft_tokens(cfg, 0, parent, tok)
+    vo.relaxed_accept(parent, draft, tok, cfg.action_lo, cfg.n_bins, 4)
+    t_tail = time.perf_counter() - t0
+    step_s = t_layers / n_sample_layers * cfg.n_layers + t_tail
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return {"value": cfg.tree_nodes / step_s, "unit": "verified tree tokens/s", "cores": threads,
+            "kind": "oracle",
+            "sample": f"{n_sample_layers} of {cfg.n_layers} layers + head + accept of the same "
+                      f"workload, float64 numpy; layer time scaled x{cfg.n_layers / n_sample_layers:g}",
+            "step_s_extrapolated": step_s}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--r", type=int, default=4)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers (invalid as a result)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build measures ONE GPU only (the tree-verification pass of one "
+                 "MI355X); --gpus must be 1")
+
+    import numpy as np
+    import torch
+    from paper_2507_22424_amd import binding as sv
+    from paper_2507_22424_amd import workload as wl
+    from paper_2507_22424_amd.runner import VerifyPass
+
+    cfg = wl.C3 if args.layers is None else wl.C3.scaled(n_layers=args.layers)
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+    B, T, L = cfg.n_episodes, cfg.tree_nodes, cfg.n_layers
+    prefix_len = wl.prefix_lengths(cfg)
+    parent = wl.episode_tree(cfg, 0)
+    vp = VerifyPass(cfg, prefix_len, parent)
+
+    t0 = time.time()
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        futs = [ex.submit(wl.layer_weights, cfg, l) for l in range(L)]
+        for l, f in enumerate(futs):
+            vp.load_layer(l, f.result())
+            futs[l] = None
+            k, v = wl.prefix_kv(cfg, 0, l, int(prefix_len[0]))
+            vp.load_prefix(l, 0, k, v)
+            if l % 8 == 7:
+                log(f"bench: {l + 1}/{L} layers resident ({time.time() - t0:.0f}s)")
+    head = wl.head_weights(cfg)
+    vp.load_head(head["g_final"], head["w_lm"])
+    vp.set_hidden(wl.hidden_rows(cfg, 0))
+
+    # draft ids within +-8 bins of the verifier's own choice (two-phase: one untimed forward)
+    vp.forward(want_logits=False)
+    torch.cuda.synchronize()
+    vp.set_draft(wl.noisy_draft_tokens(cfg, 0, parent, vp.token.cpu().numpy()))
+
+    for _ in range(args.warmup):
+        vp.step(args.r)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        vp.step(args.r)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    tokens_per_s = B * T / (dt / args.steps)
+    accepted = vp.accepted_len.cpu().tolist()
+
+    # per-kernel durations with HIP events around single launches, same stream, same inputs
+    n_ev = sv.SV_N_TIMING_EVENTS
+    evs = HipEvents(n_ev * L)
+    prof_steps = max(1, min(args.steps, 10))
+    pairs = {"qkv": (0, 1), "attn": (2, 3), "o": (3, 4), "gate_up": (5, 6), "down": (7, 8)}
+    acc_ms = {k: 0.0 for k in pairs}
+    for _ in range(prof_steps):
+        vp.x.copy_(vp.x0)
+        for l in range(L):
+            sv.sv_verify_layer_timed(vp.cfg, vp.packed[l], vp.x, vp.kv[l].struct, vp.tree.struct,
+                                     B, vp.workspace, evs.block(l * n_ev, n_ev))
+        torch.cuda.synchronize()
+        for l in range(L):
+            for k, (a, b) in pairs.items():
+                acc_ms[k] += evs.elapsed_ms(l * n_ev + a, l * n_ev + b)
+    per_step_ms = {k: v / prof_steps for k, v in acc_ms.items()}
+    H, D, F = cfg.hidden, cfg.n_heads * cfg.head_dim, cfg.mlp_dim
+    gemm_bytes = {"qkv": 3 * D * H * 2, "o": H * D * 2, "gate_up": 2 * F * H * 2, "down": H * F * 2}
+    gemm_ms = sum(per_step_ms[k] for k in gemm_bytes)
+    gemm_gbs = sum(gemm_bytes.values()) * L / (gemm_ms * 1e-3) / 1e9
+    kv_bytes = 2 * cfg.n_heads * (int(prefix_len[0]) + T) * cfg.head_dim * 2
+    weights_total = sum(gemm_bytes.values()) * L
+    step_bytes = weights_total + kv_bytes * L + cfg.n_bins * H * 2 + 2 * cfg.n_heads * T * cfg.head_dim * 2 * L
+
+    out = {
+        "metric": "verified tree tokens/sec + step latency (7B-shaped, tree 60); % HBM peak",
+        "value": tokens_per_s, "unit": "verified tree tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"C3: {L}-layer 7B-shaped verify pass + 256-bin action head + "
+                               f"relaxed accept (r={args.r}), tree {T} nodes depth 7, prefix "
+                               f"{int(prefix_len[0])}, 1 episode",
+                   "hidden": H, "layers": L, "tree_nodes": T, "prefix": int(prefix_len[0])},
+        "step_hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "step_algorithmic_bytes": step_bytes,
+        "accepted_len": accepted,
+        "kernel_ms_per_step": per_step_ms,
+        "roofline": {"bound": "hbm", "kernel": "gemm_skinny_bf16 (4 launches per layer)",
+                     "achieved": gemm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": gemm_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch_avg": weights_total / (4 * L),
+                     "avg_launch_us": gemm_ms * 1e3 / (4 * L)},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, wl)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,197 @@
+/*
+ * libspecvla_verify - the per-step tree-verification pass of Spec-VLA on one MI355X (gfx950).
+ *
+ * What the pass computes (paper: Alg. 1, the step "compute the reference token set in
+ * parallel"; Sec. 4.1: the draft tokens form a tree whose paths are verified in parallel;
+ * Sec. 4.3 / Eq. 5: relaxed acceptance): a Llama-shaped verifier scores all T nodes of a draft
+ * token tree in one forward pass over a prefix KV cache, takes the greedy argmax over the
+ * action tokens at every node (Eq. 1), accepts a draft token when the distance between its
+ * bin and the verifier's bin is at most r, and returns the longest accepted root-to-node path
+ * plus the verifier's own token that follows it.
+ *
+ * Conventions
+ *   - Plain C ABI.  Every pointer is tagged [host] or [device] below.  The caller owns every
+ *     buffer; the library allocates no device memory, keeps no state between calls and
+ *     frees nothing.  `stream` is a hipStream_t passed as void*; all device work of a call
+ *     is enqueued on it and the call returns without waiting for it.
+ *   - Every call returns an int status: SV_OK (0) or a negative SV_ERR_* code.  Arguments are
+ *     checked on the host before anything is launched; on error nothing was launched.
+ *     Faults inside kernels surface at the caller's next synchronisation, as with any launch.
+ *   - Calls that share no buffers may run concurrently from several threads.
+ *   - Rows of matrices are contiguous ("[rows, cols]" = row-major).  Weights are stored
+ *     [out_features, in_features] as in Llama checkpoints.
+ *   - T counts the root: node 0 of every tree is the last committed token, nodes 1..T-1 are
+ *     draft tokens.  parent[0] = -1 and 0 <= parent[i] < i.  depth(root) = 0.
+ *   - The residual stream x is always float32, whatever the storage type of weights and
+ *     cache: activations are a negligible share of the bytes moved and keeping them wide
+ *     keeps near-tie argmax flips rare.
+ */
+#ifndef SPECVLA_VERIFY_H
+#define SPECVLA_VERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SV_OK 0
+#define SV_ERR_NULL (-1)      /* a required pointer is NULL */
+#define SV_ERR_SHAPE (-2)     /* a size is unsupported (see each call) */
+#define SV_ERR_TREE (-3)      /* parent array is not a tree in the stated form, or too deep */
+#define SV_ERR_TOKEN (-4)     /* action range / threshold arguments are inconsistent */
+#define SV_ERR_WORKSPACE (-5) /* workspace or packed buffer too small or misaligned */
+#define SV_ERR_DTYPE (-6)     /* cfg->dtype is neither SV_F32 nor SV_BF16 */
+#define SV_ERR_LAUNCH (-7)    /* the HIP runtime reported an error at launch */
+
+#define SV_F32 0
+#define SV_BF16 1
+
+#define SV_MAX_TREE_NODES 128 /* T <= 128: the ancestor mask has at most two 64-bit words */
+#define SV_MAX_DEPTH 31       /* depth of a node, in edges */
+
+/* Shape of the verifier (Sec. 4.1, 5.1: OpenVLA = Llama-2 backbone). */
+typedef struct sv_model_cfg {
+  int32_t dtype;      /* SV_F32 or SV_BF16: storage type of weights and KV cache */
+  int32_t hidden;     /* H */
+  int32_t n_heads;    /* nh (multi-head attention, n_kv_heads = n_heads) */
+  int32_t head_dim;   /* d; nh * d is the attention width (need not equal H) */
+  int32_t mlp_dim;    /* F, SwiGLU inner width */
+  int32_t vocab;      /* V, rows of the LM head */
+  float rms_eps;      /* RMSNorm epsilon */
+  float rope_theta;   /* RoPE base */
+} sv_model_cfg;
+
+/* One decoder layer as the caller holds it: [device] pointers, cfg->dtype elements.
+ * g1, g2: [H]; wq, wk, wv: [nh*d, H]; wo: [H, nh*d]; wg, wu: [F, H]; wd: [H, F]. */
+typedef struct sv_layer_weights {
+  const void *g1, *wq, *wk, *wv, *wo, *g2, *wg, *wu, *wd;
+} sv_layer_weights;
+
+/* KV cache of ONE layer for B episodes.  k and v: [device], layout
+ * [B][n_heads][capacity][head_dim], cfg->dtype.  Rows 0 .. prefix_len[b]-1 of episode b
+ * hold the prefix (vision patches + instruction tokens; keys already rotated) and are only
+ * read.  sv_verify_layer WRITES the tree's own rotated keys and values to rows
+ * prefix_len[b] .. prefix_len[b]+T-1, so capacity >= prefix_len_max + T is required.
+ * prefix_len: [device] int32[B].  prefix_len_max: [host value] an upper bound of all
+ * prefix_len[b], used for checking and launch planning; kernels clamp prefix_len[b] to it. */
+typedef struct sv_kv_view {
+  void *k;
+  void *v;
+  const int32_t *prefix_len;
+  int32_t prefix_len_max;
+  int32_t capacity;
+} sv_kv_view;
+
+/* Draft trees of B episodes, T nodes each, as produced by sv_tree_build_masks and copied
+ * to the device by the caller.  All [device]: parent int32[B*T], depth int32[B*T],
+ * anc_mask uint64[B*T*n_words] with n_words = ceil(T/64); bit j of node i's mask (word j/64)
+ * is set iff node j lies on the path root..i, i itself included. */
+typedef struct sv_tree {
+  const int32_t *parent;
+  const int32_t *depth;
+  const uint64_t *anc_mask;
+  int32_t n_nodes; /* T, 1..SV_MAX_TREE_NODES */
+  int32_t n_words; /* ceil(T/64) */
+} sv_tree;
+
+const char *sv_version(void);
+const char *sv_strerror(int status);
+
+/* Host-only.  Checks B parent arrays ([host] int32[B*T]: parent[b*T] = -1, 0 <= parent < own
+ * index otherwise) and derives depth ([host] int32[B*T]) and ancestor-or-self masks ([host]
+ * uint64[B*T*ceil(T/64)]).  These encode which keys a tree node may attend to and its
+ * position P + depth (Sec. 4.1: every path of the tree is verified as if decoded alone).
+ * SV_ERR_TREE if an array is not such a tree or a depth exceeds d_cap (d_cap <= SV_MAX_DEPTH);
+ * SV_ERR_SHAPE if T is outside 1..SV_MAX_TREE_NODES or B < 1. */
+int sv_tree_build_masks(const int32_t *parent, int B, int T, int d_cap, int32_t *depth,
+                        uint64_t *anc_mask);
+
+/* Host-only.  Bytes of the packed form of one layer (sv_pack_layer) -> *bytes. */
+int sv_packed_layer_bytes(const sv_model_cfg *cfg, size_t *bytes);
+
+/* One-time, load-time re-tiling of a layer's nine tensors into the order the kernels stream
+ * them (q/k/v fused, gate/up fused, matrices cut into matrix-core fragments, gains widened to
+ * float32).  raw: [host] struct of [device] pointers; packed: [device], 256-byte aligned,
+ * packed_bytes >= sv_packed_layer_bytes.  The packed layout is private to the library and
+ * may change between versions; raw tensors are not needed afterwards.
+ * SV_BF16 needs H, nh*d, F multiples of 128 and d = 128; SV_F32 takes any sizes with d even. */
+int sv_pack_layer(const sv_model_cfg *cfg, const sv_layer_weights *raw, void *packed,
+                  size_t packed_bytes, void *stream);
+
+/* Host-only.  Bytes of device scratch that sv_verify_layer / sv_action_head_argmax need for
+ * B episodes of T nodes and up to n_scored scored vocabulary rows -> *bytes. */
+int sv_workspace_bytes(const sv_model_cfg *cfg, int B, int T, int n_scored, size_t *bytes);
+
+/* Host-only inspection aid for tests: where an intermediate of the last sv_verify_layer call
+ * lives inside the workspace.  which = SV_WS_ATTN_OUT: attention output before the output
+ * projection, [B*T, nh*d], cfg->dtype elements.  which = SV_WS_Q: rotated queries, float32
+ * [B*T, nh*d]. */
+#define SV_WS_ATTN_OUT 0
+#define SV_WS_Q 1
+int sv_workspace_region(const sv_model_cfg *cfg, int B, int T, int n_scored, int which,
+                        size_t *offset, size_t *bytes);
+
+/* One decoder layer over all B*T tree nodes (Alg. 1's parallel verification, one layer of
+ * M_V): RMSNorm, q/k/v projections, RoPE at position prefix_len[b] + depth, append of the
+ * tree's keys/values to the cache, attention of node i over {prefix keys} + {tree nodes on
+ * the path root..i}, output projection + residual, RMSNorm, SwiGLU MLP + residual.
+ *   packed:    [device] from sv_pack_layer (same cfg)
+ *   x:         [device] float32 [B*T, H], residual stream, updated in place
+ *   kv, tree:  [host] structs of [device] pointers, see above; tree->n_nodes = T
+ *   workspace: [device], 256-byte aligned, ws_bytes >= sv_workspace_bytes(cfg, B, T, *)
+ * SV_ERR_SHAPE if B < 1, T outside 1..SV_MAX_TREE_NODES, capacity < prefix_len_max + T, or
+ * cfg sizes are unsupported for the dtype (see sv_pack_layer). */
+int sv_verify_layer(const sv_model_cfg *cfg, const void *packed, float *x,
+                    const sv_kv_view *kv, const sv_tree *tree, int B, void *workspace,
+                    size_t ws_bytes, void *stream);
+
+/* Measurement aid: exactly sv_verify_layer, but records the caller's HIP events on `stream`
+ * around single kernel launches so that a benchmark can read per-kernel durations with
+ * hipEventElapsedTime: events[0],[1] bracket the q/k/v GEMM, [2],[3] the tree attention,
+ * [3],[4] the output GEMM, [5],[6] the gate/up GEMM, [7],[8] the down GEMM.
+ * events: [host] array of SV_N_TIMING_EVENTS hipEvent_t (created by the caller with timing
+ * enabled).  SV_ERR_NULL if the array or an entry is NULL. */
+#define SV_N_TIMING_EVENTS 9
+int sv_verify_layer_timed(const sv_model_cfg *cfg, const void *packed, float *x,
+                          const sv_kv_view *kv, const sv_tree *tree, int B, void *workspace,
+                          size_t ws_bytes, void *stream, void *const *events);
+
+/* Final RMSNorm, LM-head logits of vocabulary rows [vocab_lo, vocab_hi) and the greedy
+ * choice among them (Eq. 1), the lowest id winning exact ties.  vocab_lo = V - 256,
+ * vocab_hi = V scores the action tokens only (Sec. 4.3: 256 bins <-> 256 tokens).
+ *   g_final: [device] [H] cfg->dtype;  w_lm: [device] [V, H] cfg->dtype (plain row-major)
+ *   x: [device] float32 [n_rows, H];  out_token: [device] int32[n_rows]
+ *   out_logits: [device] float32 [n_rows, vocab_hi - vocab_lo], or NULL
+ * SV_ERR_SHAPE unless 0 <= vocab_lo < vocab_hi <= V and n_rows >= 1. */
+int sv_action_head_argmax(const sv_model_cfg *cfg, const void *g_final, const void *w_lm,
+                          const float *x, int n_rows, int vocab_lo, int vocab_hi,
+                          int32_t *out_token, float *out_logits, void *workspace,
+                          size_t ws_bytes, void *stream);
+
+/* Relaxed acceptance (Eq. 5, Alg. 1) over B trees and the longest accepted path.  Integer
+ * only.  bin(t) = t - action_lo.  Node c >= 1 passes when draft_token[c] and
+ * target_token[parent[c]] are both action tokens and |bin difference| <= r; r = 0 is strict
+ * matching (Eq. 3).  A node is accepted when it and every node above it pass (tokens after
+ * the first rejection on a path are dropped).  best = deepest accepted node, lowest index
+ * among equals.
+ *   draft_token, target_token: [device] int32[B*T] (entry 0 of each tree's draft is unused)
+ *   accept_mask:  [device] uint8[B*T], 1 = accepted (root always 1)
+ *   accepted_len: [device] int32[B] = depth(best);  best_node: [device] int32[B]
+ *   path:         [device] int32[B, d_cap+1]: root..best, then -1
+ *   out_tokens:   [device] int32[B, d_cap+1]: the accepted draft tokens, then the verifier's
+ *                 token target_token[best] (Alg. 1: accepted positions keep the draft token;
+ *                 the verifier's token fills the first rejected position or is the extra
+ *                 token), then -1.  A step thus emits accepted_len + 1 tokens.
+ * Nodes deeper than d_cap are treated as rejected.  SV_ERR_TOKEN if n_bins < 1, r < 0 or
+ * action_lo < 0; SV_ERR_SHAPE for B < 1, bad T or d_cap outside 0..SV_MAX_DEPTH. */
+int sv_relaxed_accept(const sv_tree *tree, const int32_t *draft_token,
+                      const int32_t *target_token, int action_lo, int n_bins, int r, int B,
+                      int d_cap, uint8_t *accept_mask, int32_t *accepted_len,
+                      int32_t *best_node, int32_t *path, int32_t *out_tokens, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECVLA_VERIFY_H */

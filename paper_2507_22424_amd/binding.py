@@ -1,0 +1,261 @@
+"""ctypes binding of libspecvla_verify: same names as include/specvla_verify.h.
+
+Argument marshalling only - every step of the verification pass runs in the HIP kernels of
+the library.  PyTorch supplies device memory (tensors) and the stream.  There is no CPU
+fallback: if the library has not been built, importing a function from it raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+from .build import LIB_PATH
+
+SV_F32, SV_BF16 = 0, 1
+SV_MAX_TREE_NODES = 128
+SV_MAX_DEPTH = 31
+SV_WS_ATTN_OUT, SV_WS_Q = 0, 1
+
+EXPORTS = ("sv_version", "sv_strerror", "sv_tree_build_masks", "sv_packed_layer_bytes",
+           "sv_pack_layer", "sv_workspace_bytes", "sv_workspace_region", "sv_verify_layer",
+           "sv_verify_layer_timed", "sv_action_head_argmax", "sv_relaxed_accept")
+SV_N_TIMING_EVENTS = 9
+
+
+class SvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {sv_strerror(status)} (status {status})")
+
+
+class ModelCfg(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("hidden", C.c_int32), ("n_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("mlp_dim", C.c_int32), ("vocab", C.c_int32),
+                ("rms_eps", C.c_float), ("rope_theta", C.c_float)]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("g1", "wq", "wk", "wv", "wo", "g2", "wg", "wu", "wd")]
+
+
+class KvView(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("prefix_len", C.c_void_p),
+                ("prefix_len_max", C.c_int32), ("capacity", C.c_int32)]
+
+
+class Tree(C.Structure):
+    _fields_ = [("parent", C.c_void_p), ("depth", C.c_void_p), ("anc_mask", C.c_void_p),
+                ("n_nodes", C.c_int32), ("n_words", C.c_int32)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded library; raises if it was never built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2507_22424_amd.build`"
+                               " (or __graft_entry__.build()) first")
+        l = C.CDLL(LIB_PATH)
+        l.sv_version.restype = C.c_char_p
+        l.sv_strerror.restype = C.c_char_p
+        l.sv_strerror.argtypes = [C.c_int]
+        l.sv_tree_build_masks.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+        l.sv_packed_layer_bytes.argtypes = [C.POINTER(ModelCfg), C.POINTER(C.c_size_t)]
+        l.sv_pack_layer.argtypes = [C.POINTER(ModelCfg), C.POINTER(LayerWeights), C.c_void_p,
+                                    C.c_size_t, C.c_void_p]
+        l.sv_workspace_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int, C.c_int, C.c_int,
+                                         C.POINTER(C.c_size_t)]
+        l.sv_workspace_region.argtypes = [C.POINTER(ModelCfg), C.c_int, C.c_int, C.c_int, C.c_int,
+                                          C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+        l.sv_verify_layer.argtypes = [C.POINTER(ModelCfg), C.c_void_p, C.c_void_p,
+                                      C.POINTER(KvView), C.POINTER(Tree), C.c_int, C.c_void_p,
+                                      C.c_size_t, C.c_void_p]
+        l.sv_verify_layer_timed.argtypes = l.sv_verify_layer.argtypes + [C.c_void_p]
+        l.sv_action_head_argmax.argtypes = [C.POINTER(ModelCfg), C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                            C.c_void_p, C.c_size_t, C.c_void_p]
+        l.sv_relaxed_accept.argtypes = [C.POINTER(Tree), C.c_void_p, C.c_void_p, C.c_int, C.c_int,
+                                        C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        _lib = l
+    return _lib
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise SvError(status, where)
+
+
+def _dev(t: Optional[torch.Tensor], dtype=None, name="tensor") -> int:
+    """Device pointer of a contiguous CUDA tensor (0 for None)."""
+    if t is None:
+        return 0
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def model_cfg(dtype: str, hidden: int, n_heads: int, head_dim: int, mlp_dim: int, vocab: int,
+              rms_eps: float = 1e-5, rope_theta: float = 1e4) -> ModelCfg:
+    code = {"f32": SV_F32, "bf16": SV_BF16}.get(dtype, dtype)
+    return ModelCfg(int(code), hidden, n_heads, head_dim, mlp_dim, vocab, rms_eps, rope_theta)
+
+
+def storage_dtype(cfg: ModelCfg) -> torch.dtype:
+    return torch.float32 if cfg.dtype == SV_F32 else torch.bfloat16
+
+
+# ---- the calls of include/specvla_verify.h -------------------------------------------
+
+def sv_version() -> str:
+    return lib().sv_version().decode()
+
+
+def sv_strerror(status: int) -> str:
+    return lib().sv_strerror(int(status)).decode()
+
+
+def sv_tree_build_masks(parent: np.ndarray, B: int, T: int, d_cap: int
+                        ) -> Tuple[np.ndarray, np.ndarray]:
+    """Host: depth int32[B*T] and ancestor masks uint64[B*T*ceil(T/64)] of B parent arrays."""
+    parent = np.ascontiguousarray(parent, dtype=np.int32).reshape(-1)
+    if parent.size != B * T:
+        raise ValueError("parent must hold B*T entries")
+    W = (T + 63) // 64
+    depth = np.zeros(B * T, dtype=np.int32)
+    anc = np.zeros(B * T * max(W, 1), dtype=np.uint64)
+    _check(lib().sv_tree_build_masks(parent.ctypes.data, B, T, d_cap, depth.ctypes.data,
+                                     anc.ctypes.data), "sv_tree_build_masks")
+    return depth, anc
+
+
+def sv_packed_layer_bytes(cfg: ModelCfg) -> int:
+    out = C.c_size_t(0)
+    _check(lib().sv_packed_layer_bytes(C.byref(cfg), C.byref(out)), "sv_packed_layer_bytes")
+    return out.value
+
+
+def sv_pack_layer(cfg: ModelCfg, raw: Dict[str, torch.Tensor], packed: torch.Tensor,
+                  stream=None) -> None:
+    dt = storage_dtype(cfg)
+    w = LayerWeights(*[_dev(raw[n], dt, n) for n, _ in LayerWeights._fields_])
+    _check(lib().sv_pack_layer(C.byref(cfg), C.byref(w), _dev(packed, torch.uint8, "packed"),
+                               packed.numel(), _stream(stream)), "sv_pack_layer")
+
+
+def sv_workspace_bytes(cfg: ModelCfg, B: int, T: int, n_scored: int) -> int:
+    out = C.c_size_t(0)
+    _check(lib().sv_workspace_bytes(C.byref(cfg), B, T, n_scored, C.byref(out)),
+           "sv_workspace_bytes")
+    return out.value
+
+
+def sv_workspace_region(cfg: ModelCfg, B: int, T: int, n_scored: int, which: int
+                        ) -> Tuple[int, int]:
+    off, nb = C.c_size_t(0), C.c_size_t(0)
+    _check(lib().sv_workspace_region(C.byref(cfg), B, T, n_scored, which, C.byref(off),
+                                     C.byref(nb)), "sv_workspace_region")
+    return off.value, nb.value
+
+
+def sv_verify_layer(cfg: ModelCfg, packed: torch.Tensor, x: torch.Tensor, kv: KvView,
+                    tree: Tree, B: int, workspace: torch.Tensor, stream=None) -> None:
+    if x.numel() != B * tree.n_nodes * cfg.hidden:
+        raise ValueError("x must be [B*T, hidden]")
+    _check(lib().sv_verify_layer(C.byref(cfg), _dev(packed, torch.uint8, "packed"),
+                                 _dev(x, torch.float32, "x"), C.byref(kv), C.byref(tree), B,
+                                 _dev(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                 _stream(stream)), "sv_verify_layer")
+
+
+def sv_verify_layer_timed(cfg: ModelCfg, packed: torch.Tensor, x: torch.Tensor, kv: KvView,
+                          tree: Tree, B: int, workspace: torch.Tensor, events, stream=None) -> None:
+    """`events`: ctypes array (c_void_p * SV_N_TIMING_EVENTS) of hipEvent_t handles."""
+    _check(lib().sv_verify_layer_timed(C.byref(cfg), _dev(packed, torch.uint8, "packed"),
+                                       _dev(x, torch.float32, "x"), C.byref(kv), C.byref(tree), B,
+                                       _dev(workspace, torch.uint8, "workspace"),
+                                       workspace.numel(), _stream(stream),
+                                       C.cast(events, C.c_void_p)), "sv_verify_layer_timed")
+
+
+def sv_action_head_argmax(cfg: ModelCfg, g_final: torch.Tensor, w_lm: torch.Tensor,
+                          x: torch.Tensor, n_rows: int, vocab_lo: int, vocab_hi: int,
+                          out_token: torch.Tensor, out_logits: Optional[torch.Tensor],
+                          workspace: torch.Tensor, stream=None) -> None:
+    dt = storage_dtype(cfg)
+    if w_lm.numel() != cfg.vocab * cfg.hidden or x.numel() < n_rows * cfg.hidden:
+        raise ValueError("w_lm must be [vocab, hidden] and x [n_rows, hidden]")
+    if out_token.numel() < n_rows or (out_logits is not None and
+                                      out_logits.numel() < n_rows * (vocab_hi - vocab_lo)):
+        raise ValueError("output tensors too small")
+    _check(lib().sv_action_head_argmax(
+        C.byref(cfg), _dev(g_final, dt, "g_final"), _dev(w_lm, dt, "w_lm"),
+        _dev(x, torch.float32, "x"), n_rows, vocab_lo, vocab_hi,
+        _dev(out_token, torch.int32, "out_token"), _dev(out_logits, torch.float32, "out_logits"),
+        _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)),
+        "sv_action_head_argmax")
+
+
+def sv_relaxed_accept(tree: Tree, draft_token: torch.Tensor, target_token: torch.Tensor,
+                      action_lo: int, n_bins: int, r: int, B: int, d_cap: int,
+                      accept_mask: torch.Tensor, accepted_len: torch.Tensor,
+                      best_node: torch.Tensor, path: torch.Tensor, out_tokens: torch.Tensor,
+                      stream=None) -> None:
+    T = tree.n_nodes
+    if draft_token.numel() != B * T or target_token.numel() != B * T or \
+            accept_mask.numel() != B * T or accepted_len.numel() != B or \
+            best_node.numel() != B or path.numel() != B * (d_cap + 1) or \
+            out_tokens.numel() != B * (d_cap + 1):
+        raise ValueError("relaxed_accept: tensor sizes do not match B, T, d_cap")
+    _check(lib().sv_relaxed_accept(
+        C.byref(tree), _dev(draft_token, torch.int32, "draft_token"),
+        _dev(target_token, torch.int32, "target_token"), action_lo, n_bins, r, B, d_cap,
+        _dev(accept_mask, torch.uint8, "accept_mask"), _dev(accepted_len, torch.int32, "accepted_len"),
+        _dev(best_node, torch.int32, "best_node"), _dev(path, torch.int32, "path"),
+        _dev(out_tokens, torch.int32, "out_tokens"), _stream(stream)), "sv_relaxed_accept")
+
+
+# ---- holders that keep the device tensors behind the C structs alive -------------------
+
+class DeviceTree:
+    """B trees on the device: builds depth / masks with sv_tree_build_masks and uploads."""
+
+    def __init__(self, parent: np.ndarray, B: int, T: int, d_cap: int, device="cuda"):
+        parent = np.ascontiguousarray(parent, dtype=np.int32).reshape(-1)
+        depth, anc = sv_tree_build_masks(parent, B, T, d_cap)
+        self.B, self.T, self.d_cap = B, T, d_cap
+        self.host_parent, self.host_depth, self.host_anc = parent, depth, anc
+        self.parent = torch.from_numpy(parent).to(device)
+        self.depth = torch.from_numpy(depth).to(device)
+        self.anc = torch.from_numpy(anc.view(np.int64)).to(device)
+        self.struct = Tree(self.parent.data_ptr(), self.depth.data_ptr(), self.anc.data_ptr(),
+                           T, (T + 63) // 64)
+
+
+class KvCache:
+    """KV cache of one layer, [B, n_heads, capacity, head_dim], prefix rows filled by the caller."""
+
+    def __init__(self, cfg: ModelCfg, B: int, capacity: int, prefix_len: Sequence[int],
+                 device="cuda"):
+        dt = storage_dtype(cfg)
+        self.k = torch.zeros(B, cfg.n_heads, capacity, cfg.head_dim, dtype=dt, device=device)
+        self.v = torch.zeros_like(self.k)
+        pl = np.ascontiguousarray(prefix_len, dtype=np.int32)
+        self.prefix_len = torch.from_numpy(pl).to(device)
+        self.struct = KvView(self.k.data_ptr(), self.v.data_ptr(), self.prefix_len.data_ptr(),
+                             int(pl.max()), capacity)

@@ -1,0 +1,368 @@
+// C-ABI entry points of libspecvla_verify: argument checks, launch planning, launches.
+// No allocation, no global state, no synchronisation.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+
+#include "specvla_verify.h"
+#include "sv_accept.h"
+#include "sv_gemm_mfma.h"
+#include "sv_internal.h"
+#include "sv_kernels.h"
+
+namespace sv {
+
+static int check_cfg(const sv_model_cfg* c) {
+  if (!c) return SV_ERR_NULL;
+  if (c->dtype != SV_F32 && c->dtype != SV_BF16) return SV_ERR_DTYPE;
+  if (c->hidden < 1 || c->n_heads < 1 || c->head_dim < 2 || c->mlp_dim < 1 || c->vocab < 1)
+    return SV_ERR_SHAPE;
+  if ((c->head_dim & 1) || c->head_dim > 128) return SV_ERR_SHAPE;
+  if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return SV_ERR_SHAPE;
+  if (c->dtype == SV_BF16) {
+    const int D = c->n_heads * c->head_dim;
+    if (c->hidden % 128 || D % 128 || c->mlp_dim % 128) return SV_ERR_SHAPE;
+  }
+  return SV_OK;
+}
+
+static int pick_split(int n_rows, int k, int m_tiles) {
+  const int tiles = (n_rows / kWgRows) * m_tiles;
+  const int nblk = k / kBlkK;
+  int s = (512 + tiles / 2) / tiles;
+  if (s < 1) s = 1;
+  if (s > 16) s = 16;
+  if (s > nblk) s = nblk;
+  return s;
+}
+
+static SplitPlan split_plan(const sv_model_cfg& c, int m_rows) {
+  SplitPlan p = {1, 1, 1, 1};
+  if (c.dtype != SV_BF16) return p;
+  const int D = c.n_heads * c.head_dim, mt = ceil_div(m_rows, kMTile);
+  p.qkv = pick_split(3 * D, c.hidden, mt);
+  p.o = pick_split(c.hidden, D, mt);
+  p.gu = pick_split(2 * c.mlp_dim, c.hidden, mt);
+  p.down = pick_split(c.hidden, c.mlp_dim, mt);
+  return p;
+}
+
+static WorkspaceLayout workspace_layout(const sv_model_cfg& c, int m_rows, int n_scored) {
+  const size_t es = c.dtype == SV_F32 ? 4 : 2;
+  const size_t H = c.hidden, D = (size_t)c.n_heads * c.head_dim, F = c.mlp_dim;
+  WorkspaceLayout L;
+  L.m_pad = ceil_div(m_rows, kMTile) * kMTile;
+  const size_t mp = L.m_pad;
+  const SplitPlan sp = split_plan(c, m_rows);
+  size_t pf = (size_t)sp.qkv * 3 * D;
+  if ((size_t)sp.o * H > pf) pf = (size_t)sp.o * H;
+  if ((size_t)sp.gu * 2 * F > pf) pf = (size_t)sp.gu * 2 * F;
+  if ((size_t)sp.down * H > pf) pf = (size_t)sp.down * H;
+  L.part_floats = pf * mp;
+  size_t o = 0;
+  L.xhat = o;        o = align_up(o + mp * H * es, kAlign);
+  L.q = o;           o = align_up(o + mp * D * 4, kAlign);
+  L.attn = o;        o = align_up(o + mp * D * es, kAlign);
+  L.act = o;         o = align_up(o + mp * F * es, kAlign);
+  L.part = o;        o = align_up(o + L.part_floats * 4, kAlign);
+  L.head_z = o;      o = align_up(o + mp * H * es, kAlign);
+  L.head_logits = o; o = align_up(o + mp * (size_t)(n_scored > 0 ? n_scored : 0) * 4, kAlign);
+  L.total = o;
+  return L;
+}
+
+static inline int launch_status() { return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_LAUNCH; }
+
+// ---- per-dtype launch sequences ------------------------------------------------------
+
+template <typename T>
+static void gemm_any(const sv_model_cfg& c, const T* X, const void* W, float* part,
+                     size_t plane, int M, int N, int K, int split, hipStream_t st);
+
+template <>
+void gemm_any<float>(const sv_model_cfg&, const float* X, const void* W, float* part,
+                     size_t plane, int M, int N, int K, int split, hipStream_t st) {
+  dim3 grid(ceil_div(N, 64), ceil_div(M, 64), split);
+  gemm_nt_fma<float, float><<<grid, 256, 0, st>>>(X, K, (const float*)W, K, part, N, plane, M, N, K);
+}
+
+template <>
+void gemm_any<bf16_t>(const sv_model_cfg&, const bf16_t* X, const void* W, float* part,
+                      size_t plane, int M, int N, int K, int split, hipStream_t st) {
+  dim3 grid(N / kWgRows, split, ceil_div(M, kMTile));
+  gemm_skinny_bf16<<<grid, 256, 0, st>>>(X, M, (const uint4*)W, part, plane, N, K);
+}
+
+template <typename T>
+static int verify_layer_t(const sv_model_cfg& c, const char* packed, float* x,
+                          const sv_kv_view& kv, const sv_tree& tree, int B, char* ws,
+                          hipStream_t st, hipEvent_t* ev) {
+  const int T_ = tree.n_nodes, M = B * T_;
+  auto mark = [&](int i) {
+    if (ev) (void)hipEventRecord(ev[i], st);
+  };
+  const int H = c.hidden, D = c.n_heads * c.head_dim, F = c.mlp_dim;
+  const PackedLayout pl = packed_layout(c);
+  const WorkspaceLayout wl = workspace_layout(c, M, 0);
+  const SplitPlan sp = split_plan(c, M);
+  const float* g1 = (const float*)(packed + pl.g1);
+  const float* g2 = (const float*)(packed + pl.g2);
+  T* xhat = (T*)(ws + wl.xhat);
+  float* q = (float*)(ws + wl.q);
+  T* attn = (T*)(ws + wl.attn);
+  T* act = (T*)(ws + wl.act);
+  float* part = (float*)(ws + wl.part);
+  const size_t mp = wl.m_pad;
+
+  rmsnorm_rows<T><<<M, 256, 0, st>>>(x, g1, xhat, H, c.rms_eps);
+  mark(0);
+  gemm_any<T>(c, xhat, packed + pl.wqkv, part, mp * 3 * D, M, 3 * D, H, sp.qkv, st);
+  mark(1);
+  qkv_rope_append<T><<<M, 256, 0, st>>>(part, sp.qkv, mp * 3 * D, T_, c.n_heads, c.head_dim,
+                                        tree.depth, kv.prefix_len, kv.prefix_len_max,
+                                        kv.capacity, c.rope_theta, q, (T*)kv.k, (T*)kv.v);
+  mark(2);
+  tree_attention_rowwise<T, T><<<dim3(ceil_div(M, 4), c.n_heads), 256, 0, st>>>(
+      q, (const T*)kv.k, (const T*)kv.v, kv.prefix_len, kv.prefix_len_max, tree.anc_mask,
+      tree.n_words, T_, c.n_heads, c.head_dim, kv.capacity, attn, M);
+  mark(3);
+  gemm_any<T>(c, attn, packed + pl.wo, part, mp * H, M, H, D, sp.o, st);
+  mark(4);
+  residual_rmsnorm<T><<<M, 256, 0, st>>>(part, sp.o, mp * H, x, g2, xhat, H, c.rms_eps);
+  mark(5);
+  gemm_any<T>(c, xhat, packed + pl.wgu, part, mp * 2 * F, M, 2 * F, H, sp.gu, st);
+  mark(6);
+  swiglu_rows<T><<<dim3(ceil_div(F, 256), M), 256, 0, st>>>(part, sp.gu, mp * 2 * F, act, F);
+  mark(7);
+  gemm_any<T>(c, act, packed + pl.wd, part, mp * H, M, H, F, sp.down, st);
+  mark(8);
+  residual_rmsnorm<T><<<M, 256, 0, st>>>(part, sp.down, mp * H, x, nullptr, (T*)nullptr, H,
+                                         c.rms_eps);
+  return launch_status();
+}
+
+template <typename T>
+static int pack_layer_t(const sv_model_cfg& c, const sv_layer_weights& w, char* packed,
+                        hipStream_t st) {
+  const PackedLayout pl = packed_layout(c);
+  const int H = c.hidden, D = c.n_heads * c.head_dim, F = c.mlp_dim;
+  pack_gain<T><<<ceil_div(H, 256), 256, 0, st>>>((const T*)w.g1, (float*)(packed + pl.g1), H);
+  pack_gain<T><<<ceil_div(H, 256), 256, 0, st>>>((const T*)w.g2, (float*)(packed + pl.g2), H);
+  struct Piece { const void* src; size_t dst; int rows, k, row_off; };
+  const Piece pieces[] = {
+      {w.wq, pl.wqkv, D, H, 0},   {w.wk, pl.wqkv, D, H, D}, {w.wv, pl.wqkv, D, H, 2 * D},
+      {w.wo, pl.wo, H, D, 0},     {w.wg, pl.wgu, F, H, 0},  {w.wu, pl.wgu, F, H, F},
+      {w.wd, pl.wd, H, F, 0}};
+  for (const Piece& p : pieces) {
+    if (c.dtype == SV_F32) {
+      const size_t n = (size_t)p.rows * p.k;
+      pack_rows_plain<float><<<(unsigned)((n + 255) / 256), 256, 0, st>>>(
+          (const float*)p.src, (float*)(packed + p.dst), n, (size_t)p.row_off * p.k);
+    } else {
+      const size_t chunks = (size_t)p.rows * (p.k / 8);
+      pack_rows_mfma<<<(unsigned)((chunks + 255) / 256), 256, 0, st>>>(
+          (const uint4*)p.src, (uint4*)(packed + p.dst), p.rows, p.k, p.row_off);
+    }
+  }
+  return launch_status();
+}
+
+template <typename T>
+static int head_t(const sv_model_cfg& c, const T* g_final, const T* w_lm, const float* x,
+                  int n_rows, int lo, int hi, int32_t* out_token, float* out_logits, char* ws,
+                  hipStream_t st) {
+  const WorkspaceLayout wl = workspace_layout(c, n_rows, hi - lo);
+  const int H = c.hidden, n = hi - lo;
+  T* z = (T*)(ws + wl.head_z);
+  float* logits = out_logits ? out_logits : (float*)(ws + wl.head_logits);
+  rmsnorm_rows_tg<T, T><<<n_rows, 256, 0, st>>>(x, g_final, z, H, c.rms_eps);
+  dim3 grid(ceil_div(n, 64), ceil_div(n_rows, 64), 1);
+  gemm_nt_fma<T, T><<<grid, 256, 0, st>>>(z, H, w_lm + (size_t)lo * H, H, logits, n, 0, n_rows, n, H);
+  argmax_rows<<<n_rows, 64, 0, st>>>(logits, n, lo, out_token);
+  return launch_status();
+}
+
+}  // namespace sv
+
+using namespace sv;
+
+extern "C" {
+
+const char* sv_version(void) { return "libspecvla_verify 0.1 (gfx950)"; }
+
+const char* sv_strerror(int status) {
+  switch (status) {
+    case SV_OK: return "ok";
+    case SV_ERR_NULL: return "a required pointer is NULL";
+    case SV_ERR_SHAPE: return "unsupported size";
+    case SV_ERR_TREE: return "parent array is not a valid draft tree (or too deep)";
+    case SV_ERR_TOKEN: return "inconsistent action range or threshold";
+    case SV_ERR_WORKSPACE: return "workspace or packed buffer too small or misaligned";
+    case SV_ERR_DTYPE: return "unknown dtype";
+    case SV_ERR_LAUNCH: return "HIP launch error";
+    default: return "unknown status";
+  }
+}
+
+int sv_tree_build_masks(const int32_t* parent, int B, int T, int d_cap, int32_t* depth,
+                        uint64_t* anc_mask) {
+  if (!parent || !depth || !anc_mask) return SV_ERR_NULL;
+  if (B < 1 || T < 1 || T > SV_MAX_TREE_NODES || d_cap < 0 || d_cap > SV_MAX_DEPTH)
+    return SV_ERR_SHAPE;
+  const int W = (T + 63) / 64;
+  for (int b = 0; b < B; ++b) {
+    const int32_t* par = parent + (size_t)b * T;
+    int32_t* dep = depth + (size_t)b * T;
+    uint64_t* anc = anc_mask + (size_t)b * T * W;
+    if (par[0] != -1) return SV_ERR_TREE;
+    dep[0] = 0;
+    for (int w = 0; w < W; ++w) anc[w] = 0;
+    anc[0] = 1;
+    for (int i = 1; i < T; ++i) {
+      const int p = par[i];
+      if (p < 0 || p >= i) return SV_ERR_TREE;
+      dep[i] = dep[p] + 1;
+      if (dep[i] > d_cap) return SV_ERR_TREE;
+      for (int w = 0; w < W; ++w) anc[(size_t)i * W + w] = anc[(size_t)p * W + w];
+      anc[(size_t)i * W + (i >> 6)] |= 1ull << (i & 63);
+    }
+  }
+  return SV_OK;
+}
+
+int sv_packed_layer_bytes(const sv_model_cfg* cfg, size_t* bytes) {
+  if (!bytes) return SV_ERR_NULL;
+  const int rc = check_cfg(cfg);
+  if (rc != SV_OK) return rc;
+  *bytes = packed_layout(*cfg).total;
+  return SV_OK;
+}
+
+int sv_pack_layer(const sv_model_cfg* cfg, const sv_layer_weights* raw, void* packed,
+                  size_t packed_bytes, void* stream) {
+  const int rc = check_cfg(cfg);
+  if (rc != SV_OK) return rc;
+  if (!raw || !packed || !raw->g1 || !raw->wq || !raw->wk || !raw->wv || !raw->wo || !raw->g2 ||
+      !raw->wg || !raw->wu || !raw->wd)
+    return SV_ERR_NULL;
+  if (packed_bytes < packed_layout(*cfg).total || ((uintptr_t)packed % kAlign))
+    return SV_ERR_WORKSPACE;
+  if (cfg->dtype == SV_F32) return pack_layer_t<float>(*cfg, *raw, (char*)packed, (hipStream_t)stream);
+  return pack_layer_t<bf16_t>(*cfg, *raw, (char*)packed, (hipStream_t)stream);
+}
+
+int sv_workspace_bytes(const sv_model_cfg* cfg, int B, int T, int n_scored, size_t* bytes) {
+  if (!bytes) return SV_ERR_NULL;
+  const int rc = check_cfg(cfg);
+  if (rc != SV_OK) return rc;
+  if (B < 1 || T < 1 || T > SV_MAX_TREE_NODES || n_scored < 0 || n_scored > cfg->vocab ||
+      (long long)B * T > (1 << 15))
+    return SV_ERR_SHAPE;
+  *bytes = workspace_layout(*cfg, B * T, n_scored).total;
+  return SV_OK;
+}
+
+int sv_workspace_region(const sv_model_cfg* cfg, int B, int T, int n_scored, int which,
+                        size_t* offset, size_t* bytes) {
+  if (!offset || !bytes) return SV_ERR_NULL;
+  size_t total;
+  const int rc = sv_workspace_bytes(cfg, B, T, n_scored, &total);
+  if (rc != SV_OK) return rc;
+  const WorkspaceLayout wl = workspace_layout(*cfg, B * T, n_scored);
+  const size_t es = cfg->dtype == SV_F32 ? 4 : 2;
+  const size_t D = (size_t)cfg->n_heads * cfg->head_dim, M = (size_t)B * T;
+  if (which == SV_WS_ATTN_OUT) {
+    *offset = wl.attn;
+    *bytes = M * D * es;
+  } else if (which == SV_WS_Q) {
+    *offset = wl.q;
+    *bytes = M * D * 4;
+  } else {
+    return SV_ERR_SHAPE;
+  }
+  return SV_OK;
+}
+
+static int verify_layer_checked(const sv_model_cfg* cfg, const void* packed, float* x,
+                                const sv_kv_view* kv, const sv_tree* tree, int B,
+                                void* workspace, size_t ws_bytes, void* stream,
+                                hipEvent_t* ev) {
+  const int rc = check_cfg(cfg);
+  if (rc != SV_OK) return rc;
+  if (!packed || !x || !kv || !tree || !workspace || !kv->k || !kv->v || !kv->prefix_len ||
+      !tree->parent || !tree->depth || !tree->anc_mask)
+    return SV_ERR_NULL;
+  const int T = tree->n_nodes;
+  if (B < 1 || T < 1 || T > SV_MAX_TREE_NODES || tree->n_words != (T + 63) / 64 ||
+      (long long)B * T > (1 << 15))
+    return SV_ERR_SHAPE;
+  if (kv->prefix_len_max < 0 || (long long)kv->capacity < (long long)kv->prefix_len_max + T)
+    return SV_ERR_SHAPE;
+  if (((uintptr_t)workspace % kAlign) || ((uintptr_t)packed % kAlign) ||
+      ws_bytes < workspace_layout(*cfg, B * T, 0).total)
+    return SV_ERR_WORKSPACE;
+  if (cfg->dtype == SV_F32)
+    return verify_layer_t<float>(*cfg, (const char*)packed, x, *kv, *tree, B, (char*)workspace,
+                                 (hipStream_t)stream, ev);
+  return verify_layer_t<bf16_t>(*cfg, (const char*)packed, x, *kv, *tree, B, (char*)workspace,
+                                (hipStream_t)stream, ev);
+}
+
+int sv_verify_layer(const sv_model_cfg* cfg, const void* packed, float* x, const sv_kv_view* kv,
+                    const sv_tree* tree, int B, void* workspace, size_t ws_bytes, void* stream) {
+  return verify_layer_checked(cfg, packed, x, kv, tree, B, workspace, ws_bytes, stream, nullptr);
+}
+
+int sv_verify_layer_timed(const sv_model_cfg* cfg, const void* packed, float* x,
+                          const sv_kv_view* kv, const sv_tree* tree, int B, void* workspace,
+                          size_t ws_bytes, void* stream, void* const* events) {
+  if (!events) return SV_ERR_NULL;
+  hipEvent_t ev[SV_N_TIMING_EVENTS];
+  for (int i = 0; i < SV_N_TIMING_EVENTS; ++i) {
+    if (!events[i]) return SV_ERR_NULL;
+    ev[i] = (hipEvent_t)events[i];
+  }
+  return verify_layer_checked(cfg, packed, x, kv, tree, B, workspace, ws_bytes, stream, ev);
+}
+
+int sv_action_head_argmax(const sv_model_cfg* cfg, const void* g_final, const void* w_lm,
+                          const float* x, int n_rows, int vocab_lo, int vocab_hi,
+                          int32_t* out_token, float* out_logits, void* workspace,
+                          size_t ws_bytes, void* stream) {
+  const int rc = check_cfg(cfg);
+  if (rc != SV_OK) return rc;
+  if (!g_final || !w_lm || !x || !out_token || !workspace) return SV_ERR_NULL;
+  if (n_rows < 1 || n_rows > (1 << 15) || vocab_lo < 0 || vocab_lo >= vocab_hi ||
+      vocab_hi > cfg->vocab)
+    return SV_ERR_SHAPE;
+  if (((uintptr_t)workspace % kAlign) ||
+      ws_bytes < workspace_layout(*cfg, n_rows, vocab_hi - vocab_lo).total)
+    return SV_ERR_WORKSPACE;
+  if (cfg->dtype == SV_F32)
+    return head_t<float>(*cfg, (const float*)g_final, (const float*)w_lm, x, n_rows, vocab_lo,
+                         vocab_hi, out_token, out_logits, (char*)workspace, (hipStream_t)stream);
+  return head_t<bf16_t>(*cfg, (const bf16_t*)g_final, (const bf16_t*)w_lm, x, n_rows, vocab_lo,
+                        vocab_hi, out_token, out_logits, (char*)workspace, (hipStream_t)stream);
+}
+
+int sv_relaxed_accept(const sv_tree* tree, const int32_t* draft_token,
+                      const int32_t* target_token, int action_lo, int n_bins, int r, int B,
+                      int d_cap, uint8_t* accept_mask, int32_t* accepted_len,
+                      int32_t* best_node, int32_t* path, int32_t* out_tokens, void* stream) {
+  if (!tree || !tree->parent || !tree->depth || !tree->anc_mask || !draft_token ||
+      !target_token || !accept_mask || !accepted_len || !best_node || !path || !out_tokens)
+    return SV_ERR_NULL;
+  const int T = tree->n_nodes;
+  if (B < 1 || B > (1 << 15) || T < 1 || T > SV_MAX_TREE_NODES ||
+      tree->n_words != (T + 63) / 64 || d_cap < 0 || d_cap > SV_MAX_DEPTH)
+    return SV_ERR_SHAPE;
+  if (n_bins < 1 || r < 0 || action_lo < 0) return SV_ERR_TOKEN;
+  relaxed_accept_kernel<<<B, 128, 0, (hipStream_t)stream>>>(
+      tree->parent, tree->depth, tree->anc_mask, T, tree->n_words, draft_token, target_token,
+      action_lo, n_bins, r, d_cap, accept_mask, accepted_len, best_node, path, out_tokens);
+  return launch_status();
+}
+
+}  // extern "C"

@@ -1,0 +1,110 @@
+"""Sequencing of one verification step through the C-ABI calls (no arithmetic here).
+
+`VerifyPass` owns the device buffers of one model + one batch of episodes and issues, per
+step,  n_layers x sv_verify_layer -> sv_action_head_argmax -> sv_relaxed_accept  on the
+current stream.  Used by the tests, the smoke check and the benchmark.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import binding as sv
+from .workload import VerifyConfig
+
+
+class VerifyPass:
+    def __init__(self, wc: VerifyConfig, prefix_len: Sequence[int], parent: np.ndarray,
+                 full_vocab: bool = False, device: str = "cuda"):
+        if not torch.cuda.is_available():
+            raise RuntimeError("VerifyPass needs a GPU; there is no CPU path")
+        self.wc = wc
+        self.device = device
+        self.cfg = sv.model_cfg(wc.dtype, wc.hidden, wc.n_heads, wc.head_dim, wc.mlp_dim,
+                                wc.vocab, wc.rms_eps, wc.rope_theta)
+        self.B, self.T = wc.n_episodes, wc.tree_nodes
+        self.M = self.B * self.T
+        self.d_cap = wc.max_depth
+        self.vocab_lo = 0 if full_vocab else wc.action_lo
+        self.vocab_hi = wc.vocab
+        self.n_scored = self.vocab_hi - self.vocab_lo
+        self.tree = sv.DeviceTree(parent, self.B, self.T, self.d_cap, device)
+        pl = np.asarray(prefix_len, dtype=np.int32)
+        self.capacity = int(-(-(int(pl.max()) + self.T) // 64) * 64)
+        self.kv = [sv.KvCache(self.cfg, self.B, self.capacity, pl, device)
+                   for _ in range(wc.n_layers)]
+        self.packed: List[Optional[torch.Tensor]] = [None] * wc.n_layers
+        self.packed_bytes = sv.sv_packed_layer_bytes(self.cfg)
+        self.ws_bytes = sv.sv_workspace_bytes(self.cfg, self.B, self.T, self.n_scored)
+        self.workspace = torch.zeros(self.ws_bytes, dtype=torch.uint8, device=device)
+        dt = sv.storage_dtype(self.cfg)
+        self.g_final = torch.ones(wc.hidden, dtype=dt, device=device)
+        self.w_lm = torch.zeros(wc.vocab, wc.hidden, dtype=dt, device=device)
+        self.x0 = torch.zeros(self.M, wc.hidden, dtype=torch.float32, device=device)
+        self.x = torch.zeros_like(self.x0)
+        self.draft = torch.zeros(self.M, dtype=torch.int32, device=device)
+        self.token = torch.zeros(self.M, dtype=torch.int32, device=device)
+        self.logits = torch.zeros(self.M, self.n_scored, dtype=torch.float32, device=device)
+        self.accept_mask = torch.zeros(self.M, dtype=torch.uint8, device=device)
+        self.accepted_len = torch.zeros(self.B, dtype=torch.int32, device=device)
+        self.best_node = torch.zeros(self.B, dtype=torch.int32, device=device)
+        self.path = torch.zeros(self.B, self.d_cap + 1, dtype=torch.int32, device=device)
+        self.out_tokens = torch.zeros(self.B, self.d_cap + 1, dtype=torch.int32, device=device)
+
+    # ---- loading -------------------------------------------------------------------
+    def load_layer(self, layer: int, raw: Dict[str, torch.Tensor]) -> None:
+        """Upload the nine tensors of a layer, pack them, drop the raw copies."""
+        dev = {k: v.to(self.device).contiguous() for k, v in raw.items()}
+        packed = torch.empty(self.packed_bytes, dtype=torch.uint8, device=self.device)
+        sv.sv_pack_layer(self.cfg, dev, packed)
+        torch.cuda.current_stream().synchronize()
+        self.packed[layer] = packed
+
+    def load_head(self, g_final: torch.Tensor, w_rows: torch.Tensor) -> None:
+        """w_rows: either the full [V, H] head or only the action rows [n_bins, H]."""
+        self.g_final.copy_(g_final)
+        if w_rows.shape[0] == self.wc.vocab:
+            self.w_lm.copy_(w_rows)
+        else:
+            self.w_lm[self.wc.action_lo:].copy_(w_rows)
+
+    def load_prefix(self, layer: int, episode: int, k: torch.Tensor, v: torch.Tensor) -> None:
+        P = k.shape[1]
+        self.kv[layer].k[episode, :, :P].copy_(k)
+        self.kv[layer].v[episode, :, :P].copy_(v)
+
+    def set_hidden(self, x: torch.Tensor) -> None:
+        """x: [B*T, H] in the storage dtype or float32; widened to the float32 stream."""
+        self.x0.copy_(x.reshape(self.M, -1).to(torch.float32))
+
+    def set_draft(self, draft: np.ndarray) -> None:
+        self.draft.copy_(torch.from_numpy(np.ascontiguousarray(draft, dtype=np.int32).reshape(-1)))
+
+    # ---- one step ------------------------------------------------------------------
+    def forward(self, n_layers: Optional[int] = None, want_logits: bool = True) -> None:
+        self.x.copy_(self.x0)
+        for l in range(self.wc.n_layers if n_layers is None else n_layers):
+            sv.sv_verify_layer(self.cfg, self.packed[l], self.x, self.kv[l].struct,
+                               self.tree.struct, self.B, self.workspace)
+        sv.sv_action_head_argmax(self.cfg, self.g_final, self.w_lm, self.x, self.M, self.vocab_lo,
+                                 self.vocab_hi, self.token, self.logits if want_logits else None,
+                                 self.workspace)
+
+    def accept(self, r: int, target: Optional[torch.Tensor] = None) -> None:
+        sv.sv_relaxed_accept(self.tree.struct, self.draft, self.token if target is None else target,
+                             self.wc.action_lo, self.wc.n_bins, r, self.B, self.d_cap,
+                             self.accept_mask, self.accepted_len, self.best_node, self.path,
+                             self.out_tokens)
+
+    def step(self, r: int, want_logits: bool = False) -> None:
+        self.forward(want_logits=want_logits)
+        self.accept(r)
+
+    def workspace_view(self, which: int) -> torch.Tensor:
+        off, nb = sv.sv_workspace_region(self.cfg, self.B, self.T, self.n_scored, which)
+        raw = self.workspace[off:off + nb]
+        D = self.wc.n_heads * self.wc.head_dim
+        dt = torch.float32 if which == sv.SV_WS_Q else sv.storage_dtype(self.cfg)
+        return raw.view(dt).reshape(self.M, D)

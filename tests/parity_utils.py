@@ -1,0 +1,136 @@
+"""Runs the HIP path and the CPU oracle side by side on the same seeded inputs.
+
+Both sides are fed layer by layer from paper_2507_22424_amd.workload (so a 13 GB model never
+has to sit in host memory twice); the oracle gets the stored values widened to float64.
+Error measure (per node row): max_k |gpu - ref| / max_k |ref|.
+"""
+import sys
+import time
+
+import numpy as np
+import torch
+
+from oracle import verify_oracle as vo
+from paper_2507_22424_amd import binding as sv
+from paper_2507_22424_amd import workload as wl
+from paper_2507_22424_amd.runner import VerifyPass
+
+
+def say(msg):
+    """Progress line that bypasses pytest's capture (long GPU tests must not look hung)."""
+    print(msg, file=sys.__stderr__, flush=True)
+
+
+def f64(t):
+    return t.to(torch.float64).numpy()
+
+
+def row_rel_err(gpu, ref):
+    gpu = np.asarray(gpu, dtype=np.float64)
+    num = np.max(np.abs(gpu - ref), axis=-1)
+    den = np.max(np.abs(ref), axis=-1)
+    return num / den
+
+
+class SideBySide:
+    """Outputs of one configuration from both sides."""
+
+    def __init__(self, cfg, n_layers=None, full_vocab=False, per_layer=True, tag=""):
+        L = cfg.n_layers if n_layers is None else n_layers
+        self.cfg = cfg = cfg.scaled(n_layers=L)
+        B, T = cfg.n_episodes, cfg.tree_nodes
+        self.prefix_len = wl.prefix_lengths(cfg)
+        self.parents = [wl.episode_tree(cfg, b) for b in range(B)]
+        self.gpu = VerifyPass(cfg, self.prefix_len, np.concatenate(self.parents),
+                              full_vocab=full_vocab)
+        hidden = [wl.hidden_rows(cfg, b) for b in range(B)]
+        self.gpu.set_hidden(torch.cat(hidden))
+        self.gpu.x.copy_(self.gpu.x0)
+        x_ref = [f64(h) for h in hidden]
+        self.attn_err, self.x_err = [], []
+        t0 = time.time()
+        for l in range(L):
+            w = wl.layer_weights(cfg, l)
+            self.gpu.load_layer(l, w)
+            w64 = {k: f64(v) for k, v in w.items()}
+            del w
+            ref_attn = []
+            for b in range(B):
+                P = int(self.prefix_len[b])
+                kp, vp = wl.prefix_kv(cfg, b, l, P)
+                self.gpu.load_prefix(l, b, kp, vp)
+                out = vo.verify_layer(x_ref[b], w64, f64(kp), f64(vp), self.parents[b],
+                                      cfg.n_heads, cfg.rms_eps, cfg.rope_theta)
+                x_ref[b] = out["x"]
+                ref_attn.append(out["attn"])
+            if per_layer:
+                sv.sv_verify_layer(self.gpu.cfg, self.gpu.packed[l], self.gpu.x,
+                                   self.gpu.kv[l].struct, self.gpu.tree.struct, B,
+                                   self.gpu.workspace)
+                torch.cuda.synchronize()
+                attn = self.gpu.workspace_view(sv.SV_WS_ATTN_OUT).float().cpu().numpy()
+                self.attn_err.append(row_rel_err(attn, np.concatenate(ref_attn)).max())
+                self.x_err.append(row_rel_err(self.gpu.x.cpu().numpy(),
+                                              np.concatenate(x_ref)).max())
+            say(f"[{tag or cfg.name}] layer {l + 1}/{L} done, {time.time() - t0:.0f}s"
+                + (f", attn err {self.attn_err[-1]:.2e}, x err {self.x_err[-1]:.2e}"
+                   if per_layer else ""))
+        head = wl.head_weights(cfg, full_vocab=full_vocab)
+        self.gpu.load_head(head["g_final"], head["w_lm"])
+        self.ref_x = np.concatenate(x_ref)
+        lo = 0 if full_vocab else cfg.action_lo
+        self.ref_logits, self.ref_token = vo.action_head(self.ref_x, f64(head["g_final"]),
+                                                         f64(head["w_lm"]), lo, cfg.rms_eps)
+        # the whole pass again, in one go, the way the benchmark issues it
+        self.gpu.forward(want_logits=True)
+        torch.cuda.synchronize()
+        self.gpu_logits = self.gpu.logits.cpu().numpy()
+        self.gpu_token = self.gpu.token.cpu().numpy()
+        self.gpu_x = self.gpu.x.cpu().numpy()
+        self.logit_err = row_rel_err(self.gpu_logits, self.ref_logits)
+
+    def tolerated_ties(self, tol):
+        """Nodes whose GPU token differs from the oracle's: (n tolerated, n not tolerated).
+        A difference is tolerated when the oracle's own logits of the two candidates are
+        closer than 2 * tol * max |logit| of that node."""
+        lo = self.gpu.vocab_lo
+        ok = bad = 0
+        for i in np.flatnonzero(self.gpu_token != self.ref_token):
+            row = self.ref_logits[i]
+            gap = row[self.ref_token[i] - lo] - row[self.gpu_token[i] - lo]
+            if gap <= 2 * tol * np.max(np.abs(row)):
+                ok += 1
+            else:
+                bad += 1
+        return ok, bad
+
+    def check_gpu_argmax_of_own_logits(self):
+        """The integer decision: the GPU token is the first maximum of the GPU's own logits."""
+        lo = self.gpu.vocab_lo
+        assert np.array_equal(self.gpu_token, lo + np.argmax(self.gpu_logits, axis=-1))
+
+    def accept_both(self, r, draft, target):
+        """sv_relaxed_accept on given target tokens vs the oracle; returns both results."""
+        cfg, B, T = self.cfg, self.cfg.n_episodes, self.cfg.tree_nodes
+        self.gpu.set_draft(draft)
+        tgt = torch.from_numpy(np.ascontiguousarray(target, dtype=np.int32)).cuda()
+        self.gpu.accept(r, tgt)
+        torch.cuda.synchronize()
+        g = {"mask": self.gpu.accept_mask.cpu().numpy().reshape(B, T),
+             "length": self.gpu.accepted_len.cpu().numpy(),
+             "best": self.gpu.best_node.cpu().numpy(),
+             "path": self.gpu.path.cpu().numpy(), "tokens": self.gpu.out_tokens.cpu().numpy()}
+        refs = [vo.relaxed_accept(self.parents[b], draft[b * T:(b + 1) * T],
+                                  target[b * T:(b + 1) * T], cfg.action_lo, cfg.n_bins, r)
+                for b in range(B)]
+        return g, refs
+
+
+def assert_accept_equal(g, refs, d_cap):
+    for b, ref in enumerate(refs):
+        assert g["mask"][b].astype(bool).tolist() == ref["mask"].tolist()
+        assert int(g["length"][b]) == ref["length"]
+        assert int(g["best"][b]) == ref["best"]
+        pad = [-1] * (d_cap + 1)
+        assert g["path"][b].tolist() == (ref["path"] + pad)[:d_cap + 1]
+        assert g["tokens"][b].tolist() == (ref["tokens"] + pad)[:d_cap + 1]

@@ -1,0 +1,165 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, on an MI355X.
+
+Bars: integer work (acceptance masks, lengths, paths, tokens; argmax of given logits) is
+bit-exact; attention output and logits are within 1e-5 (float32 model) / 2e-2 (bf16 model) of
+the oracle per node row (max |diff| / max |ref|); tokens may differ from the oracle's only
+at near-ties of the oracle's own logits, which are counted and reported.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import verify_oracle as vo
+from paper_2507_22424_amd import binding as sv
+from paper_2507_22424_amd import workload as wl
+
+from parity_utils import SideBySide, assert_accept_equal, say
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def check_forward(s, tol, tie_frac_cap=0.25):
+    name = s.cfg.name
+    if s.attn_err:
+        say(f"[{name}] max attn err {max(s.attn_err):.3e}, max x err {max(s.x_err):.3e}, "
+            f"logit err {s.logit_err.max():.3e}")
+        assert max(s.attn_err) <= tol
+        assert max(s.x_err) <= tol
+    assert s.logit_err.max() <= tol
+    s.check_gpu_argmax_of_own_logits()
+    ok, bad = s.tolerated_ties(tol)
+    say(f"[{name}] tokens differing from the oracle: {ok} tolerated near-ties, {bad} others, "
+        f"of {len(s.ref_token)} nodes")
+    assert bad == 0
+    assert ok <= tie_frac_cap * len(s.ref_token)
+    return ok
+
+
+def check_accept_paths(s, r_values, spread=8):
+    """(1) bit-exact acceptance on oracle-supplied target tokens; (2) end to end on the GPU's
+    own tokens: identical lengths unless a differing token (a counted near-tie) is involved."""
+    cfg, B, T = s.cfg, s.cfg.n_episodes, s.cfg.tree_nodes
+    draft = np.concatenate([
+        wl.noisy_draft_tokens(cfg, b, s.parents[b], s.ref_token[b * T:(b + 1) * T], spread)
+        for b in range(B)])
+    for r in r_values:
+        g, refs = s.accept_both(r, draft, s.ref_token)
+        assert_accept_equal(g, refs, cfg.max_depth)
+        g2, _ = s.accept_both(r, draft, s.gpu_token)
+        for b in range(B):
+            same_tokens = np.array_equal(s.gpu_token[b * T:(b + 1) * T],
+                                         s.ref_token[b * T:(b + 1) * T])
+            if same_tokens:
+                assert int(g2["length"][b]) == refs[b]["length"]
+                assert g2["tokens"][b].tolist() == g["tokens"][b].tolist()
+        say(f"[{cfg.name}] r={r}: accepted lengths {g['length'].tolist()}")
+
+
+# ---- acceptance alone (integer path) ------------------------------------------------------
+
+@pytest.mark.parametrize("B,T,dmax,kids", [(1, 1, 7, 3), (1, 15, 7, 3), (16, 60, 7, 4),
+                                           (5, 64, 7, 4), (3, 65, 9, 5), (7, 128, 7, 6)])
+def test_relaxed_accept_bit_exact(B, T, dmax, kids):
+    rng = np.random.default_rng(1000 * B + T)
+    lo, nb = 31744, 256
+    parents = [wl.draft_tree(T, dmax, kids, min(dmax, T - 1), rng) for _ in range(B)]
+    tree = sv.DeviceTree(np.concatenate(parents), B, T, dmax)
+    out = dict(mask=torch.zeros(B * T, dtype=torch.uint8, device="cuda"),
+               length=torch.zeros(B, dtype=torch.int32, device="cuda"),
+               best=torch.zeros(B, dtype=torch.int32, device="cuda"),
+               path=torch.zeros(B, dmax + 1, dtype=torch.int32, device="cuda"),
+               tokens=torch.zeros(B, dmax + 1, dtype=torch.int32, device="cuda"))
+    for trial in range(6):
+        target = lo + rng.integers(0, nb, size=B * T)
+        spread = [0, 1, 3, 8, 8, 300][trial]
+        draft = np.empty(B * T, dtype=np.int64)
+        for b in range(B):
+            for c in range(T):
+                p = max(int(parents[b][c]), 0)
+                draft[b * T + c] = target[b * T + p] + rng.integers(-spread, spread + 1)
+        if trial == 4:                       # sprinkle tokens outside the action range
+            bad = rng.random(B * T) < 0.1
+            draft[bad] = rng.integers(0, lo, size=bad.sum())
+            target[rng.random(B * T) < 0.05] = lo + nb + 3
+        d_t = torch.from_numpy(draft.astype(np.int32)).cuda()
+        t_t = torch.from_numpy(target.astype(np.int32)).cuda()
+        for r in (0, 1, 4, 8, 255):
+            sv.sv_relaxed_accept(tree.struct, d_t, t_t, lo, nb, r, B, dmax, out["mask"],
+                                 out["length"], out["best"], out["path"], out["tokens"])
+            torch.cuda.synchronize()
+            g = {k: v.cpu().numpy() for k, v in out.items()}
+            g["mask"] = g["mask"].reshape(B, T)
+            refs = [vo.relaxed_accept(parents[b], draft[b * T:(b + 1) * T],
+                                      target[b * T:(b + 1) * T], lo, nb, r) for b in range(B)]
+            assert_accept_equal(g, refs, dmax)
+
+
+# ---- configuration 1: tiny float32 model, 1e-5 ---------------------------------------------
+
+def test_c1_tiny_f32_layer_head_accept():
+    s = SideBySide(wl.C1)
+    check_forward(s, TOL["f32"], tie_frac_cap=0.0 + 1.0 / 15)
+    cfg, T = s.cfg, s.cfg.tree_nodes
+    # config 1 draws draft ids uniformly over the action tokens
+    draft = wl.uniform_draft_tokens(cfg, 0)
+    for r in cfg.r_values + (40, 255):
+        g, refs = s.accept_both(r, draft, s.ref_token)
+        assert_accept_equal(g, refs, cfg.max_depth)
+    check_accept_paths(s, cfg.r_values)
+
+
+@pytest.mark.parametrize("T,B,P", [(1, 1, 64), (70, 2, 33), (128, 1, 200)])
+def test_f32_odd_shapes(T, B, P):
+    """Root-only tree, a 140-row batch (three 64-row tiles with a ragged tail), two mask words."""
+    cfg = wl.C1.scaled(name=f"f32-T{T}-B{B}", index=10 + B, n_layers=2, tree_nodes=T,
+                       n_episodes=B, prefix_lo=max(1, P - 9), prefix_hi=P, max_children=4,
+                       spine_lo=min(3, max(T - 1, 0)))
+    s = SideBySide(cfg)
+    check_forward(s, TOL["f32"], tie_frac_cap=0.1)
+    check_accept_paths(s, (0, 3))
+
+
+# ---- bf16, small model: several tiles, ragged prefixes, 2e-2 -------------------------------
+
+@pytest.mark.parametrize("T,B,P", [(26, 3, 90), (60, 1, 280), (128, 1, 300), (70, 2, 40)])
+def test_bf16_small_model(T, B, P):
+    cfg = wl.C2.scaled(name=f"bf16-small-T{T}-B{B}", index=20 + B, n_layers=3, hidden=512,
+                       n_heads=4, head_dim=128, mlp_dim=1408, vocab=1024, n_bins=256,
+                       tree_nodes=T, n_episodes=B, prefix_lo=max(1, P - 50), prefix_hi=P,
+                       max_children=6, r_values=(0, 4))
+    s = SideBySide(cfg)
+    check_forward(s, TOL["bf16"])
+    check_accept_paths(s, (0, 4, 8))
+
+
+# ---- configuration 2: one 7B-shaped layer, bf16 ------------------------------------------
+
+def test_c2_one_7b_layer_bf16():
+    s = SideBySide(wl.C2.scaled(vocab=32000))
+    assert max(s.attn_err) <= TOL["bf16"] and max(s.x_err) <= TOL["bf16"]
+    say(f"[C2] attn err {max(s.attn_err):.3e}, x err {max(s.x_err):.3e}")
+
+
+# ---- configurations 4 and 5 at full width, a few layers deep --------------------------------
+
+def test_c4_batched_ragged_two_layers():
+    s = SideBySide(wl.C4, n_layers=2)
+    check_forward(s, TOL["bf16"])
+    check_accept_paths(s, wl.C4.r_values)
+
+
+def test_c5_long_prefix_two_layers():
+    s = SideBySide(wl.C5, n_layers=2)
+    check_forward(s, TOL["bf16"])
+    check_accept_paths(s, wl.C5.r_values)
+
+
+# ---- configuration 3: the full 32-layer pass the benchmark times ----------------------------
+
+def test_c3_full_pass_32_layers():
+    s = SideBySide(wl.C3)
+    n_ties = check_forward(s, TOL["bf16"])
+    check_accept_paths(s, wl.C3.r_values)
+    say(f"[C3] tolerated argmax near-ties: {n_ties} of {len(s.ref_token)} nodes")

@@ -1,0 +1,112 @@
+"""Host-side logic of the C-ABI library (no GPU needed): the library loads, exports every
+symbol the header declares, derives tree depths / masks like the oracle does, and turns bad
+arguments into status codes before anything would be launched."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import verify_oracle as vo
+from paper_2507_22424_amd import binding as sv
+from paper_2507_22424_amd import workload as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "specvla_verify.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(sv_[a-z_]+)\s*\(", header))
+    assert declared == set(sv.EXPORTS)
+    lib = sv.lib()
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert "gfx950" in sv.sv_version()
+    assert sv.sv_strerror(0) == "ok" and "tree" in sv.sv_strerror(-3)
+
+
+def test_tree_masks_match_the_oracle_derivation():
+    rng = np.random.default_rng(0)
+    for T, dmax, kids in [(1, 7, 3), (15, 7, 3), (60, 7, 4), (64, 7, 4), (65, 9, 5), (128, 7, 6)]:
+        B = 3
+        parents = np.concatenate([wl.draft_tree(T, dmax, kids, min(dmax, T - 1), rng)
+                                  for _ in range(B)])
+        depth, anc = sv.sv_tree_build_masks(parents, B, T, dmax)
+        W = (T + 63) // 64
+        anc = anc.reshape(B, T, W)
+        for b in range(B):
+            d_ref, a_ref = vo.tree_structure(parents[b * T:(b + 1) * T])
+            assert depth[b * T:(b + 1) * T].tolist() == d_ref.tolist()
+            for i in range(T):
+                bits = [(int(anc[b, i, j // 64]) >> (j % 64)) & 1 for j in range(T)]
+                assert bits == a_ref[i].astype(int).tolist()
+
+
+@pytest.mark.parametrize("parent", [[0, 0], [-1, 1], [-1, -1], [-1, 0, 3, 1], [-1, 0, 2]])
+def test_bad_trees_are_rejected(parent):
+    with pytest.raises(sv.SvError) as e:
+        sv.sv_tree_build_masks(np.array(parent), 1, len(parent), 7)
+    assert e.value.status == -3
+
+
+def test_depth_cap_and_size_limits():
+    chain = np.arange(-1, 9)
+    with pytest.raises(sv.SvError) as e:
+        sv.sv_tree_build_masks(chain, 1, 10, 7)
+    assert e.value.status == -3
+    sv.sv_tree_build_masks(chain, 1, 10, 9)
+    with pytest.raises(sv.SvError) as e:
+        sv.sv_tree_build_masks(np.arange(-1, 128), 1, 129, 31)
+    assert e.value.status == -2
+
+
+def test_sizes_and_cfg_checks():
+    c7 = sv.model_cfg("bf16", 4096, 32, 128, 11008, 32000)
+    nbytes = sv.sv_packed_layer_bytes(c7)
+    weights = (4 * 4096 * 4096 + 3 * 4096 * 11008) * 2
+    assert weights <= nbytes <= weights + 2 * 4096 * 4 + 8 * 256
+    assert sv.sv_workspace_bytes(c7, 1, 60, 256) > 64 * 22016 * 4
+    assert sv.sv_workspace_bytes(c7, 16, 60, 256) > sv.sv_workspace_bytes(c7, 1, 60, 256)
+    off, nb = sv.sv_workspace_region(c7, 1, 60, 256, sv.SV_WS_ATTN_OUT)
+    assert off % 256 == 0 and nb == 60 * 4096 * 2
+    for bad, status in [(sv.model_cfg(5, 256, 4, 64, 688, 512), -6),
+                        (sv.model_cfg("bf16", 4000, 32, 128, 11008, 32000), -2),
+                        (sv.model_cfg("f32", 256, 4, 63, 688, 512), -2),
+                        (sv.model_cfg("f32", 256, 4, 256, 688, 512), -2)]:
+        with pytest.raises(sv.SvError) as e:
+            sv.sv_packed_layer_bytes(bad)
+        assert e.value.status == status
+    with pytest.raises(sv.SvError) as e:
+        sv.sv_workspace_bytes(c7, 1, 129, 256)
+    assert e.value.status == -2
+
+
+def test_null_and_range_arguments_fail_before_any_launch():
+    lib = sv.lib()
+    c1 = sv.model_cfg("f32", 256, 4, 64, 688, 512)
+    assert lib.sv_verify_layer(C.byref(c1), None, None, None, None, 1, None, 0, None) == -1
+    assert lib.sv_action_head_argmax(C.byref(c1), None, None, None, 1, 256, 512, None, None,
+                                     None, 0, None) == -1
+    assert lib.sv_pack_layer(C.byref(c1), None, None, 0, None) == -1
+    assert lib.sv_relaxed_accept(None, None, None, 0, 256, 0, 1, 7, None, None, None, None,
+                                 None, None) == -1
+    # non-null dummies (never dereferenced on the host): range errors come first
+    one = C.c_void_p(256)
+    tree = sv.Tree(256, 256, 256, 15, 1)
+    args = (one, one, one, one, one, None)
+    assert lib.sv_relaxed_accept(C.byref(tree), one, one, 256, 256, -1, 1, 7, *args) == -4
+    assert lib.sv_relaxed_accept(C.byref(tree), one, one, 256, 0, 0, 1, 7, *args) == -4
+    assert lib.sv_relaxed_accept(C.byref(tree), one, one, 256, 256, 0, 0, 7, *args) == -2
+    assert lib.sv_relaxed_accept(C.byref(tree), one, one, 256, 256, 0, 1, 40, *args) == -2
+    bad_tree = sv.Tree(256, 256, 256, 15, 2)
+    assert lib.sv_relaxed_accept(C.byref(bad_tree), one, one, 256, 256, 0, 1, 7, *args) == -2
+    kv = sv.KvView(256, 256, 256, 64, 70)          # capacity < prefix + T
+    assert lib.sv_verify_layer(C.byref(c1), one, one, C.byref(kv), C.byref(tree), 1, one,
+                               1 << 30, None) == -2
+    kv = sv.KvView(256, 256, 256, 64, 128)
+    assert lib.sv_verify_layer(C.byref(c1), one, one, C.byref(kv), C.byref(tree), 1, one,
+                               16, None) == -5     # workspace too small
+    assert lib.sv_action_head_argmax(C.byref(c1), one, one, one, 15, 300, 200, one, None, one,
+                                     1 << 30, None) == -2
