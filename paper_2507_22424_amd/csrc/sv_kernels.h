@@ -207,6 +207,8 @@ __global__ __launch_bounds__(256) void tree_attention_rowwise(
   for (int j = 0; j < P; ++j) visit(j);
   for (int w = 0; w < n_words; ++w) {
     uint64_t bits = anc[(size_t)m * n_words + w];
+    const int valid = T - w * 64;             // bits at or above T name no node: ignore them
+    if (valid < 64) bits &= valid > 0 ? ((1ull << valid) - 1ull) : 0ull;
     while (bits) {
       const int j = __ffsll((unsigned long long)bits) - 1;
       bits &= bits - 1;

@@ -4,6 +4,7 @@ Both sides are fed layer by layer from paper_2507_22424_amd.workload (so a 13 GB
 has to sit in host memory twice); the oracle gets the stored values widened to float64.
 Error measure (per node row): max_k |gpu - ref| / max_k |ref|.
 """
+import os
 import sys
 import time
 
@@ -16,9 +17,20 @@ from paper_2507_22424_amd import workload as wl
 from paper_2507_22424_amd.runner import VerifyPass
 
 
+_ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
 def say(msg):
-    """Progress line that bypasses pytest's capture (long GPU tests must not look hung)."""
-    print(msg, file=sys.__stderr__, flush=True)
+    """Progress / result line: printed (visible with `pytest -s`) and appended to
+    gpurun_out/parity.log, so that a long GPU test shows signs of life and leaves its
+    measured errors behind even when pytest captures the output."""
+    print(msg, flush=True)
+    try:
+        os.makedirs(os.path.join(_ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(_ROOT, "gpurun_out", "parity.log"), "a") as f:
+            f.write(msg + "\n")
+    except OSError:
+        pass
 
 
 def f64(t):
