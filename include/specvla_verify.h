@@ -124,10 +124,16 @@ int sv_pack_layer(const sv_model_cfg *cfg, const sv_layer_weights *raw, void *pa
  * B episodes of T nodes and up to n_scored scored vocabulary rows -> *bytes. */
 int sv_workspace_bytes(const sv_model_cfg *cfg, int B, int T, int n_scored, size_t *bytes);
 
+/* Prepares a freshly allocated (or otherwise dirty) workspace: zeroes the inter-workgroup
+ * arrival counters at its start with a small kernel on `stream`.  Call once after allocating
+ * the workspace and before its first use; every later call of the library leaves the counters
+ * zero again.  workspace: [device], 256-byte aligned, ws_bytes >= sv_workspace_bytes(...). */
+int sv_workspace_init(const sv_model_cfg *cfg, int B, int T, int n_scored, void *workspace,
+                      size_t ws_bytes, void *stream);
+
 /* Host-only inspection aid for tests: where an intermediate of the last sv_verify_layer call
  * lives inside the workspace.  which = SV_WS_ATTN_OUT: attention output before the output
- * projection, [B*T, nh*d], cfg->dtype elements.  which = SV_WS_Q: rotated queries, float32
- * [B*T, nh*d]. */
+ * projection, float32 [B*T, nh*d].  which = SV_WS_Q: rotated queries, float32 [B*T, nh*d]. */
 #define SV_WS_ATTN_OUT 0
 #define SV_WS_Q 1
 int sv_workspace_region(const sv_model_cfg *cfg, int B, int T, int n_scored, int which,
@@ -140,7 +146,8 @@ int sv_workspace_region(const sv_model_cfg *cfg, int B, int T, int n_scored, int
  *   packed:    [device] from sv_pack_layer (same cfg)
  *   x:         [device] float32 [B*T, H], residual stream, updated in place
  *   kv, tree:  [host] structs of [device] pointers, see above; tree->n_nodes = T
- *   workspace: [device], 256-byte aligned, ws_bytes >= sv_workspace_bytes(cfg, B, T, *)
+ *   workspace: [device], 256-byte aligned, ws_bytes >= sv_workspace_bytes(cfg, B, T, *),
+ *              prepared once with sv_workspace_init; calls sharing a workspace must not overlap
  * SV_ERR_SHAPE if B < 1, T outside 1..SV_MAX_TREE_NODES, capacity < prefix_len_max + T, or
  * cfg sizes are unsupported for the dtype (see sv_pack_layer). */
 int sv_verify_layer(const sv_model_cfg *cfg, const void *packed, float *x,

@@ -21,7 +21,8 @@ SV_MAX_DEPTH = 31
 SV_WS_ATTN_OUT, SV_WS_Q = 0, 1
 
 EXPORTS = ("sv_version", "sv_strerror", "sv_tree_build_masks", "sv_packed_layer_bytes",
-           "sv_pack_layer", "sv_workspace_bytes", "sv_workspace_region", "sv_verify_layer",
+           "sv_pack_layer", "sv_workspace_bytes", "sv_workspace_init", "sv_workspace_region",
+           "sv_verify_layer",
            "sv_verify_layer_timed", "sv_action_head_argmax", "sv_relaxed_accept")
 SV_N_TIMING_EVENTS = 9
 
@@ -72,6 +73,8 @@ def lib() -> C.CDLL:
                                     C.c_size_t, C.c_void_p]
         l.sv_workspace_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int, C.c_int, C.c_int,
                                          C.POINTER(C.c_size_t)]
+        l.sv_workspace_init.argtypes = [C.POINTER(ModelCfg), C.c_int, C.c_int, C.c_int, C.c_void_p,
+                                        C.c_size_t, C.c_void_p]
         l.sv_workspace_region.argtypes = [C.POINTER(ModelCfg), C.c_int, C.c_int, C.c_int, C.c_int,
                                           C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
         l.sv_verify_layer.argtypes = [C.POINTER(ModelCfg), C.c_void_p, C.c_void_p,
@@ -163,6 +166,13 @@ def sv_workspace_bytes(cfg: ModelCfg, B: int, T: int, n_scored: int) -> int:
     _check(lib().sv_workspace_bytes(C.byref(cfg), B, T, n_scored, C.byref(out)),
            "sv_workspace_bytes")
     return out.value
+
+
+def sv_workspace_init(cfg: ModelCfg, B: int, T: int, n_scored: int, workspace: torch.Tensor,
+                      stream=None) -> None:
+    _check(lib().sv_workspace_init(C.byref(cfg), B, T, n_scored,
+                                   _dev(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                   _stream(stream)), "sv_workspace_init")
 
 
 def sv_workspace_region(cfg: ModelCfg, B: int, T: int, n_scored: int, which: int

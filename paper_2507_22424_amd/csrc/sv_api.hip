@@ -22,19 +22,21 @@ static int check_cfg(const sv_model_cfg* c) {
   if ((c->head_dim & 1) || c->head_dim > 128) return SV_ERR_SHAPE;
   if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return SV_ERR_SHAPE;
   if (c->dtype == SV_BF16) {
-    const int D = c->n_heads * c->head_dim;
-    if (c->hidden % 128 || D % 128 || c->mlp_dim % 128) return SV_ERR_SHAPE;
+    if (c->hidden % 128 || c->head_dim != 128 || c->mlp_dim % 128) return SV_ERR_SHAPE;
   }
   return SV_OK;
 }
 
+// Number of K slices of a GEMM with `n_rows` weight rows: enough workgroups to fill the chip
+// about twice, but never slices thinner than two 128-wide K blocks (each slice costs a
+// partial tile of traffic).
 static int pick_split(int n_rows, int k, int m_tiles) {
   const int tiles = (n_rows / kWgRows) * m_tiles;
   const int nblk = k / kBlkK;
   int s = (512 + tiles / 2) / tiles;
+  if (s > nblk / 2) s = nblk / 2;
+  if (s > 8) s = 8;
   if (s < 1) s = 1;
-  if (s > 16) s = 16;
-  if (s > nblk) s = nblk;
   return s;
 }
 
@@ -50,24 +52,37 @@ static SplitPlan split_plan(const sv_model_cfg& c, int m_rows) {
 }
 
 static WorkspaceLayout workspace_layout(const sv_model_cfg& c, int m_rows, int n_scored) {
-  const size_t es = c.dtype == SV_F32 ? 4 : 2;
   const size_t H = c.hidden, D = (size_t)c.n_heads * c.head_dim, F = c.mlp_dim;
   WorkspaceLayout L;
-  L.m_pad = ceil_div(m_rows, kMTile) * kMTile;
-  const size_t mp = L.m_pad;
+  L.m_tiles = ceil_div(m_rows, kMTile);
+  L.m_pad = L.m_tiles * kMTile;
+  const size_t mp = L.m_pad, mt = L.m_tiles;
   const SplitPlan sp = split_plan(c, m_rows);
-  size_t pf = (size_t)sp.qkv * 3 * D;
-  if ((size_t)sp.o * H > pf) pf = (size_t)sp.o * H;
-  if ((size_t)sp.gu * 2 * F > pf) pf = (size_t)sp.gu * 2 * F;
-  if ((size_t)sp.down * H > pf) pf = (size_t)sp.down * H;
-  L.part_floats = pf * mp;
+  size_t n_max = 3 * D;
+  if (2 * F > n_max) n_max = 2 * F;
+  if (H > n_max) n_max = H;
   size_t o = 0;
-  L.xhat = o;        o = align_up(o + mp * H * es, kAlign);
+  if (c.dtype == SV_BF16) {
+    // units = (row group, K slice) pairs of the largest GEMM
+    size_t units = (3 * D / kWgRows) * sp.qkv;
+    if ((H / kWgRows) * sp.o > units) units = (H / kWgRows) * sp.o;
+    if ((2 * F / kWgRows) * sp.gu > units) units = (2 * F / kWgRows) * sp.gu;
+    if ((H / kWgRows) * sp.down > units) units = (H / kWgRows) * sp.down;
+    L.counter_bytes = align_up(mt * (n_max / kWgRows) * sizeof(int), kAlign);
+    L.counters = o; o += L.counter_bytes;
+    L.sumsq = o;    o = align_up(o + mt * units * kMTile * 4, kAlign);
+    L.part = o;     o = align_up(o + mt * units * kTileFloats * 4, kAlign);
+    L.xhat = o;
+  } else {
+    L.counter_bytes = 0;
+    L.counters = L.sumsq = o;
+    L.part = o;     o = align_up(o + mp * n_max * 4, kAlign);
+    L.xhat = o;     o = align_up(o + mp * H * 4, kAlign);
+  }
   L.q = o;           o = align_up(o + mp * D * 4, kAlign);
-  L.attn = o;        o = align_up(o + mp * D * es, kAlign);
-  L.act = o;         o = align_up(o + mp * F * es, kAlign);
-  L.part = o;        o = align_up(o + L.part_floats * 4, kAlign);
-  L.head_z = o;      o = align_up(o + mp * H * es, kAlign);
+  L.attn = o;        o = align_up(o + mp * D * 4, kAlign);
+  L.act = o;         o = align_up(o + mp * F * 4, kAlign);
+  L.head_z = o;      o = align_up(o + mp * H * 4, kAlign);
   L.head_logits = o; o = align_up(o + mp * (size_t)(n_scored > 0 ? n_scored : 0) * 4, kAlign);
   L.total = o;
   return L;
@@ -75,30 +90,67 @@ static WorkspaceLayout workspace_layout(const sv_model_cfg& c, int m_rows, int n
 
 static inline int launch_status() { return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_LAUNCH; }
 
-// ---- per-dtype launch sequences ------------------------------------------------------
-
-template <typename T>
-static void gemm_any(const sv_model_cfg& c, const T* X, const void* W, float* part,
-                     size_t plane, int M, int N, int K, int split, hipStream_t st);
-
-template <>
-void gemm_any<float>(const sv_model_cfg&, const float* X, const void* W, float* part,
-                     size_t plane, int M, int N, int K, int split, hipStream_t st) {
-  dim3 grid(ceil_div(N, 64), ceil_div(M, 64), split);
-  gemm_nt_fma<float, float><<<grid, 256, 0, st>>>(X, K, (const float*)W, K, part, N, plane, M, N, K);
+__global__ void zero_ints(int* p, size_t n) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
 }
 
-template <>
-void gemm_any<bf16_t>(const sv_model_cfg&, const bf16_t* X, const void* W, float* part,
-                      size_t plane, int M, int N, int K, int split, hipStream_t st) {
-  dim3 grid(N / kWgRows, split, ceil_div(M, kMTile));
-  gemm_skinny_bf16<<<grid, 256, 0, st>>>(X, M, (const uint4*)W, part, plane, N, K);
+// ---- float32 models: plain kernels, one launch per step of the layer ----------------------
+
+static int verify_layer_f32(const sv_model_cfg& c, const char* packed, float* x,
+                            const sv_kv_view& kv, const sv_tree& tree, int B, char* ws,
+                            hipStream_t st, hipEvent_t* ev) {
+  const int T_ = tree.n_nodes, M = B * T_;
+  auto mark = [&](int i) {
+    if (ev) (void)hipEventRecord(ev[i], st);
+  };
+  const int H = c.hidden, D = c.n_heads * c.head_dim, F = c.mlp_dim;
+  const PackedLayout pl = packed_layout(c);
+  const WorkspaceLayout wl = workspace_layout(c, M, 0);
+  const float* g1 = (const float*)(packed + pl.g1);
+  const float* g2 = (const float*)(packed + pl.g2);
+  float* xhat = (float*)(ws + wl.xhat);
+  float* q = (float*)(ws + wl.q);
+  float* attn = (float*)(ws + wl.attn);
+  float* act = (float*)(ws + wl.act);
+  float* part = (float*)(ws + wl.part);
+  auto gemm = [&](const float* X, size_t w_off, int N, int K) {
+    dim3 grid(ceil_div(N, 64), ceil_div(M, 64), 1);
+    gemm_nt_fma<float, float><<<grid, 256, 0, st>>>(X, K, (const float*)(packed + w_off), K, part,
+                                                    N, 0, M, N, K);
+  };
+  rmsnorm_rows<float><<<M, 256, 0, st>>>(x, g1, xhat, H, c.rms_eps);
+  mark(0);
+  gemm(xhat, pl.wqkv, 3 * D, H);
+  mark(1);
+  qkv_rope_append<float><<<M, 256, 0, st>>>(part, 1, 0, T_, c.n_heads, c.head_dim, tree.depth,
+                                            kv.prefix_len, kv.prefix_len_max, kv.capacity,
+                                            c.rope_theta, q, (float*)kv.k, (float*)kv.v);
+  mark(2);
+  tree_attention_rowwise<float, float><<<dim3(ceil_div(M, 4), c.n_heads), 256, 0, st>>>(
+      q, (const float*)kv.k, (const float*)kv.v, kv.prefix_len, kv.prefix_len_max, tree.anc_mask,
+      tree.n_words, T_, c.n_heads, c.head_dim, kv.capacity, attn, M);
+  mark(3);
+  gemm(attn, pl.wo, H, D);
+  mark(4);
+  residual_rmsnorm<float><<<M, 256, 0, st>>>(part, 1, 0, x, g2, xhat, H, c.rms_eps);
+  mark(5);
+  gemm(xhat, pl.wgu, 2 * F, H);
+  mark(6);
+  swiglu_rows<float><<<dim3(ceil_div(F, 256), M), 256, 0, st>>>(part, 1, 0, act, F);
+  mark(7);
+  gemm(act, pl.wd, H, F);
+  mark(8);
+  residual_rmsnorm<float><<<M, 256, 0, st>>>(part, 1, 0, x, nullptr, (float*)nullptr, H,
+                                             c.rms_eps);
+  return launch_status();
 }
 
-template <typename T>
-static int verify_layer_t(const sv_model_cfg& c, const char* packed, float* x,
-                          const sv_kv_view& kv, const sv_tree& tree, int B, char* ws,
-                          hipStream_t st, hipEvent_t* ev) {
+// ---- bf16 models: five launches per layer ---------------------------------------------------
+
+static int verify_layer_bf16(const sv_model_cfg& c, const char* packed, float* x,
+                             const sv_kv_view& kv, const sv_tree& tree, int B, char* ws,
+                             hipStream_t st, hipEvent_t* ev) {
   const int T_ = tree.n_nodes, M = B * T_;
   auto mark = [&](int i) {
     if (ev) (void)hipEventRecord(ev[i], st);
@@ -107,39 +159,47 @@ static int verify_layer_t(const sv_model_cfg& c, const char* packed, float* x,
   const PackedLayout pl = packed_layout(c);
   const WorkspaceLayout wl = workspace_layout(c, M, 0);
   const SplitPlan sp = split_plan(c, M);
-  const float* g1 = (const float*)(packed + pl.g1);
-  const float* g2 = (const float*)(packed + pl.g2);
-  T* xhat = (T*)(ws + wl.xhat);
+  GemmArgs a;
+  memset(&a, 0, sizeof(a));
+  a.M = M;
+  a.part = (float*)(ws + wl.part);
+  a.sumsq = (float*)(ws + wl.sumsq);
+  a.counters = (int*)(ws + wl.counters);
+  a.eps = c.rms_eps;
   float* q = (float*)(ws + wl.q);
-  T* attn = (T*)(ws + wl.attn);
-  T* act = (T*)(ws + wl.act);
-  float* part = (float*)(ws + wl.part);
-  const size_t mp = wl.m_pad;
+  float* attn = (float*)(ws + wl.attn);
+  float* act = (float*)(ws + wl.act);
+  auto grid_of = [&](int N, int S) {
+    return dim3(8 * ceil_div(N / kWgRows, 8) * S, wl.m_tiles, 1);
+  };
 
-  rmsnorm_rows<T><<<M, 256, 0, st>>>(x, g1, xhat, H, c.rms_eps);
+  a.X = x; a.gain = (const float*)(packed + pl.g1); a.Wp = (const uint4*)(packed + pl.wqkv);
+  a.N = 3 * D; a.K = H; a.S = sp.qkv;
+  a.q_out = q; a.kc = (bf16_t*)kv.k; a.vc = (bf16_t*)kv.v; a.depth = tree.depth;
+  a.prefix_len = kv.prefix_len; a.p_max = kv.prefix_len_max; a.cap = kv.capacity; a.T = T_;
+  a.nh = c.n_heads; a.theta = c.rope_theta;
   mark(0);
-  gemm_any<T>(c, xhat, packed + pl.wqkv, part, mp * 3 * D, M, 3 * D, H, sp.qkv, st);
+  gemm_fused_bf16<PRO_GAIN, EPI_QKV><<<grid_of(a.N, a.S), 256, 0, st>>>(a);
   mark(1);
-  qkv_rope_append<T><<<M, 256, 0, st>>>(part, sp.qkv, mp * 3 * D, T_, c.n_heads, c.head_dim,
-                                        tree.depth, kv.prefix_len, kv.prefix_len_max,
-                                        kv.capacity, c.rope_theta, q, (T*)kv.k, (T*)kv.v);
   mark(2);
-  tree_attention_rowwise<T, T><<<dim3(ceil_div(M, 4), c.n_heads), 256, 0, st>>>(
-      q, (const T*)kv.k, (const T*)kv.v, kv.prefix_len, kv.prefix_len_max, tree.anc_mask,
-      tree.n_words, T_, c.n_heads, c.head_dim, kv.capacity, attn, M);
+  tree_attention_rowwise<bf16_t, float><<<dim3(ceil_div(M, 4), c.n_heads), 256, 0, st>>>(
+      q, (const bf16_t*)kv.k, (const bf16_t*)kv.v, kv.prefix_len, kv.prefix_len_max,
+      tree.anc_mask, tree.n_words, T_, c.n_heads, c.head_dim, kv.capacity, attn, M);
   mark(3);
-  gemm_any<T>(c, attn, packed + pl.wo, part, mp * H, M, H, D, sp.o, st);
+  a.X = attn; a.gain = nullptr; a.Wp = (const uint4*)(packed + pl.wo);
+  a.N = H; a.K = D; a.S = sp.o; a.x_io = x;
+  gemm_fused_bf16<PRO_PLAIN, EPI_RESID><<<grid_of(a.N, a.S), 256, 0, st>>>(a);
   mark(4);
-  residual_rmsnorm<T><<<M, 256, 0, st>>>(part, sp.o, mp * H, x, g2, xhat, H, c.rms_eps);
+  a.X = x; a.gain = (const float*)(packed + pl.g2); a.Wp = (const uint4*)(packed + pl.wgu);
+  a.N = 2 * F; a.K = H; a.S = sp.gu; a.act = act;
   mark(5);
-  gemm_any<T>(c, xhat, packed + pl.wgu, part, mp * 2 * F, M, 2 * F, H, sp.gu, st);
+  gemm_fused_bf16<PRO_GAIN, EPI_SWIGLU><<<grid_of(a.N, a.S), 256, 0, st>>>(a);
   mark(6);
-  swiglu_rows<T><<<dim3(ceil_div(F, 256), M), 256, 0, st>>>(part, sp.gu, mp * 2 * F, act, F);
+  a.X = act; a.gain = nullptr; a.Wp = (const uint4*)(packed + pl.wd);
+  a.N = H; a.K = F; a.S = sp.down; a.x_io = x;
   mark(7);
-  gemm_any<T>(c, act, packed + pl.wd, part, mp * H, M, H, F, sp.down, st);
+  gemm_fused_bf16<PRO_PLAIN, EPI_RESID><<<grid_of(a.N, a.S), 256, 0, st>>>(a);
   mark(8);
-  residual_rmsnorm<T><<<M, 256, 0, st>>>(part, sp.down, mp * H, x, nullptr, (T*)nullptr, H,
-                                         c.rms_eps);
   return launch_status();
 }
 
@@ -150,20 +210,28 @@ static int pack_layer_t(const sv_model_cfg& c, const sv_layer_weights& w, char* 
   const int H = c.hidden, D = c.n_heads * c.head_dim, F = c.mlp_dim;
   pack_gain<T><<<ceil_div(H, 256), 256, 0, st>>>((const T*)w.g1, (float*)(packed + pl.g1), H);
   pack_gain<T><<<ceil_div(H, 256), 256, 0, st>>>((const T*)w.g2, (float*)(packed + pl.g2), H);
-  struct Piece { const void* src; size_t dst; int rows, k, row_off; };
+  // float32: q|k|v and gate|up stacked, row-major.  bf16: fragment order; gate and up
+  // interleaved in blocks of 64 rows so that one 128-row tile holds both for 64 columns.
+  struct Piece {
+    const void* src; size_t dst; int rows, k;
+    int plain_off;                 // float32: first destination row
+    int group, stride, row_off;    // bf16: see pack_rows_mfma
+  };
   const Piece pieces[] = {
-      {w.wq, pl.wqkv, D, H, 0},   {w.wk, pl.wqkv, D, H, D}, {w.wv, pl.wqkv, D, H, 2 * D},
-      {w.wo, pl.wo, H, D, 0},     {w.wg, pl.wgu, F, H, 0},  {w.wu, pl.wgu, F, H, F},
-      {w.wd, pl.wd, H, F, 0}};
+      {w.wq, pl.wqkv, D, H, 0, D, 0, 0},      {w.wk, pl.wqkv, D, H, D, D, 0, D},
+      {w.wv, pl.wqkv, D, H, 2 * D, D, 0, 2 * D}, {w.wo, pl.wo, H, D, 0, H, 0, 0},
+      {w.wg, pl.wgu, F, H, 0, 64, 128, 0},    {w.wu, pl.wgu, F, H, F, 64, 128, 64},
+      {w.wd, pl.wd, H, F, 0, H, 0, 0}};
   for (const Piece& p : pieces) {
     if (c.dtype == SV_F32) {
       const size_t n = (size_t)p.rows * p.k;
       pack_rows_plain<float><<<(unsigned)((n + 255) / 256), 256, 0, st>>>(
-          (const float*)p.src, (float*)(packed + p.dst), n, (size_t)p.row_off * p.k);
+          (const float*)p.src, (float*)(packed + p.dst), n, (size_t)p.plain_off * p.k);
     } else {
       const size_t chunks = (size_t)p.rows * (p.k / 8);
       pack_rows_mfma<<<(unsigned)((chunks + 255) / 256), 256, 0, st>>>(
-          (const uint4*)p.src, (uint4*)(packed + p.dst), p.rows, p.k, p.row_off);
+          (const uint4*)p.src, (uint4*)(packed + p.dst), p.rows, p.k, p.group, p.stride,
+          p.row_off);
     }
   }
   return launch_status();
@@ -175,11 +243,11 @@ static int head_t(const sv_model_cfg& c, const T* g_final, const T* w_lm, const 
                   hipStream_t st) {
   const WorkspaceLayout wl = workspace_layout(c, n_rows, hi - lo);
   const int H = c.hidden, n = hi - lo;
-  T* z = (T*)(ws + wl.head_z);
+  float* z = (float*)(ws + wl.head_z);
   float* logits = out_logits ? out_logits : (float*)(ws + wl.head_logits);
-  rmsnorm_rows_tg<T, T><<<n_rows, 256, 0, st>>>(x, g_final, z, H, c.rms_eps);
+  rmsnorm_rows_tg<T, float><<<n_rows, 256, 0, st>>>(x, g_final, z, H, c.rms_eps);
   dim3 grid(ceil_div(n, 64), ceil_div(n_rows, 64), 1);
-  gemm_nt_fma<T, T><<<grid, 256, 0, st>>>(z, H, w_lm + (size_t)lo * H, H, logits, n, 0, n_rows, n, H);
+  gemm_nt_fma<float, T><<<grid, 256, 0, st>>>(z, H, w_lm + (size_t)lo * H, H, logits, n, 0, n_rows, n, H);
   argmax_rows<<<n_rows, 64, 0, st>>>(logits, n, lo, out_token);
   return launch_status();
 }
@@ -264,6 +332,21 @@ int sv_workspace_bytes(const sv_model_cfg* cfg, int B, int T, int n_scored, size
   return SV_OK;
 }
 
+int sv_workspace_init(const sv_model_cfg* cfg, int B, int T, int n_scored, void* workspace,
+                      size_t ws_bytes, void* stream) {
+  size_t total;
+  const int rc = sv_workspace_bytes(cfg, B, T, n_scored, &total);
+  if (rc != SV_OK) return rc;
+  if (!workspace) return SV_ERR_NULL;
+  if (((uintptr_t)workspace % kAlign) || ws_bytes < total) return SV_ERR_WORKSPACE;
+  const WorkspaceLayout wl = workspace_layout(*cfg, B * T, n_scored);
+  const size_t n = wl.counter_bytes / sizeof(int);
+  if (n > 0)
+    zero_ints<<<(unsigned)((n + 255) / 256), 256, 0, (hipStream_t)stream>>>(
+        (int*)((char*)workspace + wl.counters), n);
+  return launch_status();
+}
+
 int sv_workspace_region(const sv_model_cfg* cfg, int B, int T, int n_scored, int which,
                         size_t* offset, size_t* bytes) {
   if (!offset || !bytes) return SV_ERR_NULL;
@@ -271,11 +354,10 @@ int sv_workspace_region(const sv_model_cfg* cfg, int B, int T, int n_scored, int
   const int rc = sv_workspace_bytes(cfg, B, T, n_scored, &total);
   if (rc != SV_OK) return rc;
   const WorkspaceLayout wl = workspace_layout(*cfg, B * T, n_scored);
-  const size_t es = cfg->dtype == SV_F32 ? 4 : 2;
   const size_t D = (size_t)cfg->n_heads * cfg->head_dim, M = (size_t)B * T;
   if (which == SV_WS_ATTN_OUT) {
     *offset = wl.attn;
-    *bytes = M * D * es;
+    *bytes = M * D * 4;
   } else if (which == SV_WS_Q) {
     *offset = wl.q;
     *bytes = M * D * 4;
@@ -304,10 +386,10 @@ static int verify_layer_checked(const sv_model_cfg* cfg, const void* packed, flo
       ws_bytes < workspace_layout(*cfg, B * T, 0).total)
     return SV_ERR_WORKSPACE;
   if (cfg->dtype == SV_F32)
-    return verify_layer_t<float>(*cfg, (const char*)packed, x, *kv, *tree, B, (char*)workspace,
-                                 (hipStream_t)stream, ev);
-  return verify_layer_t<bf16_t>(*cfg, (const char*)packed, x, *kv, *tree, B, (char*)workspace,
-                                (hipStream_t)stream, ev);
+    return verify_layer_f32(*cfg, (const char*)packed, x, *kv, *tree, B, (char*)workspace,
+                            (hipStream_t)stream, ev);
+  return verify_layer_bf16(*cfg, (const char*)packed, x, *kv, *tree, B, (char*)workspace,
+                           (hipStream_t)stream, ev);
 }
 
 int sv_verify_layer(const sv_model_cfg* cfg, const void* packed, float* x, const sv_kv_view* kv,

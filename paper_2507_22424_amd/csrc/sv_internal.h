@@ -95,11 +95,12 @@ struct SplitPlan {
   int qkv, o, gu, down;
 };
 
-// Device scratch of one call (bytes from the start of the workspace).
+// Device scratch of one call (bytes from the start of the workspace).  Activations are
+// float32 for both storage types.
 struct WorkspaceLayout {
-  size_t xhat, q, attn, act, part, head_z, head_logits, total;
-  int m_pad;
-  size_t part_floats;
+  size_t counters, sumsq, part, xhat, q, attn, act, head_z, head_logits, total;
+  size_t counter_bytes;
+  int m_pad, m_tiles;
 };
 
 }  // namespace sv

@@ -38,7 +38,8 @@ class VerifyPass:
         self.packed: List[Optional[torch.Tensor]] = [None] * wc.n_layers
         self.packed_bytes = sv.sv_packed_layer_bytes(self.cfg)
         self.ws_bytes = sv.sv_workspace_bytes(self.cfg, self.B, self.T, self.n_scored)
-        self.workspace = torch.zeros(self.ws_bytes, dtype=torch.uint8, device=device)
+        self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device=device)
+        sv.sv_workspace_init(self.cfg, self.B, self.T, self.n_scored, self.workspace)
         dt = sv.storage_dtype(self.cfg)
         self.g_final = torch.ones(wc.hidden, dtype=dt, device=device)
         self.w_lm = torch.zeros(wc.vocab, wc.hidden, dtype=dt, device=device)
@@ -106,5 +107,4 @@ class VerifyPass:
         off, nb = sv.sv_workspace_region(self.cfg, self.B, self.T, self.n_scored, which)
         raw = self.workspace[off:off + nb]
         D = self.wc.n_heads * self.wc.head_dim
-        dt = torch.float32 if which == sv.SV_WS_Q else sv.storage_dtype(self.cfg)
-        return raw.view(dt).reshape(self.M, D)
+        return raw.view(torch.float32).reshape(self.M, D)

@@ -70,9 +70,10 @@ def test_sizes_and_cfg_checks():
     assert sv.sv_workspace_bytes(c7, 1, 60, 256) > 64 * 22016 * 4
     assert sv.sv_workspace_bytes(c7, 16, 60, 256) > sv.sv_workspace_bytes(c7, 1, 60, 256)
     off, nb = sv.sv_workspace_region(c7, 1, 60, 256, sv.SV_WS_ATTN_OUT)
-    assert off % 256 == 0 and nb == 60 * 4096 * 2
+    assert off % 256 == 0 and nb == 60 * 4096 * 4
     for bad, status in [(sv.model_cfg(5, 256, 4, 64, 688, 512), -6),
                         (sv.model_cfg("bf16", 4000, 32, 128, 11008, 32000), -2),
+                        (sv.model_cfg("bf16", 4096, 64, 64, 11008, 32000), -2),
                         (sv.model_cfg("f32", 256, 4, 63, 688, 512), -2),
                         (sv.model_cfg("f32", 256, 4, 256, 688, 512), -2)]:
         with pytest.raises(sv.SvError) as e:
