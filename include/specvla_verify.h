@@ -116,7 +116,8 @@ int sv_packed_layer_bytes(const sv_model_cfg *cfg, size_t *bytes);
  * float32).  raw: [host] struct of [device] pointers; packed: [device], 256-byte aligned,
  * packed_bytes >= sv_packed_layer_bytes.  The packed layout is private to the library and
  * may change between versions; raw tensors are not needed afterwards.
- * SV_BF16 needs H, nh*d, F multiples of 128 and d = 128; SV_F32 takes any sizes with d even. */
+ * SV_BF16 needs d = 128 and H, nh*d, F multiples of 256; SV_F32 takes any sizes with d even
+ * and d <= 128. */
 int sv_pack_layer(const sv_model_cfg *cfg, const sv_layer_weights *raw, void *packed,
                   size_t packed_bytes, void *stream);
 
@@ -133,9 +134,14 @@ int sv_workspace_init(const sv_model_cfg *cfg, int B, int T, int n_scored, void 
 
 /* Host-only inspection aid for tests: where an intermediate of the last sv_verify_layer call
  * lives inside the workspace.  which = SV_WS_ATTN_OUT: attention output before the output
- * projection, float32 [B*T, nh*d].  which = SV_WS_Q: rotated queries, float32 [B*T, nh*d]. */
+ * projection, float32 [B*T, nh*d].  which = SV_WS_Q: rotated queries, float32 [B*T, nh*d].
+ * which = SV_WS_STATUS: one int32 (bytes = 0 for SV_F32 models), zero unless a bf16 GEMM found
+ * the K slices of one output tile on different XCDs - the placement its cache-local reduction
+ * relies on and checks on every call; non-zero means results are suspect.  Cleared by
+ * sv_workspace_init. */
 #define SV_WS_ATTN_OUT 0
 #define SV_WS_Q 1
+#define SV_WS_STATUS 2
 int sv_workspace_region(const sv_model_cfg *cfg, int B, int T, int n_scored, int which,
                         size_t *offset, size_t *bytes);
 

@@ -18,7 +18,7 @@ from .build import LIB_PATH
 SV_F32, SV_BF16 = 0, 1
 SV_MAX_TREE_NODES = 128
 SV_MAX_DEPTH = 31
-SV_WS_ATTN_OUT, SV_WS_Q = 0, 1
+SV_WS_ATTN_OUT, SV_WS_Q, SV_WS_STATUS = 0, 1, 2
 
 EXPORTS = ("sv_version", "sv_strerror", "sv_tree_build_masks", "sv_packed_layer_bytes",
            "sv_pack_layer", "sv_workspace_bytes", "sv_workspace_init", "sv_workspace_region",

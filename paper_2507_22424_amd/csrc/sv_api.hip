@@ -22,33 +22,46 @@ static int check_cfg(const sv_model_cfg* c) {
   if ((c->head_dim & 1) || c->head_dim > 128) return SV_ERR_SHAPE;
   if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return SV_ERR_SHAPE;
   if (c->dtype == SV_BF16) {
-    if (c->hidden % 128 || c->head_dim != 128 || c->mlp_dim % 128) return SV_ERR_SHAPE;
+    if (c->hidden % 256 || c->head_dim != 128 || c->n_heads % 2 || c->mlp_dim % 256)
+      return SV_ERR_SHAPE;
   }
   return SV_OK;
 }
 
-// Number of K slices of a GEMM with `n_rows` weight rows: enough workgroups to fill the chip
-// about twice, but never slices thinner than two 128-wide K blocks (each slice costs a
-// partial tile of traffic).
-static int pick_split(int n_rows, int k, int m_tiles) {
-  const int tiles = (n_rows / kWgRows) * m_tiles;
-  const int nblk = k / kBlkK;
-  int s = (512 + tiles / 2) / tiles;
-  if (s > nblk / 2) s = nblk / 2;
-  if (s > 8) s = 8;
-  if (s < 1) s = 1;
-  return s;
+// Shape of the work split of one streaming GEMM (bf16 path): K slices and tile groups per XCD.
+// A slice should be about one LDS chunk (4 K blocks); slices longer than a chunk need at most
+// one tile per wave (4 per group) because the accumulators then stay in registers.
+struct GemmPlan {
+  int S, gpx;
+};
+
+static GemmPlan plan_gemm(int n_rows, int k, int n_xcd) {
+  const int npair = k / (2 * kBlkK);         // pieces of 256 k-values
+  const int tiles_per_xcd = ceil_div(n_rows / kFragRows, n_xcd);
+  GemmPlan p;
+  p.S = npair / 2;                           // about one LDS chunk (2 pieces) per slice
+  if (p.S > 8) p.S = 8;
+  if (p.S < 1) p.S = 1;
+  p.gpx = 32 / p.S;                          // aim at 32 units per XCD (one per CU)
+  if (p.gpx > tiles_per_xcd) p.gpx = tiles_per_xcd;
+  if (p.gpx < 1) p.gpx = 1;
+  // a slice that spans several LDS chunks keeps its accumulators in registers: one tile per wave
+  const int chunks = ceil_div(ceil_div(npair, p.S), 2);
+  if (chunks > 1 && ceil_div(tiles_per_xcd, p.gpx) > 4) p.gpx = ceil_div(tiles_per_xcd, 4);
+  return p;
 }
 
-static SplitPlan split_plan(const sv_model_cfg& c, int m_rows) {
-  SplitPlan p = {1, 1, 1, 1};
-  if (c.dtype != SV_BF16) return p;
-  const int D = c.n_heads * c.head_dim, mt = ceil_div(m_rows, kMTile);
-  p.qkv = pick_split(3 * D, c.hidden, mt);
-  p.o = pick_split(c.hidden, D, mt);
-  p.gu = pick_split(2 * c.mlp_dim, c.hidden, mt);
-  p.down = pick_split(c.hidden, c.mlp_dim, mt);
-  return p;
+static int device_xcds() {
+  static int cached[64] = {0};               // hardware facts only; a race rewrites the same value
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 1;
+  if (cached[dev] == 0) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 32;
+    int x = cus / 32;
+    cached[dev] = x < 1 ? 1 : (x > kXcds ? kXcds : x);
+  }
+  return cached[dev];
 }
 
 static WorkspaceLayout workspace_layout(const sv_model_cfg& c, int m_rows, int n_scored) {
@@ -57,21 +70,17 @@ static WorkspaceLayout workspace_layout(const sv_model_cfg& c, int m_rows, int n
   L.m_tiles = ceil_div(m_rows, kMTile);
   L.m_pad = L.m_tiles * kMTile;
   const size_t mp = L.m_pad, mt = L.m_tiles;
-  const SplitPlan sp = split_plan(c, m_rows);
   size_t n_max = 3 * D;
   if (2 * F > n_max) n_max = 2 * F;
   if (H > n_max) n_max = H;
   size_t o = 0;
   if (c.dtype == SV_BF16) {
-    // units = (row group, K slice) pairs of the largest GEMM
-    size_t units = (3 * D / kWgRows) * sp.qkv;
-    if ((H / kWgRows) * sp.o > units) units = (H / kWgRows) * sp.o;
-    if ((2 * F / kWgRows) * sp.gu > units) units = (2 * F / kWgRows) * sp.gu;
-    if ((H / kWgRows) * sp.down > units) units = (H / kWgRows) * sp.down;
-    L.counter_bytes = align_up(mt * (n_max / kWgRows) * sizeof(int), kAlign);
+    // sized for the worst split (8 slices), independent of the device
+    const size_t tiles_max = n_max / kFragRows, s_max = 8;
+    L.counter_bytes = align_up((mt * tiles_max + 64) * sizeof(int), kAlign);   // + status word
     L.counters = o; o += L.counter_bytes;
-    L.sumsq = o;    o = align_up(o + mt * units * kMTile * 4, kAlign);
-    L.part = o;     o = align_up(o + mt * units * kTileFloats * 4, kAlign);
+    L.sumsq = o;    o = align_up(o + mt * (tiles_max + kXcds) * s_max * kMTile * 4, kAlign);
+    L.part = o;     o = align_up(o + mt * tiles_max * s_max * kTileFloats * 4, kAlign);
     L.xhat = o;
   } else {
     L.counter_bytes = 0;
@@ -158,28 +167,37 @@ static int verify_layer_bf16(const sv_model_cfg& c, const char* packed, float* x
   const int H = c.hidden, D = c.n_heads * c.head_dim, F = c.mlp_dim;
   const PackedLayout pl = packed_layout(c);
   const WorkspaceLayout wl = workspace_layout(c, M, 0);
-  const SplitPlan sp = split_plan(c, M);
+  const int n_xcd = device_xcds();
+  size_t n_max = 3 * (size_t)D;
+  if (2 * (size_t)F > n_max) n_max = 2 * (size_t)F;
+  if ((size_t)H > n_max) n_max = H;
+  unsigned* counters = (unsigned*)(ws + wl.counters);
   GemmArgs a;
   memset(&a, 0, sizeof(a));
   a.M = M;
+  a.n_xcd = n_xcd;
   a.part = (float*)(ws + wl.part);
   a.sumsq = (float*)(ws + wl.sumsq);
-  a.counters = (int*)(ws + wl.counters);
+  a.tile_cnt = counters;
+  a.status = (int*)(ws + wl.counters + wl.counter_bytes) - 1;   // last word of the counter region
   a.eps = c.rms_eps;
   float* q = (float*)(ws + wl.q);
   float* attn = (float*)(ws + wl.attn);
   float* act = (float*)(ws + wl.act);
-  auto grid_of = [&](int N, int S) {
-    return dim3(8 * ceil_div(N / kWgRows, 8) * S, wl.m_tiles, 1);
+  dim3 grid(1, wl.m_tiles, 1);
+  auto shape = [&](int N, int K) {
+    const GemmPlan p = plan_gemm(N, K, n_xcd);
+    a.N = N; a.K = K; a.S = p.S; a.gpx = p.gpx;
+    grid.x = n_xcd * p.gpx * p.S;            // workgroup i -> XCD i % n_xcd, unit i / n_xcd
   };
 
   a.X = x; a.gain = (const float*)(packed + pl.g1); a.Wp = (const uint4*)(packed + pl.wqkv);
-  a.N = 3 * D; a.K = H; a.S = sp.qkv;
+  shape(3 * D, H);
   a.q_out = q; a.kc = (bf16_t*)kv.k; a.vc = (bf16_t*)kv.v; a.depth = tree.depth;
   a.prefix_len = kv.prefix_len; a.p_max = kv.prefix_len_max; a.cap = kv.capacity; a.T = T_;
   a.nh = c.n_heads; a.theta = c.rope_theta;
   mark(0);
-  gemm_fused_bf16<PRO_GAIN, EPI_QKV><<<grid_of(a.N, a.S), 256, 0, st>>>(a);
+  gemm_stream_bf16<PRO_GAIN, EPI_QKV><<<grid, 256, 0, st>>>(a);
   mark(1);
   mark(2);
   tree_attention_rowwise<bf16_t, float><<<dim3(ceil_div(M, 4), c.n_heads), 256, 0, st>>>(
@@ -187,18 +205,21 @@ static int verify_layer_bf16(const sv_model_cfg& c, const char* packed, float* x
       tree.anc_mask, tree.n_words, T_, c.n_heads, c.head_dim, kv.capacity, attn, M);
   mark(3);
   a.X = attn; a.gain = nullptr; a.Wp = (const uint4*)(packed + pl.wo);
-  a.N = H; a.K = D; a.S = sp.o; a.x_io = x;
-  gemm_fused_bf16<PRO_PLAIN, EPI_RESID><<<grid_of(a.N, a.S), 256, 0, st>>>(a);
+  shape(H, D);
+  a.x_io = x;
+  gemm_stream_bf16<PRO_PLAIN, EPI_RESID><<<grid, 256, 0, st>>>(a);
   mark(4);
   a.X = x; a.gain = (const float*)(packed + pl.g2); a.Wp = (const uint4*)(packed + pl.wgu);
-  a.N = 2 * F; a.K = H; a.S = sp.gu; a.act = act;
+  shape(2 * F, H);
+  a.act = act;
   mark(5);
-  gemm_fused_bf16<PRO_GAIN, EPI_SWIGLU><<<grid_of(a.N, a.S), 256, 0, st>>>(a);
+  gemm_stream_bf16<PRO_GAIN, EPI_SWIGLU><<<grid, 256, 0, st>>>(a);
   mark(6);
   a.X = act; a.gain = nullptr; a.Wp = (const uint4*)(packed + pl.wd);
-  a.N = H; a.K = F; a.S = sp.down; a.x_io = x;
+  shape(H, F);
+  a.x_io = x;
   mark(7);
-  gemm_fused_bf16<PRO_PLAIN, EPI_RESID><<<grid_of(a.N, a.S), 256, 0, st>>>(a);
+  gemm_stream_bf16<PRO_PLAIN, EPI_RESID><<<grid, 256, 0, st>>>(a);
   mark(8);
   return launch_status();
 }
@@ -210,18 +231,21 @@ static int pack_layer_t(const sv_model_cfg& c, const sv_layer_weights& w, char* 
   const int H = c.hidden, D = c.n_heads * c.head_dim, F = c.mlp_dim;
   pack_gain<T><<<ceil_div(H, 256), 256, 0, st>>>((const T*)w.g1, (float*)(packed + pl.g1), H);
   pack_gain<T><<<ceil_div(H, 256), 256, 0, st>>>((const T*)w.g2, (float*)(packed + pl.g2), H);
-  // float32: q|k|v and gate|up stacked, row-major.  bf16: fragment order; gate and up
-  // interleaved in blocks of 64 rows so that one 128-row tile holds both for 64 columns.
+  // float32: q|k|v and gate|up stacked, row-major.  bf16: fragment order with the row
+  // permutations of the tile-local epilogues (rotary pairs / gate-up pairs 16 lanes apart).
   struct Piece {
     const void* src; size_t dst; int rows, k;
     int plain_off;                 // float32: first destination row
-    int group, stride, row_off;    // bf16: see pack_rows_mfma
+    int mode, off;                 // bf16: see pack_rows_mfma
   };
   const Piece pieces[] = {
-      {w.wq, pl.wqkv, D, H, 0, D, 0, 0},      {w.wk, pl.wqkv, D, H, D, D, 0, D},
-      {w.wv, pl.wqkv, D, H, 2 * D, D, 0, 2 * D}, {w.wo, pl.wo, H, D, 0, H, 0, 0},
-      {w.wg, pl.wgu, F, H, 0, 64, 128, 0},    {w.wu, pl.wgu, F, H, F, 64, 128, 64},
-      {w.wd, pl.wd, H, F, 0, H, 0, 0}};
+      {w.wq, pl.wqkv, D, H, 0, PACK_PAIR16_HEAD, 0},
+      {w.wk, pl.wqkv, D, H, D, PACK_PAIR16_HEAD, D},
+      {w.wv, pl.wqkv, D, H, 2 * D, PACK_PAIR16_HEAD, 2 * D},
+      {w.wo, pl.wo, H, D, 0, PACK_PLAIN, 0},
+      {w.wg, pl.wgu, F, H, 0, PACK_PAIR16_GU, 0},
+      {w.wu, pl.wgu, F, H, F, PACK_PAIR16_GU, 16},
+      {w.wd, pl.wd, H, F, 0, PACK_PLAIN, 0}};
   for (const Piece& p : pieces) {
     if (c.dtype == SV_F32) {
       const size_t n = (size_t)p.rows * p.k;
@@ -230,8 +254,7 @@ static int pack_layer_t(const sv_model_cfg& c, const sv_layer_weights& w, char* 
     } else {
       const size_t chunks = (size_t)p.rows * (p.k / 8);
       pack_rows_mfma<<<(unsigned)((chunks + 255) / 256), 256, 0, st>>>(
-          (const uint4*)p.src, (uint4*)(packed + p.dst), p.rows, p.k, p.group, p.stride,
-          p.row_off);
+          (const uint4*)p.src, (uint4*)(packed + p.dst), p.rows, p.k, p.mode, p.off);
     }
   }
   return launch_status();
@@ -361,6 +384,9 @@ int sv_workspace_region(const sv_model_cfg* cfg, int B, int T, int n_scored, int
   } else if (which == SV_WS_Q) {
     *offset = wl.q;
     *bytes = M * D * 4;
+  } else if (which == SV_WS_STATUS) {
+    *offset = wl.counters + (wl.counter_bytes ? wl.counter_bytes - 4 : 0);
+    *bytes = wl.counter_bytes ? 4 : 0;
   } else {
     return SV_ERR_SHAPE;
   }

@@ -8,19 +8,30 @@
 //   * W is cut into fragments that are exactly one operand of v_mfma_f32_32x32x16_bf16 - 32
 //     weight rows x 16 k-values, lane l holding the 8 consecutive k-values (l / 32) * 8 .. + 7
 //     of row l % 32 - and the fragments of one 32-row tile are stored one after the other
-//     along K.  A wavefront reads its tile as one contiguous stream, 1 KiB per load
-//     instruction, straight into operand registers, one 128-wide K block ahead of the math.
-//   * activations stay float32 in memory; while staging a K block into LDS (in fragment
-//     order) each value is split into hi + lo bf16 parts and both are multiplied, so the
-//     product is accurate to ~2^-17 instead of 2^-9 at no cost in HBM bytes (the matrix cores
-//     idle most of the time on this path).  This keeps a 32-layer pass inside the 2e-2 bar.
-//   * a workgroup owns 128 weight rows x one K slice.  Slices of the same rows are placed on
-//     the same XCD (workgroup id modulo 8) so their partial tiles meet in that XCD's L2; the
-//     workgroup that finishes last adds the partials in slice order (bit-reproducible) and
-//     runs the epilogue: RMSNorm scale + RoPE + KV append, residual add, or SwiGLU.
-//   * RMSNorm is folded in: the prologue multiplies by the gain and sums x^2 over its K
-//     slice; the slices of one row group cover K exactly once, so the last workgroup has the
-//     full row sums and scales the output rows by 1/sqrt(mean + eps).
+//     along K.  A wavefront reads a tile as one contiguous stream, 1 KiB per load
+//     instruction, straight into operand registers, 16 KiB ahead of the math.
+//   * activations stay float32 in memory; when a workgroup stages its K slice of X into LDS
+//     (once, in fragment order) each value is split into hi + lo bf16 parts and both are
+//     multiplied, so the product is accurate to ~2^-17 instead of 2^-9 at no cost in HBM
+//     bytes (the matrix cores idle most of the time on this path).  This keeps a 32-layer
+//     pass inside the 2e-2 bar.  With X resident, the main loop has no barrier: each of the
+//     four waves only streams weights, reads X fragments from LDS and issues MFMAs.
+//   * work unit = (group of 32-row tiles, K slice), one per workgroup, one workgroup per CU.
+//     The hardware deals workgroups to the eight XCDs round robin (workgroup i runs on XCD
+//     i % 8), so unit = f(workgroup id) puts all slices of a tile on one XCD and their partial
+//     tiles meet in that XCD's L2: writer = plain stores, wait for completion, then an atomic
+//     on the tile's arrival counter; the wave that arrives last invalidates its L1 and adds
+//     the partials in slice order (bit-reproducible), then runs the epilogue.  This is the
+//     synchronisation the compiler itself emits between CUs that share an L2; the device-wide
+//     release (an L2 write-back per workgroup) measured 2x slower end to end.  The placement
+//     is checked, not assumed: every arrival adds to the 4-bit field of the XCD it really ran
+//     on (read from the XCC_ID register), and a last arriver that finds arrivals from another
+//     XCD raises a sticky flag in the workspace (SV_WS_STATUS) - results are then suspect.
+//   * epilogues are tile local: weight rows are permuted at pack time so that a RoPE pair
+//     (j, j + 64) and a SwiGLU pair (gate, up) sit 16 lanes apart in the same tile.
+//   * RMSNorm is folded in: staging multiplies by the gain and sums x^2 over its K slice;
+//     the slices of one group cover K exactly once, so the last wave has the full row sums
+//     and scales the output rows by 1/sqrt(mean + eps).
 #ifndef SV_GEMM_MFMA_H
 #define SV_GEMM_MFMA_H
 
@@ -30,28 +41,43 @@ namespace sv {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
 
-constexpr int kFragRows = 32;    // weight rows per fragment (MFMA N)
+constexpr int kFragRows = 32;    // weight rows per fragment and per tile (MFMA N)
 constexpr int kFragK = 16;       // k-values per fragment (MFMA K)
-constexpr int kBlkK = 128;       // k-values staged per LDS block (8 fragments)
-constexpr int kWgRows = 128;     // weight rows per workgroup (4 waves x 32)
-constexpr int kTileFloats = kMTile * kWgRows;   // one partial tile, [64][128] float32
+constexpr int kBlkK = 128;       // granularity of K slices (8 fragments)
+constexpr int kChunkBlks = 4;    // K blocks of X resident in LDS at a time (512 k-values = 2 pieces)
+constexpr int kPieceFrags = 16;  // fragments per register buffer (16 KiB in flight per wave)
+constexpr int kTileFloats = kMTile * kFragRows;   // one partial tile, [64][32] float32
+constexpr int kXcds = 8;
 
 enum { PRO_PLAIN = 0, PRO_GAIN = 1 };
 enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
+enum { PACK_PLAIN = 0, PACK_PAIR16_HEAD = 1, PACK_PAIR16_GU = 2 };
 
-// Packer: src [rows, K] bf16 row-major -> fragment order.  Source row n goes to destination
-// row  (n / group) * dst_stride + dst_off + n % group  (group = rows: plain placement behind
-// dst_off rows; group = 64, dst_stride = 128: gate / up interleaved per 128-row tile).
+// Packer: src [rows, K] bf16 row-major -> fragment order, with a row permutation:
+//   PACK_PLAIN        dst row = off + n
+//   PACK_PAIR16_HEAD  heads of 128 rows; row d of a head goes to 32*((d%64)/16) + 16*(d/64) + d%16
+//                     (a tile holds 16 rows j and their rotary partners j + 64)
+//   PACK_PAIR16_GU    dst row = 32*(n/16) + off + n%16   (off = 0 gate, 16 up)
 // One thread moves one 16-byte chunk (8 k-values); chunk (n, kc) lands at uint4 index
 // ((n/32) * (K/16) + kc/2) * 64 + (n%32) + 32 * (kc%2).
 __global__ void pack_rows_mfma(const uint4* __restrict__ src, uint4* __restrict__ dst, int rows,
-                               int K, int group, int dst_stride, int dst_off) {
+                               int K, int mode, int off) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int chunks_per_row = K / 8;
   if (i >= (size_t)rows * chunks_per_row) return;
   const int n_src = (int)(i / chunks_per_row), kc = (int)(i % chunks_per_row);
-  const int n = (n_src / group) * dst_stride + dst_off + n_src % group;
+  int n;
+  if (mode == PACK_PAIR16_HEAD) {
+    const int d = n_src % 128;
+    n = off + (n_src - d) + 32 * ((d % 64) / 16) + 16 * (d / 64) + d % 16;
+  } else if (mode == PACK_PAIR16_GU) {
+    n = 32 * (n_src / 16) + off + n_src % 16;
+  } else {
+    n = off + n_src;
+  }
   const size_t frag = (size_t)(n / kFragRows) * (K / kFragK) + (kc >> 1);
   dst[frag * 64 + (n % kFragRows) + 32 * (kc & 1)] = src[i];
 }
@@ -60,18 +86,19 @@ struct GemmArgs {
   const float* X;        // [M, K] float32 activations
   const float* gain;     // [K] RMSNorm gain (PRO_GAIN) or unused
   const uint4* Wp;       // packed weights, N rows
-  int M, N, K, S;        // rows of X, weight rows, reduction length, K slices
-  float* part;           // [m_tiles][G][S][64][128] partial tiles (S > 1)
-  float* sumsq;          // [m_tiles][G][S][64] partial row sums of x^2 (PRO_GAIN)
-  int* counters;         // [m_tiles][G] arrival counters, zero before and after the launch
+  int M, N, K;
+  int S;                 // K slices
+  int gpx;               // tile groups per XCD (units per XCD = gpx * S)
+  int n_xcd;             // XCDs of the device (8 on MI355X; 1 for a single-XCD partition)
+  float* part;           // [m_tiles][N/32][S][64][32] partial tiles
+  float* sumsq;          // [m_tiles][n_xcd*gpx][S][64] partial row sums of x^2 (PRO_GAIN)
+  unsigned* tile_cnt;    // [m_tiles][N/32] arrival counters (4 bits per XCD), zero between launches
+  int* status;           // sticky: != 0 once slices of one tile were seen on different XCDs
   float eps;
-  // EPI_RESID: x_io [M, N] += Y
-  float* x_io;
-  // EPI_SWIGLU: act [M, N/2] = silu(gate) * up; tile rows 0..63 = gate, 64..127 = up
-  float* act;
-  // EPI_QKV: N = 3 * nh * 128; tile = one head of q, k or v
-  float* q_out;          // [M, nh*128] float32, rotated
-  bf16_t* kc;            // caches [B][nh][cap][128]
+  float* x_io;           // EPI_RESID: x_io [M, N] += Y
+  float* act;            // EPI_SWIGLU: act [M, N/2] = silu(gate) * up
+  float* q_out;          // EPI_QKV: [M, nh*128] float32, rotated
+  bf16_t* kc;            // EPI_QKV: caches [B][nh][cap][128]
   bf16_t* vc;
   const int32_t* depth;
   const int32_t* prefix_len;
@@ -79,261 +106,376 @@ struct GemmArgs {
   float theta;
 };
 
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+// Two floats -> packed bf16 (round to nearest even; one v_cvt_pk_bf16_f32 on gfx950).
 __device__ inline uint32_t pack_bf16x2(float a, float b) {
-  return (uint32_t)f32_to_bf16(a).bits | ((uint32_t)f32_to_bf16(b).bits << 16);
+  const f32x2_t v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+__device__ inline float bf16_lo_f32(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ inline float bf16_hi_f32(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
+
+// XCD (accelerator complex die) this wave runs on: bits 3:0 of the XCC_ID hardware register.
+__device__ inline int xcd_actual(int n_xcd) {
+  return (int)(__builtin_amdgcn_s_getreg((4 - 1) << 11 | 0 << 6 | 20) & 0xf) % n_xcd;
 }
 
-// grid = (8 * ceil(G / 8) * S, m_tiles), block = 256.  Workgroup w serves row group
-// g = w % 8 + 8 * ((w / 8) / S) and K slice (w / 8) % S: all slices of a group share w % 8.
+// Position of element (row l % 32, k-half l / 32) inside the 64-slot fragment of k-step s.
+// The XOR spreads the slots that one staging store instruction touches over all LDS banks;
+// readers apply the same permutation, which keeps their 16-lane groups conflict free.
+__device__ inline int frag_slot(int l, int s) { return ((l & 31) ^ (((s & 7) << 1) | (l >> 5))) | (l & 32); }
+
+// grid = (workgroups, m_tiles), block = 256, 1 workgroup per CU (LDS).  K must be a multiple
+// of 256: slices are made of pieces of 16 fragments (2 K blocks), a chunk of X in LDS holds up
+// to two pieces.
 template <int PRO, int EPI>
-__global__ __launch_bounds__(256, 2) void gemm_fused_bf16(const GemmArgs a) {
-  __shared__ uint4 lds[2 * 2048];          // 2 buffers x [8 k-steps][2 m-halves][hi, lo][64 lanes]
-  __shared__ float s_rstd[kMTile];
-  __shared__ int s_last;
+__global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
+  // X chunk: [32 k-steps][2 m-halves][hi, lo][64 slots] x 16 bytes = 128 KiB
+  __shared__ uint4 xs[32 * 2 * 2 * 64];
+  __shared__ int s_pos[kMTile];             // EPI_QKV: rotary position of each row of the m tile
+  __shared__ int s_crow[kMTile];            // EPI_QKV: cache row (b * nh * cap + P + t) of each row
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int G = a.N / kWgRows, S = a.S;
-  const int slot = blockIdx.x >> 3;
-  const int g = (blockIdx.x & 7) + 8 * (slot / S);
-  const int sp = slot % S;
-  if (g >= G) return;
   const int mt = blockIdx.y, m0 = mt * kMTile;
-  const int K = a.K;
-  const int nblk = K / kBlkK;
-  const int qn = nblk / S, rem = nblk % S;
-  const int blk_begin = sp * qn + min(sp, rem);
-  const int nb = qn + (sp < rem ? 1 : 0);
-  const int ntile = g * 4 + wave;
-  const uint4* wp = a.Wp + ((size_t)ntile * (K / kFragK) + (size_t)blk_begin * 8) * 64 + lane;
+  const int K = a.K, S = a.S;
+  const int n_tiles = a.N / kFragRows;
+  const int G = a.n_xcd * a.gpx;
+  const int npair = K / (2 * kBlkK);         // pieces along K
+  const int xcd = blockIdx.x % a.n_xcd;      // where the dispatcher puts this workgroup
+  const int u = blockIdx.x / a.n_xcd;        // unit inside that XCD's share
+  if (u >= a.gpx * S) return;
 
-  f32x16_t acc0 = {}, acc1 = {};
-  uint4 wreg[8], wnext[8];
-  float4 xa[4], xb[4];                      // 4 chunks of 8 floats per thread
-  float ssq[4] = {0.f, 0.f, 0.f, 0.f};
-  const int kc = tid & 15;                  // this thread's 8-wide chunk inside a K block
-  const int mrow = tid >> 4;                // rows mrow, mrow + 16, mrow + 32, mrow + 48
+  if (EPI == EPI_QKV && tid < kMTile) {
+    const int m = min(m0 + tid, a.M - 1);
+    const int b = m / a.T, t = m - b * a.T;
+    int P = a.prefix_len[b];
+    P = P < 0 ? 0 : (P > a.p_max ? a.p_max : P);
+    s_pos[tid] = P + a.depth[m];
+    s_crow[tid] = b * a.nh * a.cap + P + t;  // + head * cap, times 128, in the epilogue
+  }
 
-  auto load_x = [&](int blk) {
-    const int k = (blk_begin + blk) * kBlkK + kc * 8;
-    float4 g0 = make_float4(1.f, 1.f, 1.f, 1.f), g1 = g0;
-    if (PRO == PRO_GAIN) {
-      g0 = *reinterpret_cast<const float4*>(a.gain + k);
-      g1 = *reinterpret_cast<const float4*>(a.gain + k + 4);
-    }
+  {
+    const int g = xcd * a.gpx + u / S;       // tile group (contiguous tiles), K slice
+    const int sp = u % S;
+    const int tq = n_tiles / G, trem = n_tiles % G;
+    const int t_begin = g * tq + min(g, trem);
+    const int t_count = tq + (g < trem ? 1 : 0);
+    const int pq = npair / S, prem = npair % S;
+    const int p_begin = sp * pq + min(sp, prem);   // first piece of the slice
+    const int np = pq + (sp < prem ? 1 : 0);       // pieces in the slice
+    const int n_chunks = (np + 1) >> 1;
+    const int my_tiles = t_count > wave ? (t_count - wave + 3) / 4 : 0;   // tiles wave, wave+4, ..
+    const size_t unit_id = ((size_t)mt * G + g) * S + sp;
+    const size_t tile_stride = (size_t)(K / kFragK) * 64;                 // uint4 per tile
+
+    uint4 wa[kPieceFrags], wb[kPieceFrags];
+    auto load_piece = [&](uint4* buf, const uint4* p) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int m = m0 + mrow + 16 * i;
-      if (m < a.M) {
-        const float* p = a.X + (size_t)m * K + k;
-        xa[i] = *reinterpret_cast<const float4*>(p);
-        xb[i] = *reinterpret_cast<const float4*>(p + 4);
-      } else {
-        xa[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-        xb[i] = xa[i];
-      }
+      for (int f = 0; f < kPieceFrags; ++f)   // streamed once: do not keep it in the caches
+        buf[f] = __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p + (size_t)f * 64)));
+    };
+    // piece j of my tile ti
+    auto piece_ptr = [&](int ti, int j) {
+      return a.Wp + (size_t)(t_begin + wave + 4 * ti) * tile_stride +
+             (size_t)(p_begin + j) * (kPieceFrags * 64) + lane;
+    };
+
+
+    float ssq[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) ssq[r] = 0.f;
+
+    // Stage chunk c of this slice: wave w converts rows w, w+4, .. ; lane = 8-wide k chunk.
+    auto stage = [&](int c, bool first) {
+      const int nkc = min(2, np - 2 * c) * 32;     // 8-wide chunks per row in this K chunk
+      const bool on = lane < nkc;
+      const int k = (p_begin + 2 * c) * (2 * kBlkK) + (on ? lane : 0) * 8;
+      float4 g0 = make_float4(1.f, 1.f, 1.f, 1.f), g1 = g0;
       if (PRO == PRO_GAIN) {
-        ssq[i] += xa[i].x * xa[i].x + xa[i].y * xa[i].y + xa[i].z * xa[i].z + xa[i].w * xa[i].w +
-                  xb[i].x * xb[i].x + xb[i].y * xb[i].y + xb[i].z * xb[i].z + xb[i].w * xb[i].w;
-        xa[i].x *= g0.x; xa[i].y *= g0.y; xa[i].z *= g0.z; xa[i].w *= g0.w;
-        xb[i].x *= g1.x; xb[i].y *= g1.y; xb[i].z *= g1.z; xb[i].w *= g1.w;
+        g0 = *reinterpret_cast<const float4*>(a.gain + k);
+        g1 = *reinterpret_cast<const float4*>(a.gain + k + 4);
       }
-    }
-  };
-  // hi = bf16(v), lo = bf16(v - hi); fragment slot of chunk (m, kc):
-  // [k-step kc/2][m-half m/32][hi|lo][lane (m%32) + 32*(kc%2)]
-  auto store_x = [&](int buf) {
+      const int s = lane >> 1;                     // k-step inside the chunk
+      // all 32 loads of this lane's 16 rows are issued before the first conversion
+      float4 xa[16], xb[16];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int m = mrow + 16 * i;
-      const float v[8] = {xa[i].x, xa[i].y, xa[i].z, xa[i].w, xb[i].x, xb[i].y, xb[i].z, xb[i].w};
-      float r[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) r[e] = v[e] - to_f32(f32_to_bf16(v[e]));
-      const uint4 hi = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]),
-                                  pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
-      const uint4 lo = make_uint4(pack_bf16x2(r[0], r[1]), pack_bf16x2(r[2], r[3]),
-                                  pack_bf16x2(r[4], r[5]), pack_bf16x2(r[6], r[7]));
-      const int base = buf * 2048 + (((kc >> 1) * 2 + (m >> 5)) * 2) * 64 + (m & 31) + 32 * (kc & 1);
-      lds[base] = hi;
-      lds[base + 64] = lo;
-    }
-  };
-
-  if (nb > 0) {
-#pragma unroll
-    for (int s = 0; s < 8; ++s) wreg[s] = wp[(size_t)s * 64];
-    load_x(0);
-    store_x(0);
-  }
-  for (int blk = 0; blk < nb; ++blk) {
-    const int cur = blk & 1;
-    const bool more = blk + 1 < nb;
-    if (more) {
-#pragma unroll
-      for (int s = 0; s < 8; ++s) wnext[s] = wp[((size_t)(blk + 1) * 8 + s) * 64];
-      load_x(blk + 1);
-    }
-    __syncthreads();
-    const uint4* xs = lds + cur * 2048;
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      const bf16x8_t w = __builtin_bit_cast(bf16x8_t, wreg[s]);
-      const bf16x8_t x0h = __builtin_bit_cast(bf16x8_t, xs[((s * 2 + 0) * 2 + 0) * 64 + lane]);
-      const bf16x8_t x0l = __builtin_bit_cast(bf16x8_t, xs[((s * 2 + 0) * 2 + 1) * 64 + lane]);
-      const bf16x8_t x1h = __builtin_bit_cast(bf16x8_t, xs[((s * 2 + 1) * 2 + 0) * 64 + lane]);
-      const bf16x8_t x1l = __builtin_bit_cast(bf16x8_t, xs[((s * 2 + 1) * 2 + 1) * 64 + lane]);
-      acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0h, w, acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1h, w, acc1, 0, 0, 0);
-      acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0l, w, acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1l, w, acc1, 0, 0, 0);
-    }
-    if (more) {
-      store_x(cur ^ 1);
-#pragma unroll
-      for (int s = 0; s < 8; ++s) wreg[s] = wnext[s];
-    }
-  }
-
-  // Accumulator register r of lane l holds row 8 * (r / 4) + 4 * (l / 32) + r % 4 (acc1: + 32)
-  // and column wave * 32 + l % 32 of the workgroup's [64][128] tile.
-  const int col = wave * 32 + (lane & 31);
-  const int rbase = 4 * (lane >> 5);
-  const size_t unit = (size_t)mt * G + g;
-
-  if (PRO == PRO_GAIN) {                    // row sums of x^2 over this K slice
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      float v = ssq[i];
-      v += __shfl_xor(v, 8, kWave);
-      v += __shfl_xor(v, 4, kWave);
-      v += __shfl_xor(v, 2, kWave);
-      v += __shfl_xor(v, 1, kWave);
-      if (kc == 0) a.sumsq[(unit * S + sp) * kMTile + mrow + 16 * i] = v;
-    }
-  }
-  if (S > 1) {
-    float* pt = a.part + (unit * S + sp) * kTileFloats + col;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int m = 8 * (r >> 2) + rbase + (r & 3);
-      pt[m * kWgRows] = acc0[r];
-      pt[(m + 32) * kWgRows] = acc1[r];
-    }
-  }
-  if (S > 1 || PRO == PRO_GAIN) {
-    __threadfence();                        // release: partial tile and row sums are visible ...
-    __syncthreads();
-    if (tid == 0) {
-      int last = 1;
-      if (S > 1) {
-        const int old = atomicAdd(a.counters + unit, 1);   // ... before the arrival is counted
-        last = old == S - 1;
-        if (last) a.counters[unit] = 0;     // left clean for the next launch
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wave + 4 * r;
+        const float* p = a.X + (size_t)min(m, a.M - 1) * K + k;
+        xa[r] = *reinterpret_cast<const float4*>(p);
+        xb[r] = *reinterpret_cast<const float4*>(p + 4);
       }
-      s_last = last;
-    }
+      // the first weight piece goes out right behind the X loads: loads return in issue order,
+      // so X is not held up by the (slower, HBM) weight loads, and both overlap the conversion
+      if (first && my_tiles > 0 && np > 0) load_piece(wa, piece_ptr(0, 0));
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int ml = wave + 4 * r;
+        const float keep = (on && (m0 + ml < a.M)) ? 1.0f : 0.0f;
+        float v[8] = {xa[r].x, xa[r].y, xa[r].z, xa[r].w, xb[r].x, xb[r].y, xb[r].z, xb[r].w};
+        if (PRO == PRO_GAIN) {
+          float t = 0.f;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) t += v[e] * v[e];
+          ssq[r] += t * keep;
+          v[0] *= g0.x; v[1] *= g0.y; v[2] *= g0.z; v[3] *= g0.w;
+          v[4] *= g1.x; v[5] *= g1.y; v[6] *= g1.z; v[7] *= g1.w;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] *= keep;
+        uint4 hi4, lo4;
+        hi4.x = pack_bf16x2(v[0], v[1]); hi4.y = pack_bf16x2(v[2], v[3]);
+        hi4.z = pack_bf16x2(v[4], v[5]); hi4.w = pack_bf16x2(v[6], v[7]);
+        lo4.x = pack_bf16x2(v[0] - bf16_lo_f32(hi4.x), v[1] - bf16_hi_f32(hi4.x));
+        lo4.y = pack_bf16x2(v[2] - bf16_lo_f32(hi4.y), v[3] - bf16_hi_f32(hi4.y));
+        lo4.z = pack_bf16x2(v[4] - bf16_lo_f32(hi4.z), v[5] - bf16_hi_f32(hi4.z));
+        lo4.w = pack_bf16x2(v[6] - bf16_lo_f32(hi4.w), v[7] - bf16_hi_f32(hi4.w));
+        const int slot = frag_slot((ml & 31) | ((lane & 1) << 5), s);
+        const int base = ((s * 2 + (ml >> 5)) * 2) * 64 + slot;
+        if (on) {
+          xs[base] = hi4;
+          xs[base + 64] = lo4;
+        }
+      }
+    };
+    // Row sums of x^2 over this K slice, published once the whole slice has been staged and
+    // completed (waitcnt) before the barrier that precedes any tile arrival of this workgroup.
+    auto publish_ssq = [&]() {
+      // 16 row sums per lane -> totals over the 64 lanes with a halving butterfly: after the
+      // exchanges over distances 32, 16, 8, 4 each lane holds one row's sum over 16 lanes-groups,
+      // two more steps finish it; lane l ends with the total of row index (l >> 2) & 15.
+      float v8[8], v4[4], v2[2], v1;
+      const bool h32 = lane & 32, h16 = lane & 16, h8 = lane & 8, h4 = lane & 4;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float mine = h32 ? ssq[i + 8] : ssq[i], other = h32 ? ssq[i] : ssq[i + 8];
+        v8[i] = mine + __shfl_xor(other, 32, kWave);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float mine = h16 ? v8[i + 4] : v8[i], other = h16 ? v8[i] : v8[i + 4];
+        v4[i] = mine + __shfl_xor(other, 16, kWave);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const float mine = h8 ? v4[i + 2] : v4[i], other = h8 ? v4[i] : v4[i + 2];
+        v2[i] = mine + __shfl_xor(other, 8, kWave);
+      }
+      {
+        const float mine = h4 ? v2[1] : v2[0], other = h4 ? v2[0] : v2[1];
+        v1 = mine + __shfl_xor(other, 4, kWave);
+      }
+      v1 += __shfl_xor(v1, 2, kWave);
+      v1 += __shfl_xor(v1, 1, kWave);
+      // row index held by this lane: bit 3 from lane bit 5, bit 2 from bit 4, bit 1 from bit 3,
+      // bit 0 from bit 2
+      const int r = ((lane >> 5) & 1) * 8 + ((lane >> 4) & 1) * 4 + ((lane >> 3) & 1) * 2 + ((lane >> 2) & 1);
+      if ((lane & 3) == 0) a.sumsq[unit_id * kMTile + wave + 4 * r] = v1;
+      __builtin_amdgcn_s_waitcnt(0);
+    };
+    stage(0, true);
+    if (PRO == PRO_GAIN && n_chunks == 1) publish_ssq();
     __syncthreads();
-    if (!s_last) return;
-    __threadfence();                        // acquire: see the other slices' results
-  }
-  if (S > 1) {                              // fixed slice order, own slice from registers
-    f32x16_t t0 = {}, t1 = {};
-    for (int s2 = 0; s2 < S; ++s2) {
-      if (s2 == sp) {
+
+    f32x16_t acc0 = {}, acc1 = {};
+    int ti = 0, j = 0;                       // piece being consumed: piece j of my tile ti
+    const int rbase = 4 * (lane >> 5);
+
+    // Consume the piece held in `cur` while the next one streams into `nxt`.
+    auto consume = [&](uint4* cur, uint4* nxt) {
+      int tin = ti, jn = j + 1;
+      if (jn == np) {
+        tin = ti + 1;
+        jn = 0;
+      }
+      if (tin < my_tiles) load_piece(nxt, piece_ptr(tin, jn));
+      const uint4* xf = xs + (size_t)((j & 1) * kPieceFrags * 4) * 64;
+#pragma unroll
+      for (int f = 0; f < kPieceFrags; ++f) {
+        // k-step inside the chunk: (j & 1) * 16 + f; its low 3 bits are those of f
+        const uint4* xp = xf + (size_t)(f * 4) * 64 + frag_slot(lane, f);
+        const bf16x8_t w = __builtin_bit_cast(bf16x8_t, cur[f]);
+        const bf16x8_t x0h = __builtin_bit_cast(bf16x8_t, xp[0]);
+        const bf16x8_t x0l = __builtin_bit_cast(bf16x8_t, xp[64]);
+        const bf16x8_t x1h = __builtin_bit_cast(bf16x8_t, xp[128]);
+        const bf16x8_t x1l = __builtin_bit_cast(bf16x8_t, xp[192]);
+        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0h, w, acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1h, w, acc1, 0, 0, 0);
+        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0l, w, acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1l, w, acc1, 0, 0, 0);
+      }
+      if (j == np - 1) {
+        // Tile finished.  The partial tile goes out in register order, [8 quads][64 lanes][4]
+        // floats (each store instruction writes 1 KiB contiguous); the reducer reads it back
+        // with the same lane -> register mapping.  Register r of lane l is row
+        // 8*(r/4) + 4*(l/32) + r%4 (+32 for acc1), column l % 32 of the [64][32] tile.
+        // The stores are issued from inline assembly on purpose: the compiler's wait-count
+        // bookkeeping then sees loads only and keeps waiting for exactly the weight fragment it
+        // needs next; a store it knew of would turn every later wait into a drain of the whole
+        // prefetch queue.  Unseen stores can only make its waits longer, never too short; their
+        // own completion is awaited explicitly before the arrival below.
+        const int tile = t_begin + wave + 4 * ti;
+        const float4* pt = reinterpret_cast<const float4*>(
+                               a.part + (((size_t)mt * n_tiles + tile) * S + sp) * kTileFloats) + lane;
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+          const f32x4_t v0 = {acc0[4 * qd], acc0[4 * qd + 1], acc0[4 * qd + 2], acc0[4 * qd + 3]};
+          const f32x4_t v1 = {acc1[4 * qd], acc1[4 * qd + 1], acc1[4 * qd + 2], acc1[4 * qd + 3]};
+          // s_nop: a store of more than 64 bits reads its data registers a few cycles after
+          // issue; the compiler cannot see that this is a store, so the wait states are explicit
+          asm volatile("global_store_dwordx4 %0, %1, off\n\ts_nop 3" ::"v"(pt + qd * 64), "v"(v0) : "memory");
+          asm volatile("global_store_dwordx4 %0, %1, off\n\ts_nop 3" ::"v"(pt + (qd + 4) * 64), "v"(v1) : "memory");
+        }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          t0[r] += acc0[r];
-          t1[r] += acc1[r];
+          acc0[r] = 0.f;
+          acc1[r] = 0.f;
         }
-      } else {
-        const float* pt = a.part + (unit * S + s2) * kTileFloats + col;
+      }
+      ti = tin;
+      j = jn;
+    };
+
+    // One chunk (<= 2 pieces) per slice: every wave walks all its tiles.  Longer slices (only
+    // with at most one tile per wave): every wave takes part in re-staging X between chunks,
+    // its accumulators carry over.  The barriers around re-staging order LDS traffic only; they
+    // do not wait for the weight loads in flight.
+    bool flip = false;
+    for (int c = 0; c < n_chunks; ++c) {
+      if (c > 0) {
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        stage(c, false);
+        if (PRO == PRO_GAIN && c == n_chunks - 1) publish_ssq();
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+      }
+      const int n_here = n_chunks == 1 ? my_tiles * np : (my_tiles > 0 ? min(2, np - 2 * c) : 0);
+      for (int t = 0; t < n_here; ++t) {
+        if (!flip) consume(wa, wb); else consume(wb, wa);
+        flip = !flip;
+      }
+    }
+
+    // ---- arrival + reduction + epilogue, per tile, by whichever wave arrives last ----
+    // Arrival = add 1 to the 4-bit field of the XCD this wave really runs on.  All S arrivals
+    // in one field: the slices shared an L2, as planned.
+    __builtin_amdgcn_s_waitcnt(0);           // this wave's partial tiles are in L2
+    const unsigned my_field = 4u * (unsigned)xcd_actual(a.n_xcd);
+    // one atomic per tile, all issued together (lane i takes tile i of this wave)
+    unsigned old_all = 0;
+    if (lane < my_tiles)
+      old_all = atomicAdd(a.tile_cnt + (size_t)mt * n_tiles + t_begin + wave + 4 * lane, 1u << my_field);
+    for (int i = 0; i < my_tiles; ++i) {
+      const int tile = t_begin + wave + 4 * i;
+      const unsigned old = __shfl(old_all, i, kWave);
+      unsigned arrived = 0;
+#pragma unroll
+      for (int x = 0; x < kXcds; ++x) arrived += (old >> (4 * x)) & 15u;
+      if (arrived != (unsigned)(S - 1)) continue;
+      if (lane == 0) {
+        a.tile_cnt[(size_t)mt * n_tiles + tile] = 0;                // clean for the next launch
+        if (old + (1u << my_field) != ((unsigned)S << my_field)) atomicOr(a.status, 1);
+      }
+      asm volatile("buffer_inv sc0 sc1" ::: "memory");              // drop stale L1 / L2 lines
+
+      f32x16_t t0 = {}, t1 = {};
+      const int ln = lane & 31;
+      // all (up to 8) slices are fetched at once, then added in slice order
+      const float4* pbase = reinterpret_cast<const float4*>(
+                                a.part + ((size_t)mt * n_tiles + tile) * S * kTileFloats) + lane;
+      float ssum[8];
+      float xres[32];                        // EPI_RESID: the residual rows, fetched with the partials
+      if (EPI == EPI_RESID) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int m = m0 + 8 * (r >> 2) + rbase + (r & 3);
+          xres[r] = a.x_io[(size_t)min(m, a.M - 1) * a.N + tile * 32 + ln];
+          xres[r + 16] = a.x_io[(size_t)min(m + 32, a.M - 1) * a.N + tile * 32 + ln];
+        }
+      }
+      {
+        float4 buf[8][8];
+#pragma unroll
+        for (int s2 = 0; s2 < 8; ++s2) {
+          const int sc = min(s2, S - 1);
+          const float4* pt = pbase + (size_t)sc * (kTileFloats / 4);
+#pragma unroll
+          for (int qd = 0; qd < 8; ++qd) buf[s2][qd] = pt[qd * 64];
+          if (PRO == PRO_GAIN) ssum[s2] = a.sumsq[(((size_t)mt * G + g) * S + sc) * kMTile + lane];
+        }
+#pragma unroll
+        for (int s2 = 0; s2 < 8; ++s2) {
+          const float keep = s2 < S ? 1.0f : 0.0f;
+#pragma unroll
+          for (int qd = 0; qd < 4; ++qd) {
+            t0[4 * qd] += keep * buf[s2][qd].x;     t0[4 * qd + 1] += keep * buf[s2][qd].y;
+            t0[4 * qd + 2] += keep * buf[s2][qd].z; t0[4 * qd + 3] += keep * buf[s2][qd].w;
+            t1[4 * qd] += keep * buf[s2][qd + 4].x;     t1[4 * qd + 1] += keep * buf[s2][qd + 4].y;
+            t1[4 * qd + 2] += keep * buf[s2][qd + 4].z; t1[4 * qd + 3] += keep * buf[s2][qd + 4].w;
+          }
+        }
+      }
+      if (PRO == PRO_GAIN) {                 // lane l: rstd of row l, then fetched per register
+        float t = 0.f;
+#pragma unroll
+        for (int s2 = 0; s2 < 8; ++s2) t += s2 < S ? ssum[s2] : 0.f;
+        const float rstd = 1.0f / sqrtf(t / (float)K + a.eps);
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int m = 8 * (r >> 2) + rbase + (r & 3);
-          t0[r] += pt[m * kWgRows];
-          t1[r] += pt[(m + 32) * kWgRows];
+          t0[r] *= __shfl(rstd, m, kWave);
+          t1[r] *= __shfl(rstd, m + 32, kWave);
         }
       }
-    }
-    acc0 = t0;
-    acc1 = t1;
-  }
-  if (PRO == PRO_GAIN) {
-    if (tid < kMTile) {
-      float t = 0.f;
-      for (int s2 = 0; s2 < S; ++s2) t += a.sumsq[(unit * S + s2) * kMTile + tid];
-      s_rstd[tid] = 1.0f / sqrtf(t / (float)K + a.eps);
-    }
-    __syncthreads();
+
+      if (EPI == EPI_RESID) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int m = 8 * (r >> 2) + rbase + (r & 3);
-      acc0[r] *= s_rstd[m];
-      acc1[r] *= s_rstd[m + 32];
-    }
-  }
-
-  if (EPI == EPI_RESID) {
+        for (int r = 0; r < 16; ++r) {
+          const int m = m0 + 8 * (r >> 2) + rbase + (r & 3);
+          if (m < a.M) a.x_io[(size_t)m * a.N + tile * 32 + ln] = xres[r] + t0[r];
+          if (m + 32 < a.M) a.x_io[(size_t)(m + 32) * a.N + tile * 32 + ln] = xres[r + 16] + t1[r];
+        }
+      }
+      if (EPI == EPI_SWIGLU) {               // lanes 0..15 gate, 16..31 up of the same column
+        const int F = a.N / 2;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int m = m0 + 8 * (r >> 2) + rbase + (r & 3);
-      if (m < a.M) a.x_io[(size_t)m * a.N + g * kWgRows + col] += acc0[r];
-      if (m + 32 < a.M) a.x_io[(size_t)(m + 32) * a.N + g * kWgRows + col] += acc1[r];
-    }
-    return;
-  }
-
-  // The other epilogues pair columns held by different waves: go through LDS (the staging
-  // buffers are free now; every wave passed the last barrier of the main loop).
-  float* tile = reinterpret_cast<float*>(lds);            // [64][129]
-  __syncthreads();
+        for (int r = 0; r < 16; ++r) {
+          const int m = m0 + 8 * (r >> 2) + rbase + (r & 3);
+          const float u0 = __shfl_xor(t0[r], 16, kWave), u1 = __shfl_xor(t1[r], 16, kWave);
+          if (ln < 16) {
+            if (m < a.M) a.act[(size_t)m * F + tile * 16 + ln] = t0[r] / (1.0f + expf(-t0[r])) * u0;
+            if (m + 32 < a.M)
+              a.act[(size_t)(m + 32) * F + tile * 16 + ln] = t1[r] / (1.0f + expf(-t1[r])) * u1;
+          }
+        }
+      }
+      if (EPI == EPI_QKV) {
+        const int tiles_per_mat = a.nh * 4;  // 128 rows per head = 4 tiles
+        const int which = tile / tiles_per_mat;                  // 0 q, 1 k, 2 v
+        const int head = (tile % tiles_per_mat) / 4, uq = tile % 4;
+        const int j = 16 * uq + (ln & 15);                       // rotary pair index, 0..63
+        const int dcol = j + 64 * (ln >> 4);                     // column inside the head
+        // angle in turns = position * theta^(-2j/128) / (2 pi)
+        const float turn_freq = exp2f(-(float)j * (1.0f / 64.0f) * log2f(a.theta)) * 0.15915494309189535f;
+        const float sgn = (ln & 16) ? 1.0f : -1.0f;
+        const int D = a.nh * 128;
+        bf16_t* cache = which == 1 ? a.kc : a.vc;
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int m = 8 * (r >> 2) + rbase + (r & 3);
-    tile[m * 129 + col] = acc0[r];
-    tile[(m + 32) * 129 + col] = acc1[r];
-  }
-  __syncthreads();
-  const int j = tid & 63;
-
-  if (EPI == EPI_SWIGLU) {
-    const int F = a.N / 2;
-#pragma unroll 4
-    for (int i = 0; i < 16; ++i) {
-      const int ml = (tid >> 6) + 4 * i, m = m0 + ml;
-      if (m >= a.M) continue;
-      const float gt = tile[ml * 129 + j], up = tile[ml * 129 + 64 + j];
-      a.act[(size_t)m * F + g * 64 + j] = gt / (1.0f + expf(-gt)) * up;
-    }
-    return;
-  }
-
-  if (EPI == EPI_QKV) {
-    const int D = a.nh * 128;
-    const int which = (g * kWgRows) / D;                  // 0 q, 1 k, 2 v
-    const int head = ((g * kWgRows) % D) / 128;
-    const float inv_freq = exp2f(-(float)j * (1.0f / 64.0f) * log2f(a.theta));
-#pragma unroll 2
-    for (int i = 0; i < 16; ++i) {
-      const int ml = (tid >> 6) + 4 * i, m = m0 + ml;
-      if (m >= a.M) continue;
-      const int b = m / a.T, t = m - b * a.T;
-      int P = a.prefix_len[b];
-      P = P < 0 ? 0 : (P > a.p_max ? a.p_max : P);
-      const float v0 = tile[ml * 129 + j], v1 = tile[ml * 129 + 64 + j];
-      const size_t crow = (((size_t)b * a.nh + head) * a.cap + (size_t)(P + t)) * 128;
-      if (which == 2) {
-        a.vc[crow + j] = f32_to_bf16(v0);
-        a.vc[crow + 64 + j] = f32_to_bf16(v1);
-      } else {
-        float sn, cs;
-        sincosf((float)(P + a.depth[m]) * inv_freq, &sn, &cs);
-        const float r0 = v0 * cs - v1 * sn, r1 = v1 * cs + v0 * sn;
-        if (which == 0) {
-          a.q_out[(size_t)m * D + head * 128 + j] = r0;
-          a.q_out[(size_t)m * D + head * 128 + 64 + j] = r1;
-        } else {
-          a.kc[crow + j] = f32_to_bf16(r0);
-          a.kc[crow + 64 + j] = f32_to_bf16(r1);
+        for (int r = 0; r < 32; ++r) {
+          const int ml = 8 * ((r & 15) >> 2) + rbase + (r & 3) + 32 * (r >> 4);
+          float v = r < 16 ? t0[r & 15] : t1[r & 15];
+          const float partner = __shfl_xor(v, 16, kWave);
+          if (which != 2) {
+            float turns = (float)s_pos[ml] * turn_freq;
+            turns -= floorf(turns);          // reduced to [0, 1) before the hardware sin / cos
+            v = v * __builtin_amdgcn_cosf(turns) + sgn * partner * __builtin_amdgcn_sinf(turns);
+          }
+          if (m0 + ml < a.M) {
+            if (which == 0)
+              a.q_out[(size_t)(m0 + ml) * D + head * 128 + dcol] = v;
+            else
+              cache[((size_t)s_crow[ml] + (size_t)head * a.cap) * 128 + dcol] = f32_to_bf16(v);
+          }
         }
       }
     }

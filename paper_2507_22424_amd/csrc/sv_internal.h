@@ -89,12 +89,6 @@ inline PackedLayout packed_layout(const sv_model_cfg& c) {
   return L;
 }
 
-// How many K-slices each of the four GEMMs of a layer is cut into (bf16 path), chosen from
-// the shapes alone so that workspace sizing and launches agree.
-struct SplitPlan {
-  int qkv, o, gu, down;
-};
-
 // Device scratch of one call (bytes from the start of the workspace).  Activations are
 // float32 for both storage types.
 struct WorkspaceLayout {

@@ -103,6 +103,11 @@ class VerifyPass:
         self.forward(want_logits=want_logits)
         self.accept(r)
 
+    def placement_status(self) -> int:
+        """0 unless a GEMM saw the slices of one tile on different XCDs (see SV_WS_STATUS)."""
+        off, nb = sv.sv_workspace_region(self.cfg, self.B, self.T, self.n_scored, sv.SV_WS_STATUS)
+        return int(self.workspace[off:off + 4].view(torch.int32).item()) if nb else 0
+
     def workspace_view(self, which: int) -> torch.Tensor:
         off, nb = sv.sv_workspace_region(self.cfg, self.B, self.T, self.n_scored, which)
         raw = self.workspace[off:off + nb]

@@ -100,6 +100,7 @@ class SideBySide:
         self.gpu_token = self.gpu.token.cpu().numpy()
         self.gpu_x = self.gpu.x.cpu().numpy()
         self.logit_err = row_rel_err(self.gpu_logits, self.ref_logits)
+        assert self.gpu.placement_status() == 0, "K slices of a tile ran on different XCDs"
 
     def tolerated_ties(self, tol):
         """Nodes whose GPU token differs from the oracle's: (n tolerated, n not tolerated).
