@@ -8,6 +8,7 @@
 
 #include "specvla_verify.h"
 #include "sv_accept.h"
+#include "sv_attention.h"
 #include "sv_gemm_mfma.h"
 #include "sv_internal.h"
 #include "sv_kernels.h"
@@ -200,9 +201,9 @@ static int verify_layer_bf16(const sv_model_cfg& c, const char* packed, float* x
   gemm_stream_bf16<PRO_GAIN, EPI_QKV><<<grid, 256, 0, st>>>(a);
   mark(1);
   mark(2);
-  tree_attention_rowwise<bf16_t, float><<<dim3(ceil_div(M, 4), c.n_heads), 256, 0, st>>>(
+  tree_attention_mfma<<<dim3(B * ceil_div(T_, kAttQ), c.n_heads), 256, 0, st>>>(
       q, (const bf16_t*)kv.k, (const bf16_t*)kv.v, kv.prefix_len, kv.prefix_len_max,
-      tree.anc_mask, tree.n_words, T_, c.n_heads, c.head_dim, kv.capacity, attn, M);
+      tree.anc_mask, tree.n_words, T_, c.n_heads, kv.capacity, attn);
   mark(3);
   a.X = attn; a.gain = nullptr; a.Wp = (const uint4*)(packed + pl.wo);
   shape(H, D);

@@ -1,0 +1,234 @@
+// Tree attention of the bf16 verification layer on the gfx950 matrix cores.
+//
+// Node i of a draft tree attends to every prefix key and to the tree nodes on its own root
+// path (its ancestor-or-self bitmask) - the keys an ordinary causal decode of that path would
+// see (the paper verifies all paths of the tree in one pass, Sec. 4.1).
+//
+// One workgroup = one (episode, head, block of 16 query nodes); its four waves split the key
+// range into 32-key tiles (flash-decoding inside the workgroup: no cross-workgroup traffic)
+// and merge their partial (max, sum, output) through LDS at the end.  Everything is computed
+// transposed, S^T = K Q^T and O^T = V^T P^T with v_mfma_f32_16x16x32_bf16, so that
+//   * a K tile is a matrix-core operand as it sits in the cache (16 B per lane, no staging),
+//   * a lane owns one query column: the online-softmax state and the rescale are per lane,
+//   * the probabilities come out of the first product in exactly the register layout the
+//     second one wants (k-slot (g, e) of lane group g = key 4g+e of the first 16-key
+//     sub-tile for e < 4, of the second for e >= 4); only V is transposed through LDS.
+// Queries and probabilities are split into hi + lo bf16 parts so that, with the exact bf16
+// keys and values, the result carries float32-level rounding only.
+#ifndef SV_ATTENTION_H
+#define SV_ATTENTION_H
+
+#include "sv_gemm_mfma.h"
+#include "sv_internal.h"
+
+namespace sv {
+
+constexpr int kAttQ = 16;        // queries per workgroup
+constexpr int kAttKeys = 32;     // keys per tile
+constexpr int kVtPitch = 72;     // bytes per row of the transposed V tile (64 + pad, 8-byte aligned)
+constexpr float kNegBig = -1.0e30f;
+
+__device__ inline bf16x8_t pack8_hi(const float* v) {
+  const uint4 u = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]),
+                             pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+  return __builtin_bit_cast(bf16x8_t, u);
+}
+__device__ inline void split8(const float* v, bf16x8_t& hi, bf16x8_t& lo) {
+  uint4 h, l;
+  h.x = pack_bf16x2(v[0], v[1]); h.y = pack_bf16x2(v[2], v[3]);
+  h.z = pack_bf16x2(v[4], v[5]); h.w = pack_bf16x2(v[6], v[7]);
+  l.x = pack_bf16x2(v[0] - bf16_lo_f32(h.x), v[1] - bf16_hi_f32(h.x));
+  l.y = pack_bf16x2(v[2] - bf16_lo_f32(h.y), v[3] - bf16_hi_f32(h.y));
+  l.z = pack_bf16x2(v[4] - bf16_lo_f32(h.z), v[5] - bf16_hi_f32(h.z));
+  l.w = pack_bf16x2(v[6] - bf16_lo_f32(h.w), v[7] - bf16_hi_f32(h.w));
+  hi = __builtin_bit_cast(bf16x8_t, h);
+  lo = __builtin_bit_cast(bf16x8_t, l);
+}
+
+// grid = (B * ceil(T / 16), n_heads), block = 256.  head_dim = 128.
+// q: float32 [M, nh*128] (rotated);  kc, vc: bf16 [B][nh][cap][128];  out: float32 [M, nh*128].
+__global__ __launch_bounds__(256) void tree_attention_mfma(
+    const float* __restrict__ q, const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc,
+    const int32_t* __restrict__ prefix_len, int p_max, const uint64_t* __restrict__ anc,
+    int n_words, int T, int nh, int cap, float* __restrict__ out) {
+  // per wave: transposed V tile [128 d][32 keys] with padded rows; reused for the merge
+  __shared__ __attribute__((aligned(16))) unsigned char lds_raw[4 * 128 * kVtPitch];
+  __shared__ float s_m[4][kAttQ], s_l[4][kAttQ];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 4, c = lane & 15;      // lane group (0..3), column = query
+  const int qblocks = (T + kAttQ - 1) / kAttQ;
+  const int b = blockIdx.x / qblocks, qb = blockIdx.x % qblocks;
+  const int h = blockIdx.y;
+  const int D = nh * 128;
+  int P = prefix_len[b];
+  P = P < 0 ? 0 : (P > p_max ? p_max : P);
+  const int nkeys = P + T;
+  const int ntiles = (nkeys + kAttKeys - 1) / kAttKeys;
+  const int tq = min(qb * kAttQ + c, T - 1);   // this lane's query node (clamped in the tail)
+  const size_t mrow = (size_t)b * T + tq;
+  const bf16_t* kbase = kc + ((size_t)b * nh + h) * cap * 128;
+  const bf16_t* vbase = vc + ((size_t)b * nh + h) * cap * 128;
+  unsigned char* vt = lds_raw + wave * 128 * kVtPitch;
+
+  // Q^T operand: lane = (query c, d-slice 32*ks + 8*g .. + 7), pre-scaled by 1/sqrt(128)
+  bf16x8_t qh[4], ql[4];
+  {
+    const float scale = 0.08838834764831845f;
+    const float* qp = q + mrow * D + h * 128 + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const float4 a0 = *reinterpret_cast<const float4*>(qp + 32 * ks);
+      const float4 a1 = *reinterpret_cast<const float4*>(qp + 32 * ks + 4);
+      const float v[8] = {a0.x * scale, a0.y * scale, a0.z * scale, a0.w * scale,
+                          a1.x * scale, a1.y * scale, a1.z * scale, a1.w * scale};
+      split8(v, qh[ks], ql[ks]);
+    }
+  }
+  unsigned long long mask0 = anc[mrow * n_words], mask1 = n_words > 1 ? anc[mrow * n_words + 1] : 0ull;
+
+  // K operand of tile t: [2 sub-tiles][4 k-steps]: lane = (key c of the sub-tile, d-slice)
+  // V rows of tile t: lane loads V[key 4*i + g][8c .. 8c+7] for i = 0..7
+  uint4 kreg[8], vreg[8];
+  auto load_tile = [&](int t) {
+    const int key0 = t * kAttKeys;
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+      const int key = min(key0 + 16 * st + c, nkeys - 1);
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+        kreg[st * 4 + ks] = *reinterpret_cast<const uint4*>(kbase + (size_t)key * 128 + 32 * ks + 8 * g);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int key = min(key0 + 4 * i + g, nkeys - 1);
+      vreg[i] = *reinterpret_cast<const uint4*>(vbase + (size_t)key * 128 + 8 * c);
+    }
+  };
+
+  f32x4_t o[8];
+#pragma unroll
+  for (int dt = 0; dt < 8; ++dt) o[dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  float m_run = kNegBig, l_run = 0.f;
+
+  int t = wave;
+  if (t < ntiles) load_tile(t);
+  for (; t < ntiles; t += 4) {
+    // ---- S^T = K Q^T for the two 16-key sub-tiles ----
+    f32x4_t s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const bf16x8_t k0 = __builtin_bit_cast(bf16x8_t, kreg[ks]);
+      const bf16x8_t k1 = __builtin_bit_cast(bf16x8_t, kreg[4 + ks]);
+      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qh[ks], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qh[ks], s1, 0, 0, 0);
+      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, ql[ks], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, ql[ks], s1, 0, 0, 0);
+    }
+    // ---- V tile -> LDS, transposed, two keys per 32-bit store ----
+    // The lane holds V[key 4i+g][8c .. 8c+7]; the lane 16 further (group g^1) holds the
+    // neighbouring key.  After one exchange each of the two has both rows; the even group
+    // writes elements 0..3, the odd group elements 4..7, as (even key | odd key << 16).
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const uint4 mine = vreg[i];
+      uint4 other;
+      other.x = __shfl_xor(mine.x, 16, kWave);
+      other.y = __shfl_xor(mine.y, 16, kWave);
+      other.z = __shfl_xor(mine.z, 16, kWave);
+      other.w = __shfl_xor(mine.w, 16, kWave);
+      const bool odd = g & 1;
+      const uint4 ev = odd ? other : mine;   // row of key 4i + (g & ~1)
+      const uint4 od = odd ? mine : other;   // row of key 4i + (g | 1)
+      // the two 32-bit words (= 4 elements) this lane transposes
+      const unsigned e_w0 = odd ? ev.z : ev.x, e_w1 = odd ? ev.w : ev.y;
+      const unsigned o_w0 = odd ? od.z : od.x, o_w1 = odd ? od.w : od.y;
+      unsigned char* dst = vt + (8 * c + (odd ? 4 : 0)) * kVtPitch + (4 * i + (g & ~1)) * 2;
+      *reinterpret_cast<unsigned*>(dst) = (e_w0 & 0xffffu) | (o_w0 << 16);
+      *reinterpret_cast<unsigned*>(dst + kVtPitch) = (e_w0 >> 16) | (o_w0 & 0xffff0000u);
+      *reinterpret_cast<unsigned*>(dst + 2 * kVtPitch) = (e_w1 & 0xffffu) | (o_w1 << 16);
+      *reinterpret_cast<unsigned*>(dst + 3 * kVtPitch) = (e_w1 >> 16) | (o_w1 & 0xffff0000u);
+    }
+    // prefetch the next tile of this wave while the rest of this one is computed
+    const int tn = t + 4;
+    const int key0 = t * kAttKeys;
+    if (tn < ntiles) load_tile(tn);
+
+    // ---- mask + online softmax (per lane: query column c) ----
+    float p[8];
+    float tile_max = kNegBig;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int kidx = key0 + 16 * (e >> 2) + 4 * g + (e & 3);
+      const int tn_ = kidx - P;              // tree node of this key, if >= 0
+      bool vis = kidx < P;
+      if (tn_ >= 0 && tn_ < T) vis = ((tn_ < 64 ? mask0 >> tn_ : mask1 >> (tn_ - 64)) & 1ull) != 0;
+      const float sv_ = e < 4 ? s0[e & 3] : s1[e & 3];
+      p[e] = vis ? sv_ : kNegBig;
+      tile_max = fmaxf(tile_max, p[e]);
+    }
+    tile_max = fmaxf(tile_max, __shfl_xor(tile_max, 16, kWave));
+    tile_max = fmaxf(tile_max, __shfl_xor(tile_max, 32, kWave));
+    const float m_new = fmaxf(m_run, tile_max);
+    const float corr = __expf(m_run - m_new);
+    float psum = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      p[e] = p[e] > 0.5f * kNegBig ? __expf(p[e] - m_new) : 0.f;
+      psum += p[e];
+    }
+    psum += __shfl_xor(psum, 16, kWave);
+    psum += __shfl_xor(psum, 32, kWave);
+    l_run = l_run * corr + psum;
+    m_run = m_new;
+    bf16x8_t ph, pl;
+    split8(p, ph, pl);
+
+    // ---- O^T = O^T * corr + V^T P^T ----
+    __builtin_amdgcn_s_waitcnt(0xc07f);      // lgkmcnt(0): this wave's V^T stores have landed
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) {
+      const unsigned char* row = vt + (16 * dt + c) * kVtPitch;
+      const uint2 va = *reinterpret_cast<const uint2*>(row + 8 * g);
+      const uint2 vb = *reinterpret_cast<const uint2*>(row + 32 + 8 * g);
+      const bf16x8_t v8 = __builtin_bit_cast(bf16x8_t, make_uint4(va.x, va.y, vb.x, vb.y));
+      f32x4_t acc = o[dt];
+      acc[0] *= corr; acc[1] *= corr; acc[2] *= corr; acc[3] *= corr;
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v8, ph, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v8, pl, acc, 0, 0, 0);
+      o[dt] = acc;
+    }
+    __builtin_amdgcn_s_waitcnt(0xc07f);      // V^T reads done before the next tile overwrites them
+  }
+
+  // ---- merge the four waves ----
+  __syncthreads();
+  float* om = reinterpret_cast<float*>(lds_raw);          // [4 waves][128 d][16 q] float32 = 32 KiB
+  if (g == 0) {
+    s_m[wave][c] = m_run;
+    s_l[wave][c] = l_run;
+  }
+#pragma unroll
+  for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) om[(wave * 128 + 16 * dt + 4 * g + r) * kAttQ + c] = o[dt][r];
+  __syncthreads();
+  // wave w finishes d rows 32w .. 32w+31: lane -> (d = 32w + lane % 32, queries (lane / 32) * 8 .. + 7)
+  const int d = 32 * wave + (lane & 31);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int qq = (lane >> 5) * 8 + i;
+    const float m_all = fmaxf(fmaxf(s_m[0][qq], s_m[1][qq]), fmaxf(s_m[2][qq], s_m[3][qq]));
+    float num = 0.f, den = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float sc = __expf(s_m[w][qq] - m_all);
+      num += sc * om[(w * 128 + d) * kAttQ + qq];
+      den += sc * s_l[w][qq];
+    }
+    const int tnode = qb * kAttQ + qq;
+    if (tnode < T) out[((size_t)b * T + tnode) * D + h * 128 + d] = num / den;
+  }
+}
+
+}  // namespace sv
+#endif
