@@ -78,7 +78,7 @@ static WorkspaceLayout workspace_layout(const sv_model_cfg& c, int m_rows, int n
   if (c.dtype == SV_BF16) {
     // sized for the worst split (8 slices), independent of the device
     const size_t tiles_max = n_max / kFragRows, s_max = 8;
-    L.counter_bytes = align_up((mt * tiles_max + 64) * sizeof(int), kAlign);   // + status word
+    L.counter_bytes = align_up((mt * (tiles_max + kXcds) * 2 + 64) * sizeof(int), kAlign);   // group counters + status word
     L.counters = o; o += L.counter_bytes;
     L.sumsq = o;    o = align_up(o + mt * (tiles_max + kXcds) * s_max * kMTile * 4, kAlign);
     L.part = o;     o = align_up(o + mt * tiles_max * s_max * kTileFloats * 4, kAlign);
@@ -179,7 +179,7 @@ static int verify_layer_bf16(const sv_model_cfg& c, const char* packed, float* x
   a.n_xcd = n_xcd;
   a.part = (float*)(ws + wl.part);
   a.sumsq = (float*)(ws + wl.sumsq);
-  a.tile_cnt = counters;
+  a.group_cnt = counters;
   a.status = (int*)(ws + wl.counters + wl.counter_bytes) - 1;   // last word of the counter region
   a.eps = c.rms_eps;
   float* q = (float*)(ws + wl.q);

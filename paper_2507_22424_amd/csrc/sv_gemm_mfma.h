@@ -20,13 +20,14 @@
 //     The hardware deals workgroups to the eight XCDs round robin (workgroup i runs on XCD
 //     i % 8), so unit = f(workgroup id) puts all slices of a tile on one XCD and their partial
 //     tiles meet in that XCD's L2: writer = plain stores, wait for completion, then an atomic
-//     on the tile's arrival counter; the wave that arrives last invalidates its L1 and adds
-//     the partials in slice order (bit-reproducible), then runs the epilogue.  This is the
+//     on the group's arrival counter; once all slices have arrived (a short, bounded wait) every
+//     wave invalidates its L1 and takes an equal share of the group's output: it adds the
+//     partials in slice order (bit-reproducible) and runs the epilogue.  This is the
 //     synchronisation the compiler itself emits between CUs that share an L2; the device-wide
 //     release (an L2 write-back per workgroup) measured 2x slower end to end.  The placement
 //     is checked, not assumed: every arrival adds to the 4-bit field of the XCD it really ran
-//     on (read from the XCC_ID register), and a last arriver that finds arrivals from another
-//     XCD raises a sticky flag in the workspace (SV_WS_STATUS) - results are then suspect.
+//     on (read from the XCC_ID register); arrivals spread over several fields, or a wait that
+//     ran out, raise a sticky flag in the workspace (SV_WS_STATUS) - results are then suspect.
 //   * epilogues are tile local: weight rows are permuted at pack time so that a RoPE pair
 //     (j, j + 64) and a SwiGLU pair (gate, up) sit 16 lanes apart in the same tile.
 //   * RMSNorm is folded in: staging multiplies by the gain and sums x^2 over its K slice;
@@ -51,6 +52,7 @@ constexpr int kChunkBlks = 4;    // K blocks of X resident in LDS at a time (512
 constexpr int kPieceFrags = 16;  // fragments per register buffer (16 KiB in flight per wave)
 constexpr int kTileFloats = kMTile * kFragRows;   // one partial tile, [64][32] float32
 constexpr int kXcds = 8;
+constexpr int kRedBatch = 3;       // reduction work items whose loads are in flight together
 
 enum { PRO_PLAIN = 0, PRO_GAIN = 1 };
 enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
@@ -92,7 +94,7 @@ struct GemmArgs {
   int n_xcd;             // XCDs of the device (8 on MI355X; 1 for a single-XCD partition)
   float* part;           // [m_tiles][N/32][S][64][32] partial tiles
   float* sumsq;          // [m_tiles][n_xcd*gpx][S][64] partial row sums of x^2 (PRO_GAIN)
-  unsigned* tile_cnt;    // [m_tiles][N/32] arrival counters (4 bits per XCD), zero between launches
+  unsigned* group_cnt;   // [m_tiles][groups][2] arrival (4 bits per XCD) / departure counters, zero between launches
   int* status;           // sticky: != 0 once slices of one tile were seen on different XCDs
   float eps;
   float* x_io;           // EPI_RESID: x_io [M, N] += Y
@@ -134,6 +136,7 @@ template <int PRO, int EPI>
 __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
   // X chunk: [32 k-steps][2 m-halves][hi, lo][64 slots] x 16 bytes = 128 KiB
   __shared__ uint4 xs[32 * 2 * 2 * 64];
+  __shared__ float s_rstd[kMTile];          // PRO_GAIN: 1 / rms of each row, known after the barrier
   __shared__ int s_pos[kMTile];             // EPI_QKV: rotary position of each row of the m tile
   __shared__ int s_crow[kMTile];            // EPI_QKV: cache row (b * nh * cap + P + t) of each row
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -356,128 +359,140 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
       }
     }
 
-    // ---- arrival + reduction + epilogue, per tile, by whichever wave arrives last ----
-    // Arrival = add 1 to the 4-bit field of the XCD this wave really runs on.  All S arrivals
-    // in one field: the slices shared an L2, as planned.
+    // ---- group barrier, then every wave of every slice reduces its share ----
+    // Arrival = add 1 to the 4-bit field of the XCD this workgroup really runs on; all S
+    // arrivals in one field means the slices shared an L2, as planned.  The workgroups of a
+    // group are dispatched within 64 consecutive workgroup ids, so they are resident together
+    // and the wait below is short; it is bounded all the same (status bit 2 on give-up).
     __builtin_amdgcn_s_waitcnt(0);           // this wave's partial tiles are in L2
-    const unsigned my_field = 4u * (unsigned)xcd_actual(a.n_xcd);
-    // one atomic per tile, all issued together (lane i takes tile i of this wave)
-    unsigned old_all = 0;
-    if (lane < my_tiles)
-      old_all = atomicAdd(a.tile_cnt + (size_t)mt * n_tiles + t_begin + wave + 4 * lane, 1u << my_field);
-    for (int i = 0; i < my_tiles; ++i) {
-      const int tile = t_begin + wave + 4 * i;
-      const unsigned old = __shfl(old_all, i, kWave);
-      unsigned arrived = 0;
+    __syncthreads();
+    unsigned* gcnt = a.group_cnt + ((size_t)mt * G + g) * 2;
+    if (tid == 0) {
+      const unsigned field = 4u * (unsigned)xcd_actual(a.n_xcd);
+      __hip_atomic_fetch_add(gcnt, 1u << field, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      unsigned v = 0, n = 0;
+      for (int spin = 0; spin < (1 << 16); ++spin) {
+        v = __hip_atomic_load(gcnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // not from L1
+        n = 0;
 #pragma unroll
-      for (int x = 0; x < kXcds; ++x) arrived += (old >> (4 * x)) & 15u;
-      if (arrived != (unsigned)(S - 1)) continue;
-      if (lane == 0) {
-        a.tile_cnt[(size_t)mt * n_tiles + tile] = 0;                // clean for the next launch
-        if (old + (1u << my_field) != ((unsigned)S << my_field)) atomicOr(a.status, 1);
+        for (int x = 0; x < kXcds; ++x) n += (v >> (4 * x)) & 15u;
+        if (n >= (unsigned)S) break;
+        __builtin_amdgcn_s_sleep(1);
       }
-      asm volatile("buffer_inv sc0 sc1" ::: "memory");              // drop stale L1 / L2 lines
+      int bad = 0;
+      if (n < (unsigned)S) bad |= 2;                                  // gave up waiting
+      else if (v != ((unsigned)S << field)) bad |= 1;                 // slices on several XCDs
+      if (bad) atomicOr(a.status, bad);
+    }
+    __syncthreads();
+    asm volatile("buffer_inv sc0" ::: "memory");                      // drop stale L1 lines (the L2 is shared)
+    if (PRO == PRO_GAIN) {                   // row sums of all slices -> 1 / rms, once per workgroup
+      if (tid < kMTile) {
+        float part8[8], t = 0.f;
+#pragma unroll
+        for (int s2 = 0; s2 < 8; ++s2)
+          part8[s2] = a.sumsq[(((size_t)mt * G + g) * S + min(s2, S - 1)) * kMTile + tid];
+#pragma unroll
+        for (int s2 = 0; s2 < 8; ++s2) t += s2 < S ? part8[s2] : 0.f;
+        s_rstd[tid] = 1.0f / sqrtf(t / (float)K + a.eps);
+      }
+    }
 
-      f32x16_t t0 = {}, t1 = {};
-      const int ln = lane & 31;
-      // all (up to 8) slices are fetched at once, then added in slice order
-      const float4* pbase = reinterpret_cast<const float4*>(
-                                a.part + ((size_t)mt * n_tiles + tile) * S * kTileFloats) + lane;
-      float ssum[8];
-      float xres[32];                        // EPI_RESID: the residual rows, fetched with the partials
-      if (EPI == EPI_RESID) {
+    // Work item = one quad of one tile: the 8 rows x 32 columns that register quad `qd` of the
+    // partial-tile layout holds (rows 8*(qd%4) + 4*(lane/32) + 0..3, +32 for qd >= 4).  Items of
+    // the group are dealt round robin to (slice, wave): item i -> slice i % S, wave (i / S) % 4.
+    const int ln = lane & 31;
+    const int n_items = t_count * 8;
+    if (PRO == PRO_GAIN) __syncthreads();    // s_rstd is complete
+    for (int it0 = sp + S * wave; it0 < n_items; it0 += 4 * S * kRedBatch) {
+      float4 part[kRedBatch][8];
+      float xres[kRedBatch][4];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int m = m0 + 8 * (r >> 2) + rbase + (r & 3);
-          xres[r] = a.x_io[(size_t)min(m, a.M - 1) * a.N + tile * 32 + ln];
-          xres[r + 16] = a.x_io[(size_t)min(m + 32, a.M - 1) * a.N + tile * 32 + ln];
-        }
-      }
-      {
-        float4 buf[8][8];
+      for (int bi = 0; bi < kRedBatch; ++bi) {                        // all loads of the batch first
+        const int it = min(it0 + 4 * S * bi, n_items - 1);
+        const int tile = t_begin + (it >> 3), qd = it & 7;
+        const int row0 = 8 * (qd & 3) + rbase + 32 * (qd >> 2);
+        const float4* pb = reinterpret_cast<const float4*>(
+                               a.part + ((size_t)mt * n_tiles + tile) * S * kTileFloats) + qd * 64 + lane;
 #pragma unroll
         for (int s2 = 0; s2 < 8; ++s2) {
           const int sc = min(s2, S - 1);
-          const float4* pt = pbase + (size_t)sc * (kTileFloats / 4);
-#pragma unroll
-          for (int qd = 0; qd < 8; ++qd) buf[s2][qd] = pt[qd * 64];
-          if (PRO == PRO_GAIN) ssum[s2] = a.sumsq[(((size_t)mt * G + g) * S + sc) * kMTile + lane];
+          part[bi][s2] = pb[(size_t)sc * (kTileFloats / 4)];
         }
+        if (EPI == EPI_RESID) {
 #pragma unroll
-        for (int s2 = 0; s2 < 8; ++s2) {
+          for (int j = 0; j < 4; ++j)
+            xres[bi][j] = a.x_io[(size_t)min(m0 + row0 + j, a.M - 1) * a.N + tile * 32 + ln];
+        }
+      }
+#pragma unroll
+      for (int bi = 0; bi < kRedBatch; ++bi) {
+        const int it = it0 + 4 * S * bi;
+        if (it >= n_items) break;
+        const int tile = t_begin + (it >> 3), qd = it & 7;
+        const int row0 = 8 * (qd & 3) + rbase + 32 * (qd >> 2);
+        float v[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s2 = 0; s2 < 8; ++s2) {                              // fixed slice order
           const float keep = s2 < S ? 1.0f : 0.0f;
+          v[0] += keep * part[bi][s2].x; v[1] += keep * part[bi][s2].y;
+          v[2] += keep * part[bi][s2].z; v[3] += keep * part[bi][s2].w;
+        }
+        if (PRO == PRO_GAIN) {
 #pragma unroll
-          for (int qd = 0; qd < 4; ++qd) {
-            t0[4 * qd] += keep * buf[s2][qd].x;     t0[4 * qd + 1] += keep * buf[s2][qd].y;
-            t0[4 * qd + 2] += keep * buf[s2][qd].z; t0[4 * qd + 3] += keep * buf[s2][qd].w;
-            t1[4 * qd] += keep * buf[s2][qd + 4].x;     t1[4 * qd + 1] += keep * buf[s2][qd + 4].y;
-            t1[4 * qd + 2] += keep * buf[s2][qd + 4].z; t1[4 * qd + 3] += keep * buf[s2][qd + 4].w;
+          for (int j = 0; j < 4; ++j) v[j] *= s_rstd[row0 + j];
+        }
+        if (EPI == EPI_RESID) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            if (m0 + row0 + j < a.M)
+              a.x_io[(size_t)(m0 + row0 + j) * a.N + tile * 32 + ln] = xres[bi][j] + v[j];
+        }
+        if (EPI == EPI_SWIGLU) {             // lanes 0..15 gate, 16..31 up of the same column
+          const int F = a.N / 2;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const float up = __shfl_xor(v[j], 16, kWave);
+            if (ln < 16 && m0 + row0 + j < a.M)
+              a.act[(size_t)(m0 + row0 + j) * F + tile * 16 + ln] = v[j] / (1.0f + expf(-v[j])) * up;
+          }
+        }
+        if (EPI == EPI_QKV) {
+          const int tiles_per_mat = a.nh * 4;  // 128 rows per head = 4 tiles
+          const int which = tile / tiles_per_mat;                  // 0 q, 1 k, 2 v
+          const int head = (tile % tiles_per_mat) / 4, uq = tile % 4;
+          const int jr = 16 * uq + (ln & 15);                      // rotary pair index, 0..63
+          const int dcol = jr + 64 * (ln >> 4);                    // column inside the head
+          // angle in turns = position * theta^(-2j/128) / (2 pi)
+          const float turn_freq = exp2f(-(float)jr * (1.0f / 64.0f) * log2f(a.theta)) * 0.15915494309189535f;
+          const float sgn = (ln & 16) ? 1.0f : -1.0f;
+          const int D = a.nh * 128;
+          bf16_t* cache = which == 1 ? a.kc : a.vc;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int ml = row0 + j;
+            float val = v[j];
+            const float partner = __shfl_xor(val, 16, kWave);
+            if (which != 2) {
+              float turns = (float)s_pos[ml] * turn_freq;
+              turns -= floorf(turns);        // reduced to [0, 1) before the hardware sin / cos
+              val = val * __builtin_amdgcn_cosf(turns) + sgn * partner * __builtin_amdgcn_sinf(turns);
+            }
+            if (m0 + ml < a.M) {
+              if (which == 0)
+                a.q_out[(size_t)(m0 + ml) * D + head * 128 + dcol] = val;
+              else
+                cache[((size_t)s_crow[ml] + (size_t)head * a.cap) * 128 + dcol] = f32_to_bf16(val);
+            }
           }
         }
       }
-      if (PRO == PRO_GAIN) {                 // lane l: rstd of row l, then fetched per register
-        float t = 0.f;
-#pragma unroll
-        for (int s2 = 0; s2 < 8; ++s2) t += s2 < S ? ssum[s2] : 0.f;
-        const float rstd = 1.0f / sqrtf(t / (float)K + a.eps);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int m = 8 * (r >> 2) + rbase + (r & 3);
-          t0[r] *= __shfl(rstd, m, kWave);
-          t1[r] *= __shfl(rstd, m + 32, kWave);
-        }
-      }
-
-      if (EPI == EPI_RESID) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int m = m0 + 8 * (r >> 2) + rbase + (r & 3);
-          if (m < a.M) a.x_io[(size_t)m * a.N + tile * 32 + ln] = xres[r] + t0[r];
-          if (m + 32 < a.M) a.x_io[(size_t)(m + 32) * a.N + tile * 32 + ln] = xres[r + 16] + t1[r];
-        }
-      }
-      if (EPI == EPI_SWIGLU) {               // lanes 0..15 gate, 16..31 up of the same column
-        const int F = a.N / 2;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int m = m0 + 8 * (r >> 2) + rbase + (r & 3);
-          const float u0 = __shfl_xor(t0[r], 16, kWave), u1 = __shfl_xor(t1[r], 16, kWave);
-          if (ln < 16) {
-            if (m < a.M) a.act[(size_t)m * F + tile * 16 + ln] = t0[r] / (1.0f + expf(-t0[r])) * u0;
-            if (m + 32 < a.M)
-              a.act[(size_t)(m + 32) * F + tile * 16 + ln] = t1[r] / (1.0f + expf(-t1[r])) * u1;
-          }
-        }
-      }
-      if (EPI == EPI_QKV) {
-        const int tiles_per_mat = a.nh * 4;  // 128 rows per head = 4 tiles
-        const int which = tile / tiles_per_mat;                  // 0 q, 1 k, 2 v
-        const int head = (tile % tiles_per_mat) / 4, uq = tile % 4;
-        const int j = 16 * uq + (ln & 15);                       // rotary pair index, 0..63
-        const int dcol = j + 64 * (ln >> 4);                     // column inside the head
-        // angle in turns = position * theta^(-2j/128) / (2 pi)
-        const float turn_freq = exp2f(-(float)j * (1.0f / 64.0f) * log2f(a.theta)) * 0.15915494309189535f;
-        const float sgn = (ln & 16) ? 1.0f : -1.0f;
-        const int D = a.nh * 128;
-        bf16_t* cache = which == 1 ? a.kc : a.vc;
-#pragma unroll
-        for (int r = 0; r < 32; ++r) {
-          const int ml = 8 * ((r & 15) >> 2) + rbase + (r & 3) + 32 * (r >> 4);
-          float v = r < 16 ? t0[r & 15] : t1[r & 15];
-          const float partner = __shfl_xor(v, 16, kWave);
-          if (which != 2) {
-            float turns = (float)s_pos[ml] * turn_freq;
-            turns -= floorf(turns);          // reduced to [0, 1) before the hardware sin / cos
-            v = v * __builtin_amdgcn_cosf(turns) + sgn * partner * __builtin_amdgcn_sinf(turns);
-          }
-          if (m0 + ml < a.M) {
-            if (which == 0)
-              a.q_out[(size_t)(m0 + ml) * D + head * 128 + dcol] = v;
-            else
-              cache[((size_t)s_crow[ml] + (size_t)head * a.cap) * 128 + dcol] = f32_to_bf16(v);
-          }
-        }
-      }
+    }
+    // the last workgroup to get here clears the group's two words for the next launch
+    if (tid == 0 &&
+        __hip_atomic_fetch_add(gcnt + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(S - 1)) {
+      gcnt[0] = 0;
+      gcnt[1] = 0;
     }
   }
 }
