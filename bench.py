@@ -88,6 +88,9 @@ def main():
     ap.add_argument("--r", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers (invalid as a result)")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device copy (calibrates rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters in the same profile)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures ONE GPU only (the tree-verification pass of one "
@@ -137,6 +140,12 @@ def main():
     ms_per_step = dt / args.steps * 1e3
     tokens_per_s = B * T / (dt / args.steps)
     accepted = vp.accepted_len.cpu().tolist()
+    accepted_by_r = {}
+    for r in cfg.r_values:
+        vp.accept(r)
+        torch.cuda.synchronize()
+        accepted_by_r[str(r)] = vp.accepted_len.cpu().tolist()
+    assert vp.placement_status() == 0, "GEMM placement check failed (see SV_WS_STATUS)"
 
     # per-kernel durations with HIP events around single launches, same stream, same inputs
     n_ev = sv.SV_N_TIMING_EVENTS
@@ -174,14 +183,19 @@ def main():
                    "hidden": H, "layers": L, "tree_nodes": T, "prefix": int(prefix_len[0])},
         "step_hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "step_algorithmic_bytes": step_bytes,
-        "accepted_len": accepted,
+        "accepted_len": accepted, "accepted_len_by_r": accepted_by_r,
         "kernel_ms_per_step": per_step_ms,
-        "roofline": {"bound": "hbm", "kernel": "gemm_skinny_bf16 (4 launches per layer)",
+        "roofline": {"bound": "hbm", "kernel": "gemm_stream_bf16 (4 launches per layer: q/k/v, o, gate/up, down)",
                      "achieved": gemm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": gemm_gbs / HBM_PEAK_GBS, "traffic": None,
                      "bytes_per_launch_avg": weights_total / (4 * L),
                      "avg_launch_us": gemm_ms * 1e3 / (4 * L)},
     }
+    if args.calib_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, wl)
     print(json.dumps(out), flush=True)

@@ -93,9 +93,15 @@ static WorkspaceLayout workspace_layout(const sv_model_cfg& c, int m_rows, int n
   L.attn = o;        o = align_up(o + mp * D * 4, kAlign);
   L.act = o;         o = align_up(o + mp * F * 4, kAlign);
   L.head_z = o;      o = align_up(o + mp * H * 4, kAlign);
-  L.head_logits = o; o = align_up(o + mp * (size_t)(n_scored > 0 ? n_scored : 0) * 4, kAlign);
+  L.head_logits = o; o = align_up(o + mp * (size_t)(n_scored > 0 ? n_scored : 0) * 4 * 16, kAlign);   // up to 16 K-slice planes
   L.total = o;
   return L;
+}
+
+// K slices of the LM-head GEMM (it has few output tiles, so the reduction is spread out).
+static int head_planes(int hidden) {
+  int p = hidden / 256;
+  return p < 1 ? 1 : (p > 16 ? 16 : p);
 }
 
 static inline int launch_status() { return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_LAUNCH; }
@@ -268,11 +274,14 @@ static int head_t(const sv_model_cfg& c, const T* g_final, const T* w_lm, const 
   const WorkspaceLayout wl = workspace_layout(c, n_rows, hi - lo);
   const int H = c.hidden, n = hi - lo;
   float* z = (float*)(ws + wl.head_z);
-  float* logits = out_logits ? out_logits : (float*)(ws + wl.head_logits);
+  float* parts = (float*)(ws + wl.head_logits);
+  const int planes = head_planes(H);
+  const size_t plane = (size_t)wl.m_pad * n;
   rmsnorm_rows_tg<T, float><<<n_rows, 256, 0, st>>>(x, g_final, z, H, c.rms_eps);
-  dim3 grid(ceil_div(n, 64), ceil_div(n_rows, 64), 1);
-  gemm_nt_fma<float, T><<<grid, 256, 0, st>>>(z, H, w_lm + (size_t)lo * H, H, logits, n, 0, n_rows, n, H);
-  argmax_rows<<<n_rows, 64, 0, st>>>(logits, n, lo, out_token);
+  dim3 grid(ceil_div(n, 64), ceil_div(n_rows, 64), planes);   // K cut into `planes` slices
+  gemm_nt_fma<float, T><<<grid, 256, 0, st>>>(z, H, w_lm + (size_t)lo * H, H, parts, n, plane,
+                                              n_rows, n, H);
+  argmax_rows<<<n_rows, 64, 0, st>>>(parts, planes, plane, out_logits, n, lo, out_token);
   return launch_status();
 }
 

@@ -269,16 +269,21 @@ __global__ __launch_bounds__(256) void swiglu_rows(const float* __restrict__ par
 
 // ---------------------------------------------------------------------------------------
 // Greedy choice per row: index of the largest logit, the lowest index on exact ties
-// (NaN never wins).  One wavefront per row.  grid = rows, block = 64.
+// (NaN never wins).  The logits arrive as `planes` K-slices of the head GEMM, [planes][rows][n]
+// with plane stride `plane`; they are added in plane order, the sums are written to
+// `logits_out` ([rows][n], may be NULL) and scanned.  One wavefront per row.
+// grid = rows, block = 64.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void argmax_rows(const float* __restrict__ logits, int n,
-                                                  int token_lo, int32_t* __restrict__ out) {
+__global__ __launch_bounds__(64) void argmax_rows(const float* __restrict__ parts, int planes,
+                                                  size_t plane, float* __restrict__ logits_out,
+                                                  int n, int token_lo, int32_t* __restrict__ out) {
   const size_t row = blockIdx.x;
-  const float* r = logits + row * n;
   float best = -INFINITY;
   int bi = 0x7fffffff;
   for (int i = threadIdx.x; i < n; i += 64) {
-    const float v = r[i];
+    float v = 0.f;
+    for (int p = 0; p < planes; ++p) v += parts[(size_t)p * plane + row * n + i];
+    if (logits_out) logits_out[row * n + i] = v;
     if (v > best || (v == best && i < bi)) {
       best = v;
       bi = i;
