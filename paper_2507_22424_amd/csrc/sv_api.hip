@@ -207,7 +207,7 @@ static int verify_layer_bf16(const sv_model_cfg& c, const char* packed, float* x
   gemm_stream_bf16<PRO_GAIN, EPI_QKV><<<grid, 256, 0, st>>>(a);
   mark(1);
   mark(2);
-  tree_attention_mfma<<<dim3(B * ceil_div(T_, kAttQ), c.n_heads), 256, 0, st>>>(
+  tree_attention_mfma<4><<<dim3(B * ceil_div(T_, kAttQ), c.n_heads), 256, 0, st>>>(
       q, (const bf16_t*)kv.k, (const bf16_t*)kv.v, kv.prefix_len, kv.prefix_len_max,
       tree.anc_mask, tree.n_words, T_, c.n_heads, kv.capacity, attn);
   mark(3);

@@ -45,15 +45,18 @@ __device__ inline void split8(const float* v, bf16x8_t& hi, bf16x8_t& lo) {
   lo = __builtin_bit_cast(bf16x8_t, l);
 }
 
-// grid = (B * ceil(T / 16), n_heads), block = 256.  head_dim = 128.
+// grid = (B * ceil(T / 16), n_heads), block = 64 * NW (NW waves split the keys; at 340 keys the
+// kernel is latency bound and 8 waves measured slower than 4).
+// head_dim = 128.
 // q: float32 [M, nh*128] (rotated);  kc, vc: bf16 [B][nh][cap][128];  out: float32 [M, nh*128].
-__global__ __launch_bounds__(256) void tree_attention_mfma(
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void tree_attention_mfma(
     const float* __restrict__ q, const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc,
     const int32_t* __restrict__ prefix_len, int p_max, const uint64_t* __restrict__ anc,
     int n_words, int T, int nh, int cap, float* __restrict__ out) {
   // per wave: transposed V tile [128 d][32 keys] with padded rows; reused for the merge
-  __shared__ __attribute__((aligned(16))) unsigned char lds_raw[4 * 128 * kVtPitch];
-  __shared__ float s_m[4][kAttQ], s_l[4][kAttQ];
+  __shared__ __attribute__((aligned(16))) unsigned char lds_raw[NW * 128 * kVtPitch];
+  __shared__ float s_m[NW][kAttQ], s_l[NW][kAttQ];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 4, c = lane & 15;      // lane group (0..3), column = query
   const int qblocks = (T + kAttQ - 1) / kAttQ;
@@ -112,7 +115,7 @@ __global__ __launch_bounds__(256) void tree_attention_mfma(
 
   int t = wave;
   if (t < ntiles) load_tile(t);
-  for (; t < ntiles; t += 4) {
+  for (; t < ntiles; t += NW) {
     // ---- S^T = K Q^T for the two 16-key sub-tiles ----
     f32x4_t s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -149,7 +152,7 @@ __global__ __launch_bounds__(256) void tree_attention_mfma(
       *reinterpret_cast<unsigned*>(dst + 3 * kVtPitch) = (e_w1 >> 16) | (o_w1 & 0xffff0000u);
     }
     // prefetch the next tile of this wave while the rest of this one is computed
-    const int tn = t + 4;
+    const int tn = t + NW;
     const int key0 = t * kAttKeys;
     if (tn < ntiles) load_tile(tn);
 
@@ -202,7 +205,7 @@ __global__ __launch_bounds__(256) void tree_attention_mfma(
 
   // ---- merge the four waves ----
   __syncthreads();
-  float* om = reinterpret_cast<float*>(lds_raw);          // [4 waves][128 d][16 q] float32 = 32 KiB
+  float* om = reinterpret_cast<float*>(lds_raw);          // [NW waves][128 d][16 q] float32
   if (g == 0) {
     s_m[wave][c] = m_run;
     s_l[wave][c] = l_run;
@@ -212,21 +215,26 @@ __global__ __launch_bounds__(256) void tree_attention_mfma(
 #pragma unroll
     for (int r = 0; r < 4; ++r) om[(wave * 128 + 16 * dt + 4 * g + r) * kAttQ + c] = o[dt][r];
   __syncthreads();
-  // wave w finishes d rows 32w .. 32w+31: lane -> (d = 32w + lane % 32, queries (lane / 32) * 8 .. + 7)
-  const int d = 32 * wave + (lane & 31);
+  // the first four waves finish d rows 32w .. 32w+31: lane -> (d = 32w + lane % 32, queries
+  // (lane / 32) * 8 .. + 7)
+  if (wave < 4) {
+    const int d = 32 * wave + (lane & 31);
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int qq = (lane >> 5) * 8 + i;
-    const float m_all = fmaxf(fmaxf(s_m[0][qq], s_m[1][qq]), fmaxf(s_m[2][qq], s_m[3][qq]));
-    float num = 0.f, den = 0.f;
+    for (int i = 0; i < 8; ++i) {
+      const int qq = (lane >> 5) * 8 + i;
+      float m_all = s_m[0][qq];
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const float sc = __expf(s_m[w][qq] - m_all);
-      num += sc * om[(w * 128 + d) * kAttQ + qq];
-      den += sc * s_l[w][qq];
+      for (int w = 1; w < NW; ++w) m_all = fmaxf(m_all, s_m[w][qq]);
+      float num = 0.f, den = 0.f;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        const float sc = __expf(s_m[w][qq] - m_all);
+        num += sc * om[(w * 128 + d) * kAttQ + qq];
+        den += sc * s_l[w][qq];
+      }
+      const int tnode = qb * kAttQ + qq;
+      if (tnode < T) out[((size_t)b * T + tnode) * D + h * 128 + d] = num / den;
     }
-    const int tnode = qb * kAttQ + qq;
-    if (tnode < T) out[((size_t)b * T + tnode) * D + h * 128 + d] = num / den;
   }
 }
 

@@ -377,7 +377,6 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
 #pragma unroll
         for (int x = 0; x < kXcds; ++x) n += (v >> (4 * x)) & 15u;
         if (n >= (unsigned)S) break;
-        __builtin_amdgcn_s_sleep(1);
       }
       int bad = 0;
       if (n < (unsigned)S) bad |= 2;                                  // gave up waiting
