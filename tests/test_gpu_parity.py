@@ -165,3 +165,64 @@ def test_c3_full_pass_32_layers():
     n_ties = check_forward(s, TOL["bf16"])
     check_accept_paths(s, wl.C3.r_values)
     say(f"[C3] tolerated argmax near-ties: {n_ties} of {len(s.ref_token)} nodes")
+
+
+# ---- robustness of the HIP path itself -----------------------------------------------------
+
+def _small_bf16(T=26, B=2, P=70, layers=2, name="bf16-robust"):
+    return wl.C2.scaled(name=name, index=31, n_layers=layers, hidden=512, n_heads=4, head_dim=128,
+                        mlp_dim=1536, vocab=1024, n_bins=256, tree_nodes=T, n_episodes=B,
+                        prefix_lo=max(0, P - 20), prefix_hi=P, max_children=4, r_values=(0, 4))
+
+
+def test_results_are_bit_reproducible_and_independent_of_workspace_contents():
+    """Split-K partial sums are added in a fixed order: two runs give identical bits, also after
+    the scratch workspace was filled with NaN patterns (only sv_workspace_init's counters count)."""
+    s = SideBySide(_small_bf16(), per_layer=False)
+    first = (s.gpu_logits.copy(), s.gpu_x.copy(), s.gpu_token.copy())
+    s.gpu.workspace.fill_(0xFF)                      # NaN everywhere, counters included
+    sv.sv_workspace_init(s.gpu.cfg, s.gpu.B, s.gpu.T, s.gpu.n_scored, s.gpu.workspace)
+    for _ in range(3):
+        s.gpu.forward(want_logits=True)
+        torch.cuda.synchronize()
+        assert np.array_equal(s.gpu.logits.cpu().numpy(), first[0])
+        assert np.array_equal(s.gpu.x.cpu().numpy(), first[1])
+        assert np.array_equal(s.gpu.token.cpu().numpy(), first[2])
+    assert s.gpu.placement_status() == 0
+
+
+@pytest.mark.parametrize("T,B,P", [(1, 1, 1), (5, 2, 0), (17, 1, 3), (64, 1, 31), (65, 1, 32)])
+def test_bf16_degenerate_trees_and_prefixes(T, B, P):
+    """Root-only tree, empty prefix (a node then sees its root path only), tile-boundary sizes."""
+    cfg = _small_bf16(T=T, B=B, P=P, name=f"bf16-edge-T{T}-P{P}").scaled(prefix_lo=P, prefix_hi=P)
+    s = SideBySide(cfg)
+    check_forward(s, TOL["bf16"])
+    check_accept_paths(s, (0, 2))
+
+
+def test_accept_depth_cap_below_tree_depth():
+    """A node deeper than d_cap counts as rejected: accepted' = accepted and depth <= d_cap."""
+    rng = np.random.default_rng(77)
+    B, T, lo, nb = 4, 60, 31744, 256
+    parents = [wl.draft_tree(T, 7, 4, 7, rng) for _ in range(B)]
+    tree = sv.DeviceTree(np.concatenate(parents), B, T, 7)
+    target = lo + rng.integers(0, nb, size=B * T)
+    draft = np.concatenate([wl.noisy_draft_tokens(wl.C3.scaled(index=40 + b), 0, parents[b],
+                                                  target[b * T:(b + 1) * T], 3) for b in range(B)])
+    d_cap = 3
+    out = dict(mask=torch.zeros(B * T, dtype=torch.uint8, device="cuda"),
+               length=torch.zeros(B, dtype=torch.int32, device="cuda"),
+               best=torch.zeros(B, dtype=torch.int32, device="cuda"),
+               path=torch.zeros(B, d_cap + 1, dtype=torch.int32, device="cuda"),
+               tokens=torch.zeros(B, d_cap + 1, dtype=torch.int32, device="cuda"))
+    sv.sv_relaxed_accept(tree.struct, torch.from_numpy(draft.astype(np.int32)).cuda(),
+                         torch.from_numpy(target.astype(np.int32)).cuda(), lo, nb, 4, B, d_cap,
+                         out["mask"], out["length"], out["best"], out["path"], out["tokens"])
+    torch.cuda.synchronize()
+    mask = out["mask"].cpu().numpy().reshape(B, T).astype(bool)
+    for b in range(B):
+        ref = vo.relaxed_accept(parents[b], draft[b * T:(b + 1) * T], target[b * T:(b + 1) * T], lo, nb, 4)
+        depth, _ = vo.tree_structure(parents[b])
+        want = ref["mask"] & (depth <= d_cap)
+        assert mask[b].tolist() == want.tolist()
+        assert int(out["length"][b]) == int(depth[want].max())
