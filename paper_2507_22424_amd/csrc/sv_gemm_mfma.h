@@ -52,7 +52,7 @@ constexpr int kChunkBlks = 4;    // K blocks of X resident in LDS at a time (512
 constexpr int kPieceFrags = 16;  // fragments per register buffer (16 KiB in flight per wave)
 constexpr int kTileFloats = kMTile * kFragRows;   // one partial tile, [64][32] float32
 constexpr int kXcds = 8;
-constexpr int kRedBatch = 3;       // reduction work items whose loads are in flight together
+constexpr int kRedBatch = 6;       // reduction work items whose loads are in flight together
 
 enum { PRO_PLAIN = 0, PRO_GAIN = 1 };
 enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
@@ -408,7 +408,8 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
       float xres[kRedBatch][4];
 #pragma unroll
       for (int bi = 0; bi < kRedBatch; ++bi) {                        // all loads of the batch first
-        const int it = min(it0 + 4 * S * bi, n_items - 1);
+        const int it = it0 + 4 * S * bi;
+        if (it >= n_items) break;
         const int tile = t_begin + (it >> 3), qd = it & 7;
         const int row0 = 8 * (qd & 3) + rbase + 32 * (qd >> 2);
         const float4* pb = reinterpret_cast<const float4*>(

@@ -226,3 +226,20 @@ def test_accept_depth_cap_below_tree_depth():
         want = ref["mask"] & (depth <= d_cap)
         assert mask[b].tolist() == want.tolist()
         assert int(out["length"][b]) == int(depth[want].max())
+
+
+def test_full_vocabulary_head_variant():
+    """vocab_lo = 0: the whole LM head is scored (not the hot path; tokens may leave the action
+    range, which the acceptance rule then rejects on both sides)."""
+    cfg = _small_bf16(T=26, B=2, P=40, name="bf16-fullvocab")
+    s = SideBySide(cfg, full_vocab=True, per_layer=False)
+    assert s.gpu_logits.shape == (52, cfg.vocab)
+    assert s.logit_err.max() <= TOL["bf16"]
+    s.check_gpu_argmax_of_own_logits()
+    ok, bad = s.tolerated_ties(TOL["bf16"])
+    assert bad == 0
+    T = cfg.tree_nodes
+    draft = np.concatenate([wl.uniform_draft_tokens(cfg, b) for b in range(cfg.n_episodes)])
+    for r in (0, 300):
+        g, refs = s.accept_both(r, draft, s.ref_token)
+        assert_accept_equal(g, refs, cfg.max_depth)
