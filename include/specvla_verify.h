@@ -204,6 +204,21 @@ int sv_relaxed_accept(const sv_tree *tree, const int32_t *draft_token,
                       int d_cap, uint8_t *accept_mask, int32_t *accepted_len,
                       int32_t *best_node, int32_t *path, int32_t *out_tokens, void *stream);
 
+/* Between two verification passes (the outer loop of Alg. 1): makes the accepted path part of
+ * the prefix of ONE layer's cache.  The K/V rows of path[b][1..accepted_len[b]] (appended by
+ * sv_verify_layer at rows prefix_len[b] + node) move to rows prefix_len[b] + 1 .. + len; the
+ * root already sits at row prefix_len[b].  Call once per layer with that layer's kv view and
+ * the path / accepted_len that sv_relaxed_accept wrote ([device] int32 [B, d_cap+1] / [B]); then
+ * call sv_advance_prefix once.  The verifier's bonus token out_tokens[b][len] is the root of the
+ * next tree.  kv->prefix_len is only read here. */
+int sv_commit_path(const sv_model_cfg *cfg, const sv_kv_view *kv, int T, const int32_t *path,
+                   const int32_t *accepted_len, int B, int d_cap, void *stream);
+
+/* prefix_len[b] += accepted_len[b] + 1 on the device ([device] int32[B] each).  The caller
+ * raises its host-side bound kv.prefix_len_max by d_cap + 1 (or by what it reads back). */
+int sv_advance_prefix(int32_t *prefix_len, const int32_t *accepted_len, int B, int d_cap,
+                      void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,8 @@ SV_WS_ATTN_OUT, SV_WS_Q, SV_WS_STATUS = 0, 1, 2
 EXPORTS = ("sv_version", "sv_strerror", "sv_tree_build_masks", "sv_packed_layer_bytes",
            "sv_pack_layer", "sv_workspace_bytes", "sv_workspace_init", "sv_workspace_region",
            "sv_verify_layer",
-           "sv_verify_layer_timed", "sv_action_head_argmax", "sv_relaxed_accept")
+           "sv_verify_layer_timed", "sv_action_head_argmax", "sv_relaxed_accept",
+           "sv_commit_path", "sv_advance_prefix")
 SV_N_TIMING_EVENTS = 9
 
 
@@ -87,6 +88,9 @@ def lib() -> C.CDLL:
         l.sv_relaxed_accept.argtypes = [C.POINTER(Tree), C.c_void_p, C.c_void_p, C.c_int, C.c_int,
                                         C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        l.sv_commit_path.argtypes = [C.POINTER(ModelCfg), C.POINTER(KvView), C.c_int, C.c_void_p,
+                                     C.c_void_p, C.c_int, C.c_int, C.c_void_p]
+        l.sv_advance_prefix.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
         _lib = l
     return _lib
 
@@ -238,6 +242,22 @@ def sv_relaxed_accept(tree: Tree, draft_token: torch.Tensor, target_token: torch
         _dev(accept_mask, torch.uint8, "accept_mask"), _dev(accepted_len, torch.int32, "accepted_len"),
         _dev(best_node, torch.int32, "best_node"), _dev(path, torch.int32, "path"),
         _dev(out_tokens, torch.int32, "out_tokens"), _stream(stream)), "sv_relaxed_accept")
+
+
+def sv_commit_path(cfg: ModelCfg, kv: KvView, T: int, path: torch.Tensor,
+                   accepted_len: torch.Tensor, B: int, d_cap: int, stream=None) -> None:
+    if path.numel() != B * (d_cap + 1) or accepted_len.numel() != B:
+        raise ValueError("commit_path: tensor sizes do not match B, d_cap")
+    _check(lib().sv_commit_path(C.byref(cfg), C.byref(kv), T, _dev(path, torch.int32, "path"),
+                                _dev(accepted_len, torch.int32, "accepted_len"), B, d_cap,
+                                _stream(stream)), "sv_commit_path")
+
+
+def sv_advance_prefix(prefix_len: torch.Tensor, accepted_len: torch.Tensor, B: int, d_cap: int,
+                      stream=None) -> None:
+    _check(lib().sv_advance_prefix(_dev(prefix_len, torch.int32, "prefix_len"),
+                                   _dev(accepted_len, torch.int32, "accepted_len"), B, d_cap,
+                                   _stream(stream)), "sv_advance_prefix")
 
 
 # ---- holders that keep the device tensors behind the C structs alive -------------------

@@ -81,5 +81,44 @@ __global__ __launch_bounds__(128) void relaxed_accept_kernel(
   }
 }
 
+// Commit of the accepted path (the step of Alg. 1 between two verification passes): the K/V
+// rows of the accepted nodes, appended at cache rows P + node, move to rows P + depth, so that
+// the cache again holds one contiguous prefix; the root (depth 0) already sits at row P.
+// Moves run in increasing depth with a barrier in between: node index >= depth, so a row is
+// read before a later move overwrites it.  grid = (B, n_heads), block = 128.
+template <typename TKV>
+__global__ __launch_bounds__(128) void commit_path_kernel(
+    TKV* __restrict__ kc, TKV* __restrict__ vc, const int32_t* __restrict__ prefix_len, int p_max,
+    int cap, int T, int nh, int d, const int32_t* __restrict__ path,
+    const int32_t* __restrict__ accepted_len, int d_cap) {
+  const int b = blockIdx.x, h = blockIdx.y;
+  int P = prefix_len[b];
+  P = P < 0 ? 0 : (P > p_max ? p_max : P);
+  int len = accepted_len[b];
+  len = len < 0 ? 0 : (len > d_cap ? d_cap : len);
+  TKV* kb = kc + ((size_t)b * nh + h) * cap * d;
+  TKV* vb = vc + ((size_t)b * nh + h) * cap * d;
+  for (int i = 1; i <= len; ++i) {
+    const int node = path[(size_t)b * (d_cap + 1) + i];
+    if (node > i && node < T) {              // node == i: already in place
+      for (int e = threadIdx.x; e < d; e += 128) {
+        kb[(size_t)(P + i) * d + e] = kb[(size_t)(P + node) * d + e];
+        vb[(size_t)(P + i) * d + e] = vb[(size_t)(P + node) * d + e];
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// prefix_len[b] += accepted_len[b] + 1 (the root and the accepted draft tokens are now prefix).
+__global__ void advance_prefix_kernel(int32_t* __restrict__ prefix_len,
+                                      const int32_t* __restrict__ accepted_len, int B, int d_cap) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  int len = accepted_len[b];
+  len = len < 0 ? 0 : (len > d_cap ? d_cap : len);
+  prefix_len[b] += len + 1;
+}
+
 }  // namespace sv
 #endif

@@ -483,4 +483,34 @@ int sv_relaxed_accept(const sv_tree* tree, const int32_t* draft_token,
   return launch_status();
 }
 
+int sv_commit_path(const sv_model_cfg* cfg, const sv_kv_view* kv, int T, const int32_t* path,
+                   const int32_t* accepted_len, int B, int d_cap, void* stream) {
+  const int rc = check_cfg(cfg);
+  if (rc != SV_OK) return rc;
+  if (!kv || !kv->k || !kv->v || !kv->prefix_len || !path || !accepted_len) return SV_ERR_NULL;
+  if (B < 1 || B > (1 << 15) || T < 1 || T > SV_MAX_TREE_NODES || d_cap < 0 || d_cap > SV_MAX_DEPTH)
+    return SV_ERR_SHAPE;
+  if (kv->prefix_len_max < 0 || (long long)kv->capacity < (long long)kv->prefix_len_max + T)
+    return SV_ERR_SHAPE;
+  const dim3 grid(B, cfg->n_heads);
+  if (cfg->dtype == SV_F32)
+    commit_path_kernel<float><<<grid, 128, 0, (hipStream_t)stream>>>(
+        (float*)kv->k, (float*)kv->v, kv->prefix_len, kv->prefix_len_max, kv->capacity, T,
+        cfg->n_heads, cfg->head_dim, path, accepted_len, d_cap);
+  else
+    commit_path_kernel<bf16_t><<<grid, 128, 0, (hipStream_t)stream>>>(
+        (bf16_t*)kv->k, (bf16_t*)kv->v, kv->prefix_len, kv->prefix_len_max, kv->capacity, T,
+        cfg->n_heads, cfg->head_dim, path, accepted_len, d_cap);
+  return launch_status();
+}
+
+int sv_advance_prefix(int32_t* prefix_len, const int32_t* accepted_len, int B, int d_cap,
+                      void* stream) {
+  if (!prefix_len || !accepted_len) return SV_ERR_NULL;
+  if (B < 1 || B > (1 << 15) || d_cap < 0 || d_cap > SV_MAX_DEPTH) return SV_ERR_SHAPE;
+  advance_prefix_kernel<<<(B + 63) / 64, 64, 0, (hipStream_t)stream>>>(prefix_len, accepted_len, B,
+                                                                       d_cap);
+  return launch_status();
+}
+
 }  // extern "C"

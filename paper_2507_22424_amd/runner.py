@@ -17,7 +17,7 @@ from .workload import VerifyConfig
 
 class VerifyPass:
     def __init__(self, wc: VerifyConfig, prefix_len: Sequence[int], parent: np.ndarray,
-                 full_vocab: bool = False, device: str = "cuda"):
+                 full_vocab: bool = False, device: str = "cuda", extra_capacity: int = 0):
         if not torch.cuda.is_available():
             raise RuntimeError("VerifyPass needs a GPU; there is no CPU path")
         self.wc = wc
@@ -32,7 +32,7 @@ class VerifyPass:
         self.n_scored = self.vocab_hi - self.vocab_lo
         self.tree = sv.DeviceTree(parent, self.B, self.T, self.d_cap, device)
         pl = np.asarray(prefix_len, dtype=np.int32)
-        self.capacity = int(-(-(int(pl.max()) + self.T) // 64) * 64)
+        self.capacity = int(-(-(int(pl.max()) + self.T + extra_capacity) // 64) * 64)
         self.kv = [sv.KvCache(self.cfg, self.B, self.capacity, pl, device)
                    for _ in range(wc.n_layers)]
         self.packed: List[Optional[torch.Tensor]] = [None] * wc.n_layers
@@ -102,6 +102,23 @@ class VerifyPass:
     def step(self, r: int, want_logits: bool = False) -> None:
         self.forward(want_logits=want_logits)
         self.accept(r)
+
+    def set_tree(self, parent: np.ndarray) -> None:
+        """New draft trees (same B, T) for the next step."""
+        self.tree = sv.DeviceTree(parent, self.B, self.T, self.d_cap, self.device)
+
+    def commit(self) -> None:
+        """Make the accepted paths part of the prefix in every layer (outer loop of Alg. 1)."""
+        for l in range(self.wc.n_layers):
+            sv.sv_commit_path(self.cfg, self.kv[l].struct, self.T, self.path, self.accepted_len,
+                              self.B, self.d_cap)
+        # all layers share the prefix lengths of layer 0's holder
+        sv.sv_advance_prefix(self.kv[0].prefix_len, self.accepted_len, self.B, self.d_cap)
+        for l in range(self.wc.n_layers):
+            if l > 0:
+                self.kv[l].prefix_len.copy_(self.kv[0].prefix_len)
+            self.kv[l].struct.prefix_len_max = min(self.kv[l].struct.prefix_len_max + self.d_cap + 1,
+                                                   self.capacity - self.T)
 
     def placement_status(self) -> int:
         """0 unless a GEMM saw the slices of one tile on different XCDs (see SV_WS_STATUS)."""

@@ -13,6 +13,8 @@ from oracle import verify_oracle as vo
 from paper_2507_22424_amd import binding as sv
 from paper_2507_22424_amd import workload as wl
 
+from paper_2507_22424_amd.runner import VerifyPass
+
 from parity_utils import SideBySide, assert_accept_equal, say
 
 pytestmark = pytest.mark.gpu
@@ -243,3 +245,96 @@ def test_full_vocabulary_head_variant():
     for r in (0, 300):
         g, refs = s.accept_both(r, draft, s.ref_token)
         assert_accept_equal(g, refs, cfg.max_depth)
+
+
+def test_multi_step_loop_with_kv_commit_reproduces_greedy_decoding():
+    """The outer loop of Alg. 1 on the GPU with strict acceptance (r = 0): verify a (mock-)drafted
+    tree, take the accepted tokens plus the verifier's own token, commit the path's K/V rows,
+    continue from the new root - the emitted sequence must be the oracle's greedy decoding."""
+    from oracle import sequential_decode as seq
+    cfg = wl.C1.scaled(name="loop-f32", index=12, n_layers=2, hidden=128, n_heads=2, head_dim=64,
+                       mlp_dim=192, vocab=96, n_bins=32, prefix_lo=11, prefix_hi=11,
+                       tree_nodes=12, max_depth=4, max_children=3, spine_lo=3)
+    f64 = lambda t: t.to(torch.float64).numpy()
+    P0, n_emit = 11, 9
+    weights = [wl.layer_weights(cfg, l) for l in range(cfg.n_layers)]
+    kvs = [wl.prefix_kv(cfg, 0, l, P0) for l in range(cfg.n_layers)]
+    head = wl.head_weights(cfg)
+    E = wl.embedding_table(cfg)
+    lo = cfg.action_lo
+    rng = np.random.default_rng(5)
+    root_tok = lo + 3
+    greedy = seq.greedy_decode(f64(E), root_tok, n_emit, [{k: f64(v) for k, v in w.items()} for w in weights],
+                               [(f64(k), f64(v)) for k, v in kvs], f64(head["g_final"]),
+                               f64(head["w_lm"]), lo, cfg.n_heads, cfg.rms_eps, cfg.rope_theta)
+
+    parent = wl.draft_tree(cfg.tree_nodes, cfg.max_depth, cfg.max_children, 3, rng)
+    vp = VerifyPass(cfg, [P0], parent, extra_capacity=n_emit + cfg.max_depth + 2)
+    for l in range(cfg.n_layers):
+        vp.load_layer(l, weights[l])
+        vp.load_prefix(l, 0, *kvs[l])
+    vp.load_head(head["g_final"], head["w_lm"])
+
+    emitted, lengths = [], []
+    while len(emitted) < n_emit:
+        parent = wl.draft_tree(cfg.tree_nodes, cfg.max_depth, cfg.max_children, 3, rng)
+        vp.set_tree(parent)
+        draft = lo + rng.integers(0, cfg.n_bins, size=cfg.tree_nodes)
+        draft[0] = root_tok
+        # mock drafter: plant a prefix of the true continuation on the first-child path
+        node, k = 0, len(emitted)
+        for _ in range(int(rng.integers(0, cfg.max_depth + 1))):
+            kids = [c for c in range(cfg.tree_nodes) if parent[c] == node]
+            if not kids or k >= n_emit:
+                break
+            node = kids[0]
+            draft[node] = greedy[k]
+            k += 1
+        vp.set_hidden(E[torch.from_numpy(draft)])
+        vp.set_draft(draft)
+        vp.step(0)
+        torch.cuda.synchronize()
+        n = int(vp.accepted_len[0])
+        out = vp.out_tokens[0, :n + 1].tolist()
+        emitted += out
+        lengths.append(n)
+        vp.commit()
+        root_tok = out[-1]
+    say(f"[loop-f32] accepted lengths per step {lengths}, emitted {emitted[:n_emit]}")
+    assert emitted[:n_emit] == greedy[:n_emit]
+    assert max(lengths) >= 1                       # the planted drafts were really accepted
+    assert int(vp.kv[0].prefix_len[0]) == P0 + len(emitted)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_commit_path_moves_exactly_the_accepted_rows(dtype):
+    """sv_commit_path: the K/V row of the accepted node at depth i lands at prefix_len + i, every
+    other row below prefix_len + accepted_len + 1 keeps its bits; sv_advance_prefix adds
+    accepted_len + 1 (outer loop of Alg. 1)."""
+    from paper_2507_22424_amd import binding as sv
+    B, T, d_cap, nh, d = 3, 20, 5, 4, 128
+    cfg = sv.ModelCfg(sv.SV_F32 if dtype == "f32" else sv.SV_BF16, nh * d, nh, d, 256, 512, 1e-5, 1e4)
+    prefix = [7, 0, 33]
+    cap = 64
+    kv = sv.KvCache(cfg, B, cap, prefix)
+    g = torch.Generator().manual_seed(11)
+    kv.k.copy_(torch.randn(kv.k.shape, generator=g).to(kv.k.dtype))
+    kv.v.copy_(torch.randn(kv.v.shape, generator=g).to(kv.v.dtype))
+    k0, v0 = kv.k.cpu().clone(), kv.v.cpu().clone()
+    # paths with strictly increasing node indices (a child is numbered after its parent)
+    path = np.array([[0, 3, 4, 9, 19, -1], [0, 1, 2, 3, -1, -1], [0, 17, -1, -1, -1, -1]], dtype=np.int32)
+    alen = np.array([4, 3, 0], dtype=np.int32)
+    d_path = torch.from_numpy(path).cuda()
+    d_len = torch.from_numpy(alen).cuda()
+    sv.sv_commit_path(cfg, kv.struct, T, d_path, d_len, B, d_cap)
+    sv.sv_advance_prefix(kv.prefix_len, d_len, B, d_cap)
+    torch.cuda.synchronize()
+    k1, v1 = kv.k.cpu(), kv.v.cpu()
+    for b in range(B):
+        P = prefix[b]
+        want_k, want_v = k0[b].clone(), v0[b].clone()
+        for i in range(1, alen[b] + 1):
+            want_k[:, P + i] = k0[b][:, P + path[b, i]]
+            want_v[:, P + i] = v0[b][:, P + path[b, i]]
+        assert torch.equal(k1[b], want_k) and torch.equal(v1[b], want_v), b
+    assert kv.prefix_len.cpu().tolist() == [p + int(a) + 1 for p, a in zip(prefix, alen)]
