@@ -23,9 +23,11 @@ SV_WS_ATTN_OUT, SV_WS_Q, SV_WS_STATUS = 0, 1, 2
 EXPORTS = ("sv_version", "sv_strerror", "sv_tree_build_masks", "sv_packed_layer_bytes",
            "sv_pack_layer", "sv_workspace_bytes", "sv_workspace_init", "sv_workspace_region",
            "sv_verify_layer",
-           "sv_verify_layer_timed", "sv_action_head_argmax", "sv_relaxed_accept",
+           "sv_verify_layer_timed", "sv_verify_stack", "sv_verify_stack_timeline",
+           "sv_action_head_argmax", "sv_relaxed_accept",
            "sv_commit_path", "sv_advance_prefix")
 SV_N_TIMING_EVENTS = 9
+SV_TIMELINE_SLOTS = 16
 
 
 class SvError(RuntimeError):
@@ -82,6 +84,11 @@ def lib() -> C.CDLL:
                                       C.POINTER(KvView), C.POINTER(Tree), C.c_int, C.c_void_p,
                                       C.c_size_t, C.c_void_p]
         l.sv_verify_layer_timed.argtypes = l.sv_verify_layer.argtypes + [C.c_void_p]
+        l.sv_verify_stack.argtypes = [C.POINTER(ModelCfg), C.c_int, C.POINTER(C.c_void_p), C.c_void_p,
+                                      C.POINTER(KvView), C.POINTER(Tree), C.c_int, C.c_void_p,
+                                      C.c_size_t, C.c_void_p]
+        l.sv_verify_stack_timeline.argtypes = l.sv_verify_stack.argtypes + [
+            C.c_void_p, C.c_size_t, C.POINTER(C.c_int)]
         l.sv_action_head_argmax.argtypes = [C.POINTER(ModelCfg), C.c_void_p, C.c_void_p, C.c_void_p,
                                             C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                             C.c_void_p, C.c_size_t, C.c_void_p]
@@ -207,6 +214,38 @@ def sv_verify_layer_timed(cfg: ModelCfg, packed: torch.Tensor, x: torch.Tensor, 
                                        C.cast(events, C.c_void_p)), "sv_verify_layer_timed")
 
 
+def _stack_arrays(packed: Sequence[torch.Tensor], kv: Sequence[KvView]):
+    n = len(packed)
+    if n < 1 or len(kv) != n:
+        raise ValueError("verify_stack: one packed blob and one KV view per layer")
+    ptrs = (C.c_void_p * n)(*[_dev(p, torch.uint8, "packed") for p in packed])
+    views = (KvView * n)(*kv)
+    return n, ptrs, views
+
+
+def sv_verify_stack(cfg: ModelCfg, packed: Sequence[torch.Tensor], x: torch.Tensor,
+                    kv: Sequence[KvView], tree: Tree, B: int, workspace: torch.Tensor,
+                    stream=None) -> None:
+    n, ptrs, views = _stack_arrays(packed, kv)
+    _check(lib().sv_verify_stack(C.byref(cfg), n, ptrs, _dev(x, torch.float32, "x"), views,
+                                 C.byref(tree), B, _dev(workspace, torch.uint8, "workspace"),
+                                 workspace.numel(), _stream(stream)), "sv_verify_stack")
+
+
+def sv_verify_stack_timeline(cfg: ModelCfg, packed: Sequence[torch.Tensor], x: torch.Tensor,
+                             kv: Sequence[KvView], tree: Tree, B: int, workspace: torch.Tensor,
+                             timeline: torch.Tensor, stream=None) -> int:
+    """Returns the number of workgroups that wrote into `timeline` (int64, device)."""
+    n, ptrs, views = _stack_arrays(packed, kv)
+    n_wg = C.c_int(0)
+    _check(lib().sv_verify_stack_timeline(
+        C.byref(cfg), n, ptrs, _dev(x, torch.float32, "x"), views, C.byref(tree), B,
+        _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream),
+        _dev(timeline, torch.int64, "timeline"), timeline.numel(), C.byref(n_wg)),
+        "sv_verify_stack_timeline")
+    return n_wg.value
+
+
 def sv_action_head_argmax(cfg: ModelCfg, g_final: torch.Tensor, w_lm: torch.Tensor,
                           x: torch.Tensor, n_rows: int, vocab_lo: int, vocab_hi: int,
                           out_token: torch.Tensor, out_logits: Optional[torch.Tensor],
@@ -281,11 +320,13 @@ class KvCache:
     """KV cache of one layer, [B, n_heads, capacity, head_dim], prefix rows filled by the caller."""
 
     def __init__(self, cfg: ModelCfg, B: int, capacity: int, prefix_len: Sequence[int],
-                 device="cuda"):
+                 device="cuda", share_prefix_with: Optional["KvCache"] = None):
         dt = storage_dtype(cfg)
         self.k = torch.zeros(B, cfg.n_heads, capacity, cfg.head_dim, dtype=dt, device=device)
         self.v = torch.zeros_like(self.k)
         pl = np.ascontiguousarray(prefix_len, dtype=np.int32)
-        self.prefix_len = torch.from_numpy(pl).to(device)
+        # the layers of one model have the same prefix lengths: one device array can serve all
+        self.prefix_len = (share_prefix_with.prefix_len if share_prefix_with is not None
+                           else torch.from_numpy(pl).to(device))
         self.struct = KvView(self.k.data_ptr(), self.v.data_ptr(), self.prefix_len.data_ptr(),
                              int(pl.max()), capacity)

@@ -12,6 +12,7 @@
 #include "sv_gemm_mfma.h"
 #include "sv_internal.h"
 #include "sv_kernels.h"
+#include "sv_stack_persistent.h"
 
 namespace sv {
 
@@ -83,7 +84,19 @@ static WorkspaceLayout workspace_layout(const sv_model_cfg& c, int m_rows, int n
     L.sumsq = o;    o = align_up(o + mt * (tiles_max + kXcds) * s_max * kMTile * 4, kAlign);
     L.part = o;     o = align_up(o + mt * tiles_max * s_max * kTileFloats * 4, kAlign);
     L.xhat = o;
+    L.stack_ctl = L.stack_ctl_bytes = L.stack_sumsq = L.stack_part = L.stack_part_bytes = 0;
+    if (mt == 1) {
+      // group words [32 layers][4 phases][256 groups] x 8 B, then grid (8 x 64), workgroup
+      // counters (256) and flags (256 x 16) as 32-bit words, then the launch description
+      L.stack_ctl_bytes = align_up((size_t)kStackMaxLayers * 4 * 256 * 8 + (8 * 64 + 256 + 256 * 16) * 4 +
+                                   sizeof(StackArgs), kAlign);
+      L.stack_ctl = o;   o += L.stack_ctl_bytes;
+      L.stack_sumsq = o; o = align_up(o + (size_t)kXcds * kUnitsPerXcd * kMTile * 4, kAlign);
+      L.stack_part_bytes = (tiles_max + kXcds * kUnitsPerXcd) * s_max * kTileFloats * 4;
+      L.stack_part = o;  o = align_up(o + L.stack_part_bytes, kAlign);
+    }
   } else {
+    L.stack_ctl = L.stack_ctl_bytes = L.stack_sumsq = L.stack_part = L.stack_part_bytes = 0;
     L.counter_bytes = 0;
     L.counters = L.sumsq = o;
     L.part = o;     o = align_up(o + mp * n_max * 4, kAlign);
@@ -228,6 +241,88 @@ static int verify_layer_bf16(const sv_model_cfg& c, const char* packed, float* x
   mark(7);
   gemm_stream_bf16<PRO_PLAIN, EPI_RESID><<<grid, 256, 0, st>>>(a);
   mark(8);
+  return launch_status();
+}
+
+// ---- bf16 models, up to 64 rows: the whole stack as persistent launches ----------------------
+
+// Fills the launch description; false if this shape / device / cache layout needs the
+// per-layer path.
+static bool stack_plan(const sv_model_cfg& c, int n_layers, const void* const* packed,
+                       const sv_kv_view* kv, const sv_tree& tree, int B, float* x, char* ws,
+                       StackArgs* a, StackBufs* d, StackArgs** a_dev) {
+  const int T_ = tree.n_nodes, M = B * T_;
+  if (c.dtype != SV_BF16 || M > kMTile || n_layers < 1 || n_layers > kStackMaxLayers) return false;
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+    return false;
+  const int n_xcd = device_xcds();
+  if (cus < n_xcd * kUnitsPerXcd) return false;
+  for (int l = 1; l < n_layers; ++l)
+    if (kv[l].prefix_len != kv[0].prefix_len || kv[l].prefix_len_max != kv[0].prefix_len_max ||
+        kv[l].capacity != kv[0].capacity)
+      return false;
+  const int H = c.hidden, D = c.n_heads * c.head_dim, F = c.mlp_dim;
+  const WorkspaceLayout wl = workspace_layout(c, M, 0);
+  const PackedLayout pl = packed_layout(c);
+  memset(a, 0, sizeof(*a));
+  memset(d, 0, sizeof(*d));
+  const int NK[4][2] = {{3 * D, H}, {H, D}, {2 * F, H}, {H, F}};
+  size_t part_xcd = 0;
+  int gmax = 1;
+  for (int ph = 0; ph < 4; ++ph) {
+    const GemmPlan p = plan_gemm(NK[ph][0], NK[ph][1], n_xcd);
+    if (p.gpx * p.S > kUnitsPerXcd) return false;
+    a->plan[ph] = PhasePlan{NK[ph][0], NK[ph][1], p.S, p.gpx};
+    const PhaseGeom g0 = phase_geom(a->plan[ph], n_xcd, 0, 0);
+    if (g0.n_chunks > 1 && g0.t_max > 4) return false;     // accumulators of one tile per wave only
+    const size_t need = (size_t)p.gpx * g0.t_max * p.S * kTileFloats;
+    if (need > part_xcd) part_xcd = need;
+    if (n_xcd * p.gpx > gmax) gmax = n_xcd * p.gpx;
+  }
+  if (gmax > 256 || part_xcd * n_xcd * 4 > wl.stack_part_bytes) return false;
+  for (int l = 0; l < n_layers; ++l) {
+    a->L[l].packed = (const unsigned char*)packed[l];
+    a->L[l].kc = (bf16_t*)kv[l].k;
+    a->L[l].vc = (bf16_t*)kv[l].v;
+  }
+  a->n_layers = n_layers;
+  a->off_g1 = (unsigned)pl.g1; a->off_g2 = (unsigned)pl.g2;
+  a->off_wqkv = pl.wqkv; a->off_wo = pl.wo; a->off_wgu = pl.wgu; a->off_wd = pl.wd;
+  a->M = M; a->T = T_; a->nh = c.n_heads; a->n_xcd = n_xcd;
+  a->eps = c.rms_eps; a->theta = c.rope_theta;
+  d->x_io = x;
+  d->q = (float*)(ws + wl.q);
+  d->attn = (float*)(ws + wl.attn);
+  d->act = (float*)(ws + wl.act);
+  d->part = (float*)(ws + wl.stack_part);
+  a->part_xcd_floats = part_xcd;
+  d->sumsq = (float*)(ws + wl.stack_sumsq);
+  char* ctl = ws + wl.stack_ctl;
+  d->group_cnt = (unsigned long long*)ctl;
+  a->gmax = 256;
+  unsigned* words = (unsigned*)(ctl + (size_t)kStackMaxLayers * 4 * 256 * 8);
+  d->grid_cnt = words;
+  d->wg_cnt = words + 8 * 64;
+  d->wg_flag = words + 8 * 64 + 256;
+  *a_dev = (StackArgs*)(words + 8 * 64 + 256 + 256 * 16);
+  d->status = (int*)(ws + wl.counters + wl.counter_bytes) - 1;
+  d->depth = tree.depth;
+  d->prefix_len = kv[0].prefix_len;
+  d->anc = tree.anc_mask;
+  a->n_words = tree.n_words;
+  a->p_max = kv[0].prefix_len_max;
+  a->cap = kv[0].capacity;
+  return true;
+}
+
+static int launch_stack(const StackArgs& a, const StackBufs& d, StackArgs* a_dev, char* ws,
+                        const WorkspaceLayout& wl, hipStream_t st) {
+  const size_t n = wl.stack_ctl_bytes / sizeof(int);
+  zero_ints<<<(unsigned)((n + 255) / 256), 256, 0, st>>>((int*)(ws + wl.stack_ctl), n);
+  write_stack_args<<<1, 64, 0, st>>>(a, a_dev);
+  verify_stack_persistent<<<a.n_xcd * kUnitsPerXcd, 512, 0, st>>>(a_dev, d);
   return launch_status();
 }
 
@@ -443,6 +538,75 @@ int sv_verify_layer_timed(const sv_model_cfg* cfg, const void* packed, float* x,
     ev[i] = (hipEvent_t)events[i];
   }
   return verify_layer_checked(cfg, packed, x, kv, tree, B, workspace, ws_bytes, stream, ev);
+}
+
+static int verify_stack_args(const sv_model_cfg* cfg, int n_layers, const void* const* packed,
+                             float* x, const sv_kv_view* kv, const sv_tree* tree, int B,
+                             void* workspace, size_t ws_bytes) {
+  const int rc = check_cfg(cfg);
+  if (rc != SV_OK) return rc;
+  if (!packed || !x || !kv || !tree || !workspace || !tree->parent || !tree->depth || !tree->anc_mask)
+    return SV_ERR_NULL;
+  if (n_layers < 1) return SV_ERR_SHAPE;
+  const int T = tree->n_nodes;
+  if (B < 1 || T < 1 || T > SV_MAX_TREE_NODES || tree->n_words != (T + 63) / 64 ||
+      (long long)B * T > (1 << 15))
+    return SV_ERR_SHAPE;
+  for (int l = 0; l < n_layers; ++l) {
+    if (!packed[l] || !kv[l].k || !kv[l].v || !kv[l].prefix_len) return SV_ERR_NULL;
+    if ((uintptr_t)packed[l] % kAlign) return SV_ERR_WORKSPACE;
+    if (kv[l].prefix_len_max < 0 || (long long)kv[l].capacity < (long long)kv[l].prefix_len_max + T)
+      return SV_ERR_SHAPE;
+  }
+  if (((uintptr_t)workspace % kAlign) || ws_bytes < workspace_layout(*cfg, B * T, 0).total)
+    return SV_ERR_WORKSPACE;
+  return SV_OK;
+}
+
+int sv_verify_stack(const sv_model_cfg* cfg, int n_layers, const void* const* packed, float* x,
+                    const sv_kv_view* kv, const sv_tree* tree, int B, void* workspace,
+                    size_t ws_bytes, void* stream) {
+  const int rc = verify_stack_args(cfg, n_layers, packed, x, kv, tree, B, workspace, ws_bytes);
+  if (rc != SV_OK) return rc;
+  const WorkspaceLayout wl = workspace_layout(*cfg, B * tree->n_nodes, 0);
+  for (int l0 = 0; l0 < n_layers; l0 += kStackMaxLayers) {
+    const int nl = n_layers - l0 < kStackMaxLayers ? n_layers - l0 : kStackMaxLayers;
+    StackArgs a;
+    StackBufs d;
+    StackArgs* a_dev = nullptr;
+    if (stack_plan(*cfg, nl, packed + l0, kv + l0, *tree, B, x, (char*)workspace, &a, &d, &a_dev)) {
+      const int r2 = launch_stack(a, d, a_dev, (char*)workspace, wl, (hipStream_t)stream);
+      if (r2 != SV_OK) return r2;
+    } else {
+      for (int l = l0; l < l0 + nl; ++l) {
+        const int r2 = verify_layer_checked(cfg, packed[l], x, kv + l, tree, B, workspace, ws_bytes,
+                                            stream, nullptr);
+        if (r2 != SV_OK) return r2;
+      }
+    }
+  }
+  return SV_OK;
+}
+
+int sv_verify_stack_timeline(const sv_model_cfg* cfg, int n_layers, const void* const* packed,
+                             float* x, const sv_kv_view* kv, const sv_tree* tree, int B,
+                             void* workspace, size_t ws_bytes, void* stream, long long* timeline,
+                             size_t timeline_len, int* n_workgroups) {
+  if (!timeline || !n_workgroups) return SV_ERR_NULL;
+  const int rc = verify_stack_args(cfg, n_layers, packed, x, kv, tree, B, workspace, ws_bytes);
+  if (rc != SV_OK) return rc;
+  StackArgs a;
+  StackBufs d;
+  StackArgs* a_dev = nullptr;
+  if (!stack_plan(*cfg, n_layers, packed, kv, *tree, B, x, (char*)workspace, &a, &d, &a_dev))
+    return SV_ERR_SHAPE;
+  const int wgs = a.n_xcd * kUnitsPerXcd;
+  if (timeline_len < (size_t)wgs * n_layers * kTsPerLayer) return SV_ERR_WORKSPACE;
+  static_assert(kTsPerLayer == SV_TIMELINE_SLOTS, "timeline slots");
+  d.ts = timeline;
+  *n_workgroups = wgs;
+  return launch_stack(a, d, a_dev, (char*)workspace, workspace_layout(*cfg, B * tree->n_nodes, 0),
+                      (hipStream_t)stream);
 }
 
 int sv_action_head_argmax(const sv_model_cfg* cfg, const void* g_final, const void* w_lm,

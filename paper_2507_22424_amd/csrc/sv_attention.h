@@ -28,6 +28,12 @@ constexpr int kAttKeys = 32;     // keys per tile
 constexpr int kVtPitch = 72;     // bytes per row of the transposed V tile (64 + pad, 8-byte aligned)
 constexpr float kNegBig = -1.0e30f;
 
+// 16-byte load from global memory (also when the compiler cannot tell where the pointer points)
+__device__ inline uint4 ld_global_u4(const void* p) {
+  const u32x4_t v = *(const __attribute__((address_space(1))) u32x4_t*)p;
+  return make_uint4(v[0], v[1], v[2], v[3]);
+}
+
 __device__ inline bf16x8_t pack8_hi(const float* v) {
   const uint4 u = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]),
                              pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
@@ -45,23 +51,23 @@ __device__ inline void split8(const float* v, bf16x8_t& hi, bf16x8_t& lo) {
   lo = __builtin_bit_cast(bf16x8_t, l);
 }
 
-// grid = (B * ceil(T / 16), n_heads), block = 64 * NW (NW waves split the keys; at 340 keys the
-// kernel is latency bound and 8 waves measured slower than 4).
+// Work of one workgroup of NW waves: query block bx = (episode, block of 16 nodes), head by.
+// lds_raw: NW * 128 * kVtPitch bytes; s_m, s_l: [NW][16] floats; sync(): barrier of the waves
+// that run this body (called twice).  DEV_OUT: the result is written with device-scope stores
+// (for readers on other XCDs inside the same launch).
 // head_dim = 128.
 // q: float32 [M, nh*128] (rotated);  kc, vc: bf16 [B][nh][cap][128];  out: float32 [M, nh*128].
-template <int NW>
-__global__ __launch_bounds__(64 * NW) void tree_attention_mfma(
+template <int NW, bool DEV_OUT, typename Sync>
+__device__ inline void tree_attention_body(
     const float* __restrict__ q, const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc,
     const int32_t* __restrict__ prefix_len, int p_max, const uint64_t* __restrict__ anc,
-    int n_words, int T, int nh, int cap, float* __restrict__ out) {
-  // per wave: transposed V tile [128 d][32 keys] with padded rows; reused for the merge
-  __shared__ __attribute__((aligned(16))) unsigned char lds_raw[NW * 128 * kVtPitch];
-  __shared__ float s_m[NW][kAttQ], s_l[NW][kAttQ];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int n_words, int T, int nh, int cap, float* __restrict__ out, int bx, int by,
+    unsigned char* lds_raw, float (*s_m)[kAttQ], float (*s_l)[kAttQ], int tid, Sync sync) {
+  const int lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 4, c = lane & 15;      // lane group (0..3), column = query
   const int qblocks = (T + kAttQ - 1) / kAttQ;
-  const int b = blockIdx.x / qblocks, qb = blockIdx.x % qblocks;
-  const int h = blockIdx.y;
+  const int b = bx / qblocks, qb = bx % qblocks;
+  const int h = by;
   const int D = nh * 128;
   int P = prefix_len[b];
   P = P < 0 ? 0 : (P > p_max ? p_max : P);
@@ -99,12 +105,12 @@ __global__ __launch_bounds__(64 * NW) void tree_attention_mfma(
       const int key = min(key0 + 16 * st + c, nkeys - 1);
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks)
-        kreg[st * 4 + ks] = *reinterpret_cast<const uint4*>(kbase + (size_t)key * 128 + 32 * ks + 8 * g);
+        kreg[st * 4 + ks] = ld_global_u4(kbase + (size_t)key * 128 + 32 * ks + 8 * g);
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int key = min(key0 + 4 * i + g, nkeys - 1);
-      vreg[i] = *reinterpret_cast<const uint4*>(vbase + (size_t)key * 128 + 8 * c);
+      vreg[i] = ld_global_u4(vbase + (size_t)key * 128 + 8 * c);
     }
   };
 
@@ -203,8 +209,8 @@ __global__ __launch_bounds__(64 * NW) void tree_attention_mfma(
     __builtin_amdgcn_s_waitcnt(0xc07f);      // V^T reads done before the next tile overwrites them
   }
 
-  // ---- merge the four waves ----
-  __syncthreads();
+  // ---- merge the waves ----
+  sync();
   float* om = reinterpret_cast<float*>(lds_raw);          // [NW waves][128 d][16 q] float32
   if (g == 0) {
     s_m[wave][c] = m_run;
@@ -214,7 +220,7 @@ __global__ __launch_bounds__(64 * NW) void tree_attention_mfma(
   for (int dt = 0; dt < 8; ++dt)
 #pragma unroll
     for (int r = 0; r < 4; ++r) om[(wave * 128 + 16 * dt + 4 * g + r) * kAttQ + c] = o[dt][r];
-  __syncthreads();
+  sync();
   // the first four waves finish d rows 32w .. 32w+31: lane -> (d = 32w + lane % 32, queries
   // (lane / 32) * 8 .. + 7)
   if (wave < 4) {
@@ -233,9 +239,31 @@ __global__ __launch_bounds__(64 * NW) void tree_attention_mfma(
         den += sc * s_l[w][qq];
       }
       const int tnode = qb * kAttQ + qq;
-      if (tnode < T) out[((size_t)b * T + tnode) * D + h * 128 + d] = num / den;
+      if (tnode < T) {
+        float* dst = out + ((size_t)b * T + tnode) * D + h * 128 + d;
+        if (DEV_OUT)
+          __hip_atomic_store((__attribute__((address_space(1))) float*)dst, num / den, __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
+        else
+          *dst = num / den;
+      }
     }
   }
+}
+
+// grid = (B * ceil(T / 16), n_heads), block = 64 * NW (NW waves split the keys; at 340 keys the
+// kernel is latency bound and 8 waves measured slower than 4).
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void tree_attention_mfma(
+    const float* __restrict__ q, const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc,
+    const int32_t* __restrict__ prefix_len, int p_max, const uint64_t* __restrict__ anc,
+    int n_words, int T, int nh, int cap, float* __restrict__ out) {
+  // per wave: transposed V tile [128 d][32 keys] with padded rows; reused for the merge
+  __shared__ __attribute__((aligned(16))) unsigned char lds_raw[NW * 128 * kVtPitch];
+  __shared__ float s_m[NW][kAttQ], s_l[NW][kAttQ];
+  tree_attention_body<NW, false>(q, kc, vc, prefix_len, p_max, anc, n_words, T, nh, cap, out,
+                                 (int)blockIdx.x, (int)blockIdx.y, lds_raw, s_m, s_l,
+                                 (int)threadIdx.x, [] { __syncthreads(); });
 }
 
 }  // namespace sv

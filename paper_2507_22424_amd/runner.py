@@ -33,8 +33,10 @@ class VerifyPass:
         self.tree = sv.DeviceTree(parent, self.B, self.T, self.d_cap, device)
         pl = np.asarray(prefix_len, dtype=np.int32)
         self.capacity = int(-(-(int(pl.max()) + self.T + extra_capacity) // 64) * 64)
-        self.kv = [sv.KvCache(self.cfg, self.B, self.capacity, pl, device)
-                   for _ in range(wc.n_layers)]
+        self.kv: List[sv.KvCache] = []
+        for _ in range(wc.n_layers):       # one prefix-length array for all layers
+            self.kv.append(sv.KvCache(self.cfg, self.B, self.capacity, pl, device,
+                                      share_prefix_with=self.kv[0] if self.kv else None))
         self.packed: List[Optional[torch.Tensor]] = [None] * wc.n_layers
         self.packed_bytes = sv.sv_packed_layer_bytes(self.cfg)
         self.ws_bytes = sv.sv_workspace_bytes(self.cfg, self.B, self.T, self.n_scored)
@@ -84,10 +86,17 @@ class VerifyPass:
         self.draft.copy_(torch.from_numpy(np.ascontiguousarray(draft, dtype=np.int32).reshape(-1)))
 
     # ---- one step ------------------------------------------------------------------
-    def forward(self, n_layers: Optional[int] = None, want_logits: bool = True) -> None:
+    def forward(self, n_layers: Optional[int] = None, want_logits: bool = True,
+                per_layer_calls: bool = False) -> None:
+        """All layers (sv_verify_stack, or one sv_verify_layer per layer), then the head."""
         self.x.copy_(self.x0)
-        for l in range(self.wc.n_layers if n_layers is None else n_layers):
-            sv.sv_verify_layer(self.cfg, self.packed[l], self.x, self.kv[l].struct,
+        n = self.wc.n_layers if n_layers is None else n_layers
+        if per_layer_calls:
+            for l in range(n):
+                sv.sv_verify_layer(self.cfg, self.packed[l], self.x, self.kv[l].struct,
+                                   self.tree.struct, self.B, self.workspace)
+        else:
+            sv.sv_verify_stack(self.cfg, self.packed[:n], self.x, [kv.struct for kv in self.kv[:n]],
                                self.tree.struct, self.B, self.workspace)
         sv.sv_action_head_argmax(self.cfg, self.g_final, self.w_lm, self.x, self.M, self.vocab_lo,
                                  self.vocab_hi, self.token, self.logits if want_logits else None,
@@ -115,8 +124,6 @@ class VerifyPass:
         # all layers share the prefix lengths of layer 0's holder
         sv.sv_advance_prefix(self.kv[0].prefix_len, self.accepted_len, self.B, self.d_cap)
         for l in range(self.wc.n_layers):
-            if l > 0:
-                self.kv[l].prefix_len.copy_(self.kv[0].prefix_len)
             self.kv[l].struct.prefix_len_max = min(self.kv[l].struct.prefix_len_max + self.d_cap + 1,
                                                    self.capacity - self.T)
 

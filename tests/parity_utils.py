@@ -87,6 +87,7 @@ class SideBySide:
             say(f"[{tag or cfg.name}] layer {l + 1}/{L} done, {time.time() - t0:.0f}s"
                 + (f", attn err {self.attn_err[-1]:.2e}, x err {self.x_err[-1]:.2e}"
                    if per_layer else ""))
+        x_layer_calls = self.gpu.x.clone() if per_layer else None
         head = wl.head_weights(cfg, full_vocab=full_vocab)
         self.gpu.load_head(head["g_final"], head["w_lm"])
         self.ref_x = np.concatenate(x_ref)
@@ -99,6 +100,10 @@ class SideBySide:
         self.gpu_logits = self.gpu.logits.cpu().numpy()
         self.gpu_token = self.gpu.token.cpu().numpy()
         self.gpu_x = self.gpu.x.cpu().numpy()
+        # sv_verify_stack (one persistent launch where it applies) and a sequence of
+        # sv_verify_layer calls do the same arithmetic in the same order
+        if x_layer_calls is not None:
+            assert torch.equal(self.gpu.x, x_layer_calls), "stack and per-layer routes differ"
         self.logit_err = row_rel_err(self.gpu_logits, self.ref_logits)
         assert self.gpu.placement_status() == 0, "K slices of a tile ran on different XCDs"
 
