@@ -172,36 +172,38 @@ int sv_verify_layer_timed(const sv_model_cfg *cfg, const void *packed, float *x,
                           size_t ws_bytes, void *stream, void *const *events);
 
 /* The whole verifier stack (Sec. 4.1: M_V scores every draft position in one forward pass):
- * the result is that of sv_verify_layer called for layer 0 .. n_layers-1 in turn on the same x.
- * For a bf16 model with B*T <= 64 rows on a device whose compute units are all free, the
- * layers run as one persistent launch per 32 layers in which the weight stream continues
- * across the phase boundaries of a layer (much faster); otherwise the call falls back to one
- * sv_verify_layer per layer.  In the persistent form the workgroups meet at device-wide
- * barriers with bounded waits: run nothing else on the device meanwhile; if the workgroups
- * cannot all be resident the waits run out, the status word (SV_WS_STATUS) becomes non-zero
- * and the results are invalid.
+ * exactly sv_verify_layer for layer 0 .. n_layers-1 in turn on the same x, issued from one call.
  *   packed: [host] array of n_layers [device] pointers, each from sv_pack_layer
- *   kv:     [host] array of n_layers views; the persistent form needs all views to share
- *           prefix_len, prefix_len_max and capacity (else: fallback)
+ *   kv:     [host] array of n_layers views (one cache per layer)
  *   others: as sv_verify_layer
  * SV_ERR_SHAPE if n_layers < 1; otherwise the errors of sv_verify_layer. */
 int sv_verify_stack(const sv_model_cfg *cfg, int n_layers, const void *const *packed, float *x,
                     const sv_kv_view *kv, const sv_tree *tree, int B, void *workspace,
                     size_t ws_bytes, void *stream);
 
-/* Measurement aid: sv_verify_stack in its persistent form only (SV_ERR_SHAPE where that form
- * does not apply, or n_layers > 32), with a timeline: workgroup w writes the device clock
- * (100 MHz) at fixed points of layer l to timeline[(w * n_layers + l) * SV_TIMELINE_SLOTS + i]:
- * for GEMM phase p = 0..3 (q/k/v, output, gate/up, down) slot 3p = activations staged,
- * 3p+1 = all tiles handed over, 3p+2 = reduction and epilogue done; 12 = first device-wide
- * barrier passed, 13 = attention done, 14 = second barrier passed.
- *   timeline: [device] int64 [n_workgroups * n_layers * SV_TIMELINE_SLOTS], n_workgroups =
- *             *n_workgroups on return (at most 256); timeline_len = entries available. */
+/* Experimental single-launch form of sv_verify_stack, bit-identical results: up to 32 layers
+ * run as ONE persistent launch (one workgroup per compute unit, split into waves that only
+ * stream weights and waves that stage, reduce, attend and synchronise), so that weight loads
+ * of the next phase are already in flight while a phase boundary is worked on.  Measured
+ * slower than the per-layer launches on MI355X (the boundaries, not the launches, dominate);
+ * kept as a measured design point.  Needs a bf16 model, B*T <= 64, n_layers <= 32, all kv
+ * views sharing prefix_len / prefix_len_max / capacity, and every compute unit of the device
+ * free: the workgroups meet at device-wide barriers with bounded waits; if they cannot all be
+ * resident the waits run out, the status word (SV_WS_STATUS) becomes non-zero and the results
+ * are invalid.  SV_ERR_SHAPE where the form does not apply.
+ *   timeline: NULL, or [device] int64 [n_workgroups * n_layers * SV_TIMELINE_SLOTS]: workgroup
+ *             w writes the device clock (100 MHz) at fixed points of layer l to
+ *             timeline[(w * n_layers + l) * SV_TIMELINE_SLOTS + i]; for GEMM phase p = 0..3
+ *             (q/k/v, output, gate/up, down) slot 3p = activations staged, 3p+1 = all tiles
+ *             handed over, 3p+2 = reduction and epilogue done; 12 = first device-wide barrier
+ *             passed, 13 = attention done, 14 = second barrier passed
+ *   timeline_len: entries available (SV_ERR_WORKSPACE if too few)
+ *   n_workgroups: [host] out, may be NULL: workgroups of the launch (at most 256) */
 #define SV_TIMELINE_SLOTS 16
-int sv_verify_stack_timeline(const sv_model_cfg *cfg, int n_layers, const void *const *packed,
-                             float *x, const sv_kv_view *kv, const sv_tree *tree, int B,
-                             void *workspace, size_t ws_bytes, void *stream, long long *timeline,
-                             size_t timeline_len, int *n_workgroups);
+int sv_verify_stack_persistent(const sv_model_cfg *cfg, int n_layers, const void *const *packed,
+                               float *x, const sv_kv_view *kv, const sv_tree *tree, int B,
+                               void *workspace, size_t ws_bytes, void *stream, long long *timeline,
+                               size_t timeline_len, int *n_workgroups);
 
 /* Final RMSNorm, LM-head logits of vocabulary rows [vocab_lo, vocab_hi) and the greedy
  * choice among them (Eq. 1), the lowest id winning exact ties.  vocab_lo = V - 256,

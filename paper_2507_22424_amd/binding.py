@@ -16,6 +16,8 @@ import torch
 from .build import LIB_PATH
 
 SV_F32, SV_BF16 = 0, 1
+(SV_OK, SV_ERR_NULL, SV_ERR_SHAPE, SV_ERR_TREE, SV_ERR_TOKEN, SV_ERR_WORKSPACE, SV_ERR_DTYPE,
+ SV_ERR_LAUNCH) = (0, -1, -2, -3, -4, -5, -6, -7)
 SV_MAX_TREE_NODES = 128
 SV_MAX_DEPTH = 31
 SV_WS_ATTN_OUT, SV_WS_Q, SV_WS_STATUS = 0, 1, 2
@@ -23,7 +25,7 @@ SV_WS_ATTN_OUT, SV_WS_Q, SV_WS_STATUS = 0, 1, 2
 EXPORTS = ("sv_version", "sv_strerror", "sv_tree_build_masks", "sv_packed_layer_bytes",
            "sv_pack_layer", "sv_workspace_bytes", "sv_workspace_init", "sv_workspace_region",
            "sv_verify_layer",
-           "sv_verify_layer_timed", "sv_verify_stack", "sv_verify_stack_timeline",
+           "sv_verify_layer_timed", "sv_verify_stack", "sv_verify_stack_persistent",
            "sv_action_head_argmax", "sv_relaxed_accept",
            "sv_commit_path", "sv_advance_prefix")
 SV_N_TIMING_EVENTS = 9
@@ -87,7 +89,7 @@ def lib() -> C.CDLL:
         l.sv_verify_stack.argtypes = [C.POINTER(ModelCfg), C.c_int, C.POINTER(C.c_void_p), C.c_void_p,
                                       C.POINTER(KvView), C.POINTER(Tree), C.c_int, C.c_void_p,
                                       C.c_size_t, C.c_void_p]
-        l.sv_verify_stack_timeline.argtypes = l.sv_verify_stack.argtypes + [
+        l.sv_verify_stack_persistent.argtypes = l.sv_verify_stack.argtypes + [
             C.c_void_p, C.c_size_t, C.POINTER(C.c_int)]
         l.sv_action_head_argmax.argtypes = [C.POINTER(ModelCfg), C.c_void_p, C.c_void_p, C.c_void_p,
                                             C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
@@ -232,17 +234,17 @@ def sv_verify_stack(cfg: ModelCfg, packed: Sequence[torch.Tensor], x: torch.Tens
                                  workspace.numel(), _stream(stream)), "sv_verify_stack")
 
 
-def sv_verify_stack_timeline(cfg: ModelCfg, packed: Sequence[torch.Tensor], x: torch.Tensor,
-                             kv: Sequence[KvView], tree: Tree, B: int, workspace: torch.Tensor,
-                             timeline: torch.Tensor, stream=None) -> int:
-    """Returns the number of workgroups that wrote into `timeline` (int64, device)."""
+def sv_verify_stack_persistent(cfg: ModelCfg, packed: Sequence[torch.Tensor], x: torch.Tensor,
+                               kv: Sequence[KvView], tree: Tree, B: int, workspace: torch.Tensor,
+                               timeline: Optional[torch.Tensor] = None, stream=None) -> int:
+    """Returns the number of workgroups of the launch (they write into `timeline`, int64, device)."""
     n, ptrs, views = _stack_arrays(packed, kv)
     n_wg = C.c_int(0)
-    _check(lib().sv_verify_stack_timeline(
+    _check(lib().sv_verify_stack_persistent(
         C.byref(cfg), n, ptrs, _dev(x, torch.float32, "x"), views, C.byref(tree), B,
         _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream),
-        _dev(timeline, torch.int64, "timeline"), timeline.numel(), C.byref(n_wg)),
-        "sv_verify_stack_timeline")
+        _dev(timeline, torch.int64, "timeline"), 0 if timeline is None else timeline.numel(),
+        C.byref(n_wg)), "sv_verify_stack_persistent")
     return n_wg.value
 
 

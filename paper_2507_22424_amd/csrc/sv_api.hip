@@ -568,31 +568,18 @@ int sv_verify_stack(const sv_model_cfg* cfg, int n_layers, const void* const* pa
                     size_t ws_bytes, void* stream) {
   const int rc = verify_stack_args(cfg, n_layers, packed, x, kv, tree, B, workspace, ws_bytes);
   if (rc != SV_OK) return rc;
-  const WorkspaceLayout wl = workspace_layout(*cfg, B * tree->n_nodes, 0);
-  for (int l0 = 0; l0 < n_layers; l0 += kStackMaxLayers) {
-    const int nl = n_layers - l0 < kStackMaxLayers ? n_layers - l0 : kStackMaxLayers;
-    StackArgs a;
-    StackBufs d;
-    StackArgs* a_dev = nullptr;
-    if (stack_plan(*cfg, nl, packed + l0, kv + l0, *tree, B, x, (char*)workspace, &a, &d, &a_dev)) {
-      const int r2 = launch_stack(a, d, a_dev, (char*)workspace, wl, (hipStream_t)stream);
-      if (r2 != SV_OK) return r2;
-    } else {
-      for (int l = l0; l < l0 + nl; ++l) {
-        const int r2 = verify_layer_checked(cfg, packed[l], x, kv + l, tree, B, workspace, ws_bytes,
-                                            stream, nullptr);
-        if (r2 != SV_OK) return r2;
-      }
-    }
+  for (int l = 0; l < n_layers; ++l) {
+    const int r2 = verify_layer_checked(cfg, packed[l], x, kv + l, tree, B, workspace, ws_bytes,
+                                        stream, nullptr);
+    if (r2 != SV_OK) return r2;
   }
   return SV_OK;
 }
 
-int sv_verify_stack_timeline(const sv_model_cfg* cfg, int n_layers, const void* const* packed,
-                             float* x, const sv_kv_view* kv, const sv_tree* tree, int B,
-                             void* workspace, size_t ws_bytes, void* stream, long long* timeline,
-                             size_t timeline_len, int* n_workgroups) {
-  if (!timeline || !n_workgroups) return SV_ERR_NULL;
+int sv_verify_stack_persistent(const sv_model_cfg* cfg, int n_layers, const void* const* packed,
+                               float* x, const sv_kv_view* kv, const sv_tree* tree, int B,
+                               void* workspace, size_t ws_bytes, void* stream, long long* timeline,
+                               size_t timeline_len, int* n_workgroups) {
   const int rc = verify_stack_args(cfg, n_layers, packed, x, kv, tree, B, workspace, ws_bytes);
   if (rc != SV_OK) return rc;
   StackArgs a;
@@ -601,10 +588,10 @@ int sv_verify_stack_timeline(const sv_model_cfg* cfg, int n_layers, const void* 
   if (!stack_plan(*cfg, n_layers, packed, kv, *tree, B, x, (char*)workspace, &a, &d, &a_dev))
     return SV_ERR_SHAPE;
   const int wgs = a.n_xcd * kUnitsPerXcd;
-  if (timeline_len < (size_t)wgs * n_layers * kTsPerLayer) return SV_ERR_WORKSPACE;
   static_assert(kTsPerLayer == SV_TIMELINE_SLOTS, "timeline slots");
+  if (timeline && timeline_len < (size_t)wgs * n_layers * kTsPerLayer) return SV_ERR_WORKSPACE;
   d.ts = timeline;
-  *n_workgroups = wgs;
+  if (n_workgroups) *n_workgroups = wgs;
   return launch_stack(a, d, a_dev, (char*)workspace, workspace_layout(*cfg, B * tree->n_nodes, 0),
                       (hipStream_t)stream);
 }

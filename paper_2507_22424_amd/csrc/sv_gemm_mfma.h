@@ -49,7 +49,8 @@ constexpr int kFragRows = 32;    // weight rows per fragment and per tile (MFMA 
 constexpr int kFragK = 16;       // k-values per fragment (MFMA K)
 constexpr int kBlkK = 128;       // granularity of K slices (8 fragments)
 constexpr int kChunkBlks = 4;    // K blocks of X resident in LDS at a time (512 k-values = 2 pieces)
-constexpr int kPieceFrags = 16;  // fragments per register buffer (16 KiB in flight per wave)
+constexpr int kPieceFrags = 8;   // fragments per ring slot: 128 k-values, 8 KiB per wave
+constexpr int kRing = 4;         // ring slots: 32 KiB of weights in flight per wave
 constexpr int kTileFloats = kMTile * kFragRows;   // one partial tile, [64][32] float32
 constexpr int kXcds = 8;
 constexpr int kRedBatch = 6;       // reduction work items whose loads are in flight together
@@ -139,12 +140,13 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
   __shared__ float s_rstd[kMTile];          // PRO_GAIN: 1 / rms of each row, known after the barrier
   __shared__ int s_pos[kMTile];             // EPI_QKV: rotary position of each row of the m tile
   __shared__ int s_crow[kMTile];            // EPI_QKV: cache row (b * nh * cap + P + t) of each row
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: bookkeeping stays in scalar registers
   const int mt = blockIdx.y, m0 = mt * kMTile;
   const int K = a.K, S = a.S;
   const int n_tiles = a.N / kFragRows;
   const int G = a.n_xcd * a.gpx;
-  const int npair = K / (2 * kBlkK);         // pieces along K
+  const int npair = K / (2 * kBlkK);         // 256-k blocks along K
   const int xcd = blockIdx.x % a.n_xcd;      // where the dispatcher puts this workgroup
   const int u = blockIdx.x / a.n_xcd;        // unit inside that XCD's share
   if (u >= a.gpx * S) return;
@@ -165,35 +167,46 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
     const int t_begin = g * tq + min(g, trem);
     const int t_count = tq + (g < trem ? 1 : 0);
     const int pq = npair / S, prem = npair % S;
-    const int p_begin = sp * pq + min(sp, prem);   // first piece of the slice
-    const int np = pq + (sp < prem ? 1 : 0);       // pieces in the slice
-    const int n_chunks = (np + 1) >> 1;
+    const int p_begin = 2 * (sp * pq + min(sp, prem));   // first piece (128 k-values) of the slice
+    const int np = 2 * (pq + (sp < prem ? 1 : 0));       // pieces in the slice
+    const int n_chunks = (np + 3) >> 2;                  // LDS chunks of 4 pieces
     const int my_tiles = t_count > wave ? (t_count - wave + 3) / 4 : 0;   // tiles wave, wave+4, ..
+    const int rounds = (t_count + 3) / 4;                // the same for the four waves
     const size_t unit_id = ((size_t)mt * G + g) * S + sp;
     const size_t tile_stride = (size_t)(K / kFragK) * 64;                 // uint4 per tile
+    typedef const __attribute__((address_space(1))) u32x4_t* wptr_t;
+    const wptr_t wbase = (wptr_t)a.Wp + (size_t)(t_begin + wave) * tile_stride +
+                         (size_t)p_begin * (kPieceFrags * 64);
 
-    uint4 wa[kPieceFrags], wb[kPieceFrags];
-    auto load_piece = [&](uint4* buf, const uint4* p) {
+    // Ring of weight pieces.  Every step of the main loop issues exactly kPieceFrags loads into
+    // the slot it has just consumed - a cache-resident dummy address once nothing is left - so
+    // the number of younger loads behind any slot is a compile-time constant and the wait
+    // before each MFMA is exact (a conditional load would force a full drain instead).
+    u32x4_t ring[kRing][kPieceFrags];
+    int ir = 0, ij = 0;                                  // next piece to issue: round, piece
+    auto issue = [&](u32x4_t* buf) {
+      wptr_t p = ir < my_tiles ? wbase + (size_t)ir * (4 * tile_stride) + (size_t)ij * (kPieceFrags * 64)
+                               : (wptr_t)a.Wp;
 #pragma unroll
       for (int f = 0; f < kPieceFrags; ++f)   // streamed once: do not keep it in the caches
-        buf[f] = __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p + (size_t)f * 64)));
+        buf[f] = __builtin_nontemporal_load(p + ((unsigned)lane + f * 64u));
+      if (++ij == np) {
+        ij = 0;
+        ++ir;
+      }
     };
-    // piece j of my tile ti
-    auto piece_ptr = [&](int ti, int j) {
-      return a.Wp + (size_t)(t_begin + wave + 4 * ti) * tile_stride +
-             (size_t)(p_begin + j) * (kPieceFrags * 64) + lane;
-    };
-
 
     float ssq[16];
 #pragma unroll
     for (int r = 0; r < 16; ++r) ssq[r] = 0.f;
 
     // Stage chunk c of this slice: wave w converts rows w, w+4, .. ; lane = 8-wide k chunk.
-    auto stage = [&](int c, bool first) {
-      const int nkc = min(2, np - 2 * c) * 32;     // 8-wide chunks per row in this K chunk
+    // `with_ring`: the ring is filled right behind the X loads (loads return in issue order,
+    // so X is not held up by the slower weight loads, and both overlap the conversion).
+    auto stage = [&](int c, bool with_ring) {
+      const int nkc = min(4, np - 4 * c) * 16;     // 8-wide chunks per row in this K chunk
       const bool on = lane < nkc;
-      const int k = (p_begin + 2 * c) * (2 * kBlkK) + (on ? lane : 0) * 8;
+      const int k = (p_begin + 4 * c) * kBlkK + (on ? lane : 0) * 8;
       float4 g0 = make_float4(1.f, 1.f, 1.f, 1.f), g1 = g0;
       if (PRO == PRO_GAIN) {
         g0 = *reinterpret_cast<const float4*>(a.gain + k);
@@ -209,9 +222,10 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
         xa[r] = *reinterpret_cast<const float4*>(p);
         xb[r] = *reinterpret_cast<const float4*>(p + 4);
       }
-      // the first weight piece goes out right behind the X loads: loads return in issue order,
-      // so X is not held up by the (slower, HBM) weight loads, and both overlap the conversion
-      if (first && my_tiles > 0 && np > 0) load_piece(wa, piece_ptr(0, 0));
+      if (with_ring) {
+#pragma unroll
+        for (int sl = 0; sl < kRing; ++sl) issue(ring[sl]);
+      }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int ml = wave + 4 * r;
@@ -274,89 +288,86 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
       // row index held by this lane: bit 3 from lane bit 5, bit 2 from bit 4, bit 1 from bit 3,
       // bit 0 from bit 2
       const int r = ((lane >> 5) & 1) * 8 + ((lane >> 4) & 1) * 4 + ((lane >> 3) & 1) * 2 + ((lane >> 2) & 1);
-      if ((lane & 3) == 0) a.sumsq[unit_id * kMTile + wave + 4 * r] = v1;
-      __builtin_amdgcn_s_waitcnt(0);
+      // (inline assembly for the same reason as the partial-tile stores below)
+      if ((lane & 3) == 0)
+        asm volatile("global_store_dword %0, %1, off" ::"v"(a.sumsq + unit_id * kMTile + wave + 4 * r), "v"(v1) : "memory");
     };
     stage(0, true);
     if (PRO == PRO_GAIN && n_chunks == 1) publish_ssq();
-    __syncthreads();
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // X chunk 0 is in LDS; weight loads stay in flight
 
     f32x16_t acc0 = {}, acc1 = {};
-    int ti = 0, j = 0;                       // piece being consumed: piece j of my tile ti
     const int rbase = 4 * (lane >> 5);
+    int cr = 0, cj = 0;                                  // piece being consumed: round, piece
 
-    // Consume the piece held in `cur` while the next one streams into `nxt`.
-    auto consume = [&](uint4* cur, uint4* nxt) {
-      int tin = ti, jn = j + 1;
-      if (jn == np) {
-        tin = ti + 1;
-        jn = 0;
-      }
-      if (tin < my_tiles) load_piece(nxt, piece_ptr(tin, jn));
-      const uint4* xf = xs + (size_t)((j & 1) * kPieceFrags * 4) * 64;
-#pragma unroll
-      for (int f = 0; f < kPieceFrags; ++f) {
-        // k-step inside the chunk: (j & 1) * 16 + f; its low 3 bits are those of f
-        const uint4* xp = xf + (size_t)(f * 4) * 64 + frag_slot(lane, f);
-        const bf16x8_t w = __builtin_bit_cast(bf16x8_t, cur[f]);
-        const bf16x8_t x0h = __builtin_bit_cast(bf16x8_t, xp[0]);
-        const bf16x8_t x0l = __builtin_bit_cast(bf16x8_t, xp[64]);
-        const bf16x8_t x1h = __builtin_bit_cast(bf16x8_t, xp[128]);
-        const bf16x8_t x1l = __builtin_bit_cast(bf16x8_t, xp[192]);
-        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0h, w, acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1h, w, acc1, 0, 0, 0);
-        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0l, w, acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1l, w, acc1, 0, 0, 0);
-      }
-      if (j == np - 1) {
-        // Tile finished.  The partial tile goes out in register order, [8 quads][64 lanes][4]
-        // floats (each store instruction writes 1 KiB contiguous); the reducer reads it back
-        // with the same lane -> register mapping.  Register r of lane l is row
-        // 8*(r/4) + 4*(l/32) + r%4 (+32 for acc1), column l % 32 of the [64][32] tile.
-        // The stores are issued from inline assembly on purpose: the compiler's wait-count
-        // bookkeeping then sees loads only and keeps waiting for exactly the weight fragment it
-        // needs next; a store it knew of would turn every later wait into a drain of the whole
-        // prefetch queue.  Unseen stores can only make its waits longer, never too short; their
-        // own completion is awaited explicitly before the arrival below.
-        const int tile = t_begin + wave + 4 * ti;
-        const float4* pt = reinterpret_cast<const float4*>(
-                               a.part + (((size_t)mt * n_tiles + tile) * S + sp) * kTileFloats) + lane;
-#pragma unroll
-        for (int qd = 0; qd < 4; ++qd) {
-          const f32x4_t v0 = {acc0[4 * qd], acc0[4 * qd + 1], acc0[4 * qd + 2], acc0[4 * qd + 3]};
-          const f32x4_t v1 = {acc1[4 * qd], acc1[4 * qd + 1], acc1[4 * qd + 2], acc1[4 * qd + 3]};
-          // s_nop: a store of more than 64 bits reads its data registers a few cycles after
-          // issue; the compiler cannot see that this is a store, so the wait states are explicit
-          asm volatile("global_store_dwordx4 %0, %1, off\n\ts_nop 3" ::"v"(pt + qd * 64), "v"(v0) : "memory");
-          asm volatile("global_store_dwordx4 %0, %1, off\n\ts_nop 3" ::"v"(pt + (qd + 4) * 64), "v"(v1) : "memory");
+    // One step: the piece in `buf` (piece cj of this wave's tile of round cr) is multiplied,
+    // the slot is refilled.  A slice longer than one LDS chunk (then every wave has at most one
+    // tile) re-stages X between chunks: all four waves take part, the accumulators carry over;
+    // the barriers around re-staging order LDS traffic only.
+    auto step = [&](u32x4_t* buf) {
+      if (cr < rounds) {
+        const int jq = cj & 3;
+        if (jq == 0 && cj > 0) {
+          asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+          stage(cj >> 2, false);
+          if (PRO == PRO_GAIN && (cj >> 2) == n_chunks - 1) publish_ssq();
+          asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
         }
+        if (cr < my_tiles) {
+          const uint4* xf = xs + (size_t)(jq * kPieceFrags * 4) * 64;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          acc0[r] = 0.f;
-          acc1[r] = 0.f;
+          for (int f = 0; f < kPieceFrags; ++f) {
+            // k-step inside the chunk: jq * 8 + f; its low 3 bits are those of f
+            const uint4* xp = xf + (size_t)(f * 4) * 64 + frag_slot(lane, f);
+            const bf16x8_t w = __builtin_bit_cast(bf16x8_t, buf[f]);
+            const bf16x8_t x0h = __builtin_bit_cast(bf16x8_t, xp[0]);
+            const bf16x8_t x0l = __builtin_bit_cast(bf16x8_t, xp[64]);
+            const bf16x8_t x1h = __builtin_bit_cast(bf16x8_t, xp[128]);
+            const bf16x8_t x1l = __builtin_bit_cast(bf16x8_t, xp[192]);
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0h, w, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1h, w, acc1, 0, 0, 0);
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0l, w, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1l, w, acc1, 0, 0, 0);
+          }
+          if (cj == np - 1) {
+            // Tile finished.  The partial tile goes out in register order, [8 quads][64 lanes][4]
+            // floats (each store instruction writes 1 KiB contiguous); the reducer reads it back
+            // with the same lane -> register mapping.  Register r of lane l is row
+            // 8*(r/4) + 4*(l/32) + r%4 (+32 for acc1), column l % 32 of the [64][32] tile.
+            // The stores are issued from inline assembly on purpose: the compiler's wait-count
+            // bookkeeping then sees loads only and keeps its waits exact; a store it knew of would
+            // turn every later wait into a drain of the whole ring.  Unseen stores can only make
+            // its waits longer, never too short; their own completion is awaited explicitly
+            // before the arrival below.
+            const int tile = t_begin + wave + 4 * cr;
+            const float4* pt = reinterpret_cast<const float4*>(
+                                   a.part + (((size_t)mt * n_tiles + tile) * S + sp) * kTileFloats) + lane;
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+              const f32x4_t v0 = {acc0[4 * qd], acc0[4 * qd + 1], acc0[4 * qd + 2], acc0[4 * qd + 3]};
+              const f32x4_t v1 = {acc1[4 * qd], acc1[4 * qd + 1], acc1[4 * qd + 2], acc1[4 * qd + 3]};
+              // s_nop: a store of more than 64 bits reads its data registers a few cycles after
+              // issue; the compiler cannot see that this is a store, so the wait states are explicit
+              asm volatile("global_store_dwordx4 %0, %1, off\n\ts_nop 3" ::"v"(pt + qd * 64), "v"(v0) : "memory");
+              asm volatile("global_store_dwordx4 %0, %1, off\n\ts_nop 3" ::"v"(pt + (qd + 4) * 64), "v"(v1) : "memory");
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              acc0[r] = 0.f;
+              acc1[r] = 0.f;
+            }
+          }
+        }
+        if (++cj == np) {
+          cj = 0;
+          ++cr;
         }
       }
-      ti = tin;
-      j = jn;
+      issue(buf);
     };
-
-    // One chunk (<= 2 pieces) per slice: every wave walks all its tiles.  Longer slices (only
-    // with at most one tile per wave): every wave takes part in re-staging X between chunks,
-    // its accumulators carry over.  The barriers around re-staging order LDS traffic only; they
-    // do not wait for the weight loads in flight.
-    bool flip = false;
-    for (int c = 0; c < n_chunks; ++c) {
-      if (c > 0) {
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        stage(c, false);
-        if (PRO == PRO_GAIN && c == n_chunks - 1) publish_ssq();
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-      }
-      const int n_here = n_chunks == 1 ? my_tiles * np : (my_tiles > 0 ? min(2, np - 2 * c) : 0);
-      for (int t = 0; t < n_here; ++t) {
-        if (!flip) consume(wa, wb); else consume(wb, wa);
-        flip = !flip;
-      }
+    while (cr < rounds) {
+#pragma unroll
+      for (int sl = 0; sl < kRing; ++sl) step(ring[sl]);
     }
 
     // ---- group barrier, then every wave of every slice reduces its share ----

@@ -87,17 +87,22 @@ class VerifyPass:
 
     # ---- one step ------------------------------------------------------------------
     def forward(self, n_layers: Optional[int] = None, want_logits: bool = True,
-                per_layer_calls: bool = False) -> None:
-        """All layers (sv_verify_stack, or one sv_verify_layer per layer), then the head."""
+                route: str = "stack") -> None:
+        """All layers, then the head.  route: "stack" (one sv_verify_stack call), "layers" (one
+        sv_verify_layer call per layer) or "persistent" (sv_verify_stack_persistent)."""
         self.x.copy_(self.x0)
         n = self.wc.n_layers if n_layers is None else n_layers
-        if per_layer_calls:
+        views = [kv.struct for kv in self.kv[:n]]
+        if route == "layers":
             for l in range(n):
-                sv.sv_verify_layer(self.cfg, self.packed[l], self.x, self.kv[l].struct,
-                                   self.tree.struct, self.B, self.workspace)
+                sv.sv_verify_layer(self.cfg, self.packed[l], self.x, views[l], self.tree.struct,
+                                   self.B, self.workspace)
+        elif route == "persistent":
+            sv.sv_verify_stack_persistent(self.cfg, self.packed[:n], self.x, views,
+                                          self.tree.struct, self.B, self.workspace)
         else:
-            sv.sv_verify_stack(self.cfg, self.packed[:n], self.x, [kv.struct for kv in self.kv[:n]],
-                               self.tree.struct, self.B, self.workspace)
+            sv.sv_verify_stack(self.cfg, self.packed[:n], self.x, views, self.tree.struct, self.B,
+                               self.workspace)
         sv.sv_action_head_argmax(self.cfg, self.g_final, self.w_lm, self.x, self.M, self.vocab_lo,
                                  self.vocab_hi, self.token, self.logits if want_logits else None,
                                  self.workspace)

@@ -47,7 +47,7 @@ def row_rel_err(gpu, ref):
 class SideBySide:
     """Outputs of one configuration from both sides."""
 
-    def __init__(self, cfg, n_layers=None, full_vocab=False, per_layer=True, tag=""):
+    def __init__(self, cfg, n_layers=None, full_vocab=False, per_layer=True, tag="", persistent=True):
         L = cfg.n_layers if n_layers is None else n_layers
         self.cfg = cfg = cfg.scaled(n_layers=L)
         B, T = cfg.n_episodes, cfg.tree_nodes
@@ -100,10 +100,21 @@ class SideBySide:
         self.gpu_logits = self.gpu.logits.cpu().numpy()
         self.gpu_token = self.gpu.token.cpu().numpy()
         self.gpu_x = self.gpu.x.cpu().numpy()
-        # sv_verify_stack (one persistent launch where it applies) and a sequence of
-        # sv_verify_layer calls do the same arithmetic in the same order
+        # the three routes do the same arithmetic in the same order: sv_verify_layer calls,
+        # sv_verify_stack, and (where it applies) the single persistent launch
         if x_layer_calls is not None:
             assert torch.equal(self.gpu.x, x_layer_calls), "stack and per-layer routes differ"
+        self.persistent_checked = False
+        if persistent:
+            try:
+                self.gpu.forward(want_logits=True, route="persistent")
+                torch.cuda.synchronize()
+                assert np.array_equal(self.gpu.x.cpu().numpy(), self.gpu_x), "persistent route differs"
+                assert np.array_equal(self.gpu.logits.cpu().numpy(), self.gpu_logits)
+                self.persistent_checked = True
+            except sv.SvError as e:
+                if e.status != sv.SV_ERR_SHAPE:
+                    raise
         self.logit_err = row_rel_err(self.gpu_logits, self.ref_logits)
         assert self.gpu.placement_status() == 0, "K slices of a tile ran on different XCDs"
 

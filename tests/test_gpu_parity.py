@@ -134,6 +134,7 @@ def test_bf16_small_model(T, B, P):
                        tree_nodes=T, n_episodes=B, prefix_lo=max(1, P - 50), prefix_hi=P,
                        max_children=6, r_values=(0, 4))
     s = SideBySide(cfg)
+    assert s.persistent_checked == (B * T <= 64)    # the single-launch route, where it applies
     check_forward(s, TOL["bf16"])
     check_accept_paths(s, (0, 4, 8))
 
@@ -142,6 +143,7 @@ def test_bf16_small_model(T, B, P):
 
 def test_c2_one_7b_layer_bf16():
     s = SideBySide(wl.C2.scaled(vocab=32000))
+    assert s.persistent_checked
     assert max(s.attn_err) <= TOL["bf16"] and max(s.x_err) <= TOL["bf16"]
     say(f"[C2] attn err {max(s.attn_err):.3e}, x err {max(s.x_err):.3e}")
 
@@ -164,6 +166,7 @@ def test_c5_long_prefix_two_layers():
 
 def test_c3_full_pass_32_layers():
     s = SideBySide(wl.C3)
+    assert s.persistent_checked
     n_ties = check_forward(s, TOL["bf16"])
     check_accept_paths(s, wl.C3.r_values)
     say(f"[C3] tolerated argmax near-ties: {n_ties} of {len(s.ref_token)} nodes")

@@ -111,3 +111,30 @@ def test_null_and_range_arguments_fail_before_any_launch():
                                16, None) == -5     # workspace too small
     assert lib.sv_action_head_argmax(C.byref(c1), one, one, one, 15, 300, 200, one, None, one,
                                      1 << 30, None) == -2
+
+
+def test_stack_calls_check_their_arguments_before_any_launch():
+    lib = sv.lib()
+    c7 = sv.model_cfg("bf16", 4096, 32, 128, 11008, 32000)
+    one = C.c_void_p(256)
+    tree = sv.Tree(256, 256, 256, 60, 1)
+    ptrs = (C.c_void_p * 2)(256, 512)
+    kvs = (sv.KvView * 2)(sv.KvView(256, 256, 256, 280, 384), sv.KvView(256, 256, 256, 280, 384))
+    big = 1 << 40
+    for fn, tail in ((lib.sv_verify_stack, ()), (lib.sv_verify_stack_persistent, (None, 0, None))):
+        assert fn(C.byref(c7), 2, None, one, kvs, C.byref(tree), 1, one, big, None, *tail) == -1
+        assert fn(C.byref(c7), 0, ptrs, one, kvs, C.byref(tree), 1, one, big, None, *tail) == -2
+        assert fn(C.byref(c7), 2, ptrs, one, kvs, C.byref(tree), 1, one, 16, None, *tail) == -5
+        bad = (C.c_void_p * 2)(256, 0)
+        assert fn(C.byref(c7), 2, bad, one, kvs, C.byref(tree), 1, one, big, None, *tail) == -1
+        odd = (C.c_void_p * 2)(256, 513)          # packed blobs are 256-byte aligned
+        assert fn(C.byref(c7), 2, odd, one, kvs, C.byref(tree), 1, one, big, None, *tail) == -5
+    # the single-launch form: float32 models and more than 64 rows are outside its reach
+    c1 = sv.model_cfg("f32", 256, 4, 64, 688, 512)
+    t15 = sv.Tree(256, 256, 256, 15, 1)
+    k1 = (sv.KvView * 1)(sv.KvView(256, 256, 256, 64, 128))
+    p1 = (C.c_void_p * 1)(256)
+    assert lib.sv_verify_stack_persistent(C.byref(c1), 1, p1, one, k1, C.byref(t15), 1, one, big,
+                                          None, None, 0, None) == -2
+    assert lib.sv_verify_stack_persistent(C.byref(c7), 2, ptrs, one, kvs, C.byref(tree), 2, one,
+                                          big, None, None, 0, None) == -2
