@@ -36,6 +36,8 @@
 #ifndef SV_GEMM_MFMA_H
 #define SV_GEMM_MFMA_H
 
+#include <type_traits>
+
 #include "sv_internal.h"
 
 namespace sv {
@@ -183,16 +185,22 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
     // the number of younger loads behind any slot is a compile-time constant and the wait
     // before each MFMA is exact (a conditional load would force a full drain instead).
     u32x4_t ring[kRing][kPieceFrags];
-    int ir = 0, ij = 0;                                  // next piece to issue: round, piece
+    // next piece to load: a running pointer (piece after piece, then a jump to this wave's next
+    // tile), so that issuing costs a handful of scalar instructions
+    wptr_t ip = my_tiles > 0 ? wbase : (wptr_t)a.Wp;
+    const size_t tile_jump = 4 * tile_stride - (size_t)np * (kPieceFrags * 64);
+    int ij = 0, it = 0;
     auto issue = [&](u32x4_t* buf) {
-      wptr_t p = ir < my_tiles ? wbase + (size_t)ir * (4 * tile_stride) + (size_t)ij * (kPieceFrags * 64)
-                               : (wptr_t)a.Wp;
 #pragma unroll
       for (int f = 0; f < kPieceFrags; ++f)   // streamed once: do not keep it in the caches
-        buf[f] = __builtin_nontemporal_load(p + ((unsigned)lane + f * 64u));
-      if (++ij == np) {
-        ij = 0;
-        ++ir;
+        buf[f] = __builtin_nontemporal_load(ip + ((unsigned)lane + f * 64u));
+      if (it < my_tiles) {
+        ip += kPieceFrags * 64;
+        if (++ij == np) {
+          ij = 0;
+          ip += tile_jump;
+          if (++it == my_tiles) ip = (wptr_t)a.Wp;
+        }
       }
     };
 
@@ -298,37 +306,72 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
 
     f32x16_t acc0 = {}, acc1 = {};
     const int rbase = 4 * (lane >> 5);
-    int cr = 0, cj = 0;                                  // piece being consumed: round, piece
+    const bool multi = n_chunks > 1;
+    int ct = 0, cj = 0;                                  // piece being consumed: tile count, piece
+    // a slice longer than one LDS chunk is walked by all four waves together (re-staging needs
+    // them all), also by a wave that has no tile; otherwise every wave just walks its own tiles
+    int steps_left = (multi ? rounds : my_tiles) * np;
+    // partial tile of this wave's current tile and this slice
+    const float4* pt = reinterpret_cast<const float4*>(a.part) + lane +
+                       (((size_t)mt * n_tiles + t_begin + wave) * S + sp) * (kTileFloats / 4);
 
-    // One step: the piece in `buf` (piece cj of this wave's tile of round cr) is multiplied,
-    // the slot is refilled.  A slice longer than one LDS chunk (then every wave has at most one
-    // tile) re-stages X between chunks: all four waves take part, the accumulators carry over;
-    // the barriers around re-staging order LDS traffic only.
+    // One step: the piece in `buf` (piece cj of this wave's current tile) is multiplied and the
+    // slot is refilled.  The loop is compute bound at one wave per SIMD, so the bookkeeping
+    // between the MFMA blocks is kept to a few scalar instructions: a tile's first product takes
+    // a zero addend instead of cleared accumulators, finished tiles are stored straight from the
+    // accumulator registers.
     auto step = [&](u32x4_t* buf) {
-      if (cr < rounds) {
+      if (steps_left > 0) {
+        --steps_left;
         const int jq = cj & 3;
-        if (jq == 0 && cj > 0) {
+        if (multi && jq == 0 && cj > 0) {
+          // re-stage X for the next chunk: the accumulators carry over; the barriers order LDS
+          // traffic only, weight loads stay in flight
           asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
           stage(cj >> 2, false);
           if (PRO == PRO_GAIN && (cj >> 2) == n_chunks - 1) publish_ssq();
           asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
         }
-        if (cr < my_tiles) {
+        if (ct < my_tiles) {
           const uint4* xf = xs + (size_t)(jq * kPieceFrags * 4) * 64;
+          // One basic block per piece: 32 LDS reads and 32 MFMAs.  The schedule is pinned so
+          // that the four X operands of fragment f + 1 are read while the MFMAs of fragment f
+          // run (left to itself the scheduler reads each operand right before its use, and the
+          // matrix pipe waits for LDS every time).  k-step inside the chunk: jq * 8 + f; its
+          // low 3 bits are those of f.
+          auto piece_block = [&](auto first_of_tile) {
+            constexpr bool kFirst = decltype(first_of_tile)::value;
 #pragma unroll
-          for (int f = 0; f < kPieceFrags; ++f) {
-            // k-step inside the chunk: jq * 8 + f; its low 3 bits are those of f
-            const uint4* xp = xf + (size_t)(f * 4) * 64 + frag_slot(lane, f);
-            const bf16x8_t w = __builtin_bit_cast(bf16x8_t, buf[f]);
-            const bf16x8_t x0h = __builtin_bit_cast(bf16x8_t, xp[0]);
-            const bf16x8_t x0l = __builtin_bit_cast(bf16x8_t, xp[64]);
-            const bf16x8_t x1h = __builtin_bit_cast(bf16x8_t, xp[128]);
-            const bf16x8_t x1l = __builtin_bit_cast(bf16x8_t, xp[192]);
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0h, w, acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1h, w, acc1, 0, 0, 0);
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0l, w, acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1l, w, acc1, 0, 0, 0);
-          }
+            for (int f = 0; f < kPieceFrags; ++f) {
+              const uint4* xp = xf + (size_t)(f * 4) * 64 + frag_slot(lane, f);
+              const bf16x8_t w = __builtin_bit_cast(bf16x8_t, buf[f]);
+              const bf16x8_t x0h = __builtin_bit_cast(bf16x8_t, xp[0]);
+              const bf16x8_t x0l = __builtin_bit_cast(bf16x8_t, xp[64]);
+              const bf16x8_t x1h = __builtin_bit_cast(bf16x8_t, xp[128]);
+              const bf16x8_t x1l = __builtin_bit_cast(bf16x8_t, xp[192]);
+              if (kFirst && f == 0) {                    // a tile's first product: zero addend
+                const f32x16_t zero = {};
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0h, w, zero, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1h, w, zero, 0, 0, 0);
+              } else {
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0h, w, acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1h, w, acc1, 0, 0, 0);
+              }
+              acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0l, w, acc0, 0, 0, 0);
+              acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1l, w, acc1, 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);       // LDS reads of fragment 0
+#pragma unroll
+            for (int f = 0; f < kPieceFrags - 1; ++f) {
+#pragma unroll
+              for (int q = 0; q < 4; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA of fragment f
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read of fragment f + 1
+              }
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+          };
+          if (cj == 0) piece_block(std::true_type{}); else piece_block(std::false_type{});
           if (cj == np - 1) {
             // Tile finished.  The partial tile goes out in register order, [8 quads][64 lanes][4]
             // floats (each store instruction writes 1 KiB contiguous); the reducer reads it back
@@ -339,9 +382,6 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
             // turn every later wait into a drain of the whole ring.  Unseen stores can only make
             // its waits longer, never too short; their own completion is awaited explicitly
             // before the arrival below.
-            const int tile = t_begin + wave + 4 * cr;
-            const float4* pt = reinterpret_cast<const float4*>(
-                                   a.part + (((size_t)mt * n_tiles + tile) * S + sp) * kTileFloats) + lane;
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
               const f32x4_t v0 = {acc0[4 * qd], acc0[4 * qd + 1], acc0[4 * qd + 2], acc0[4 * qd + 3]};
@@ -351,21 +391,17 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
               asm volatile("global_store_dwordx4 %0, %1, off\n\ts_nop 3" ::"v"(pt + qd * 64), "v"(v0) : "memory");
               asm volatile("global_store_dwordx4 %0, %1, off\n\ts_nop 3" ::"v"(pt + (qd + 4) * 64), "v"(v1) : "memory");
             }
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              acc0[r] = 0.f;
-              acc1[r] = 0.f;
-            }
+            pt += (size_t)4 * S * (kTileFloats / 4);     // this wave's next tile
           }
         }
         if (++cj == np) {
           cj = 0;
-          ++cr;
+          ++ct;
         }
       }
       issue(buf);
     };
-    while (cr < rounds) {
+    while (steps_left > 0) {
 #pragma unroll
       for (int sl = 0; sl < kRing; ++sl) step(ring[sl]);
     }
