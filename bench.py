@@ -1,6 +1,6 @@
 """Benchmark of one Spec-VLA tree-verification step on one MI355X.
 
-step = 32 x sv_verify_layer -> sv_action_head_argmax -> sv_relaxed_accept for the full
+step = sv_verify_stack (32 layers) -> sv_action_head_argmax -> sv_relaxed_accept for the full
 7B-shaped configuration (60-node tree, 280-token prefix, bf16 weights), all inputs resident
 in HBM.  Prints ONE JSON line: verified tree tokens/s, step latency, the HBM roofline of the
 dominant kernel (the weight-streaming GEMM, timed live with HIP events) and the CPU oracle
@@ -18,6 +18,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM-side bytes per launch of the dominant kernel (average over the four GEMM launches of a
+# layer), from the two rocprofv3 --pmc runs summarised in profiles/c3_step_hbm_traffic.txt:
+# fetched (FETCH_SIZE x 2, calibrated with a 1 GiB copy) + written (WRITE_SIZE x 1):
+# gate/up 234.2 + 47.8, q/k/v 134.6 + 27.2, output and down 86.3 + 9.4 each (MB).
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = (234.21 + 47.81 + 134.55 + 27.21 + 2 * (86.27 + 9.39)) / 4 * 1e6
 
 
 def log(msg):
@@ -187,7 +192,8 @@ def main():
         "kernel_ms_per_step": per_step_ms,
         "roofline": {"bound": "hbm", "kernel": "gemm_stream_bf16 (4 launches per layer: q/k/v, o, gate/up, down)",
                      "achieved": gemm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": gemm_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "frac": gemm_gbs / HBM_PEAK_GBS, "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH,
+                     "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/c3_step_hbm_traffic.txt",
                      "bytes_per_launch_avg": weights_total / (4 * L),
                      "avg_launch_us": gemm_ms * 1e3 / (4 * L)},
     }
