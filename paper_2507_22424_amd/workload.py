@@ -208,6 +208,37 @@ def episode_tree(cfg: VerifyConfig, episode: int) -> np.ndarray:
     return draft_tree(cfg.tree_nodes, cfg.max_depth, cfg.max_children, spine, rng)
 
 
+def candidate_forest(top_k: int, depth: int, seed: int, n_bins: int = 256, action_lo: int = 0):
+    """Synthetic record of a drafter's top-K predictions, level by level, shaped like a
+    dynamic draft tree's candidates (Sec. 4.1, Sec. 5.1: top 8, depth 4-5): level 1 holds
+    top_k children of the root; at every further level the top_k candidates of the level
+    above with the highest joint log-probability are expanded, each into top_k children.
+    Log-probabilities are the top_k entries of a log-softmax over random logits.
+    Returns dict(parent int32 [n] (-1 = child of the root, else an earlier candidate),
+    logp float32 [n], token int32 [n]); n = top_k + (depth - 1) * top_k**2."""
+    rng = np.random.Generator(np.random.PCG64(S0 + 7919 * seed + 17))
+    parent, logp, token, joint = [], [], [], []
+
+    def children(of: int, base: float):
+        logits = rng.standard_normal(n_bins) * 2.0
+        lsm = logits - np.log(np.sum(np.exp(logits)))
+        top = np.argsort(-lsm, kind="stable")[:top_k]
+        for t in top:
+            parent.append(of); logp.append(np.float32(lsm[t])); token.append(action_lo + int(t))
+            joint.append(base + float(np.float32(lsm[t])))
+
+    children(-1, 0.0)
+    level = list(range(top_k))
+    for _ in range(depth - 1):
+        expand = sorted(level, key=lambda c: (-joint[c], c))[:top_k]
+        first = len(parent)
+        for c in sorted(expand):
+            children(c, joint[c])
+        level = list(range(first, len(parent)))
+    return {"parent": np.asarray(parent, dtype=np.int32), "logp": np.asarray(logp, dtype=np.float32),
+            "token": np.asarray(token, dtype=np.int32)}
+
+
 def uniform_draft_tokens(cfg: VerifyConfig, episode: int) -> np.ndarray:
     """Draft ids uniform over the action tokens (entry 0, the root, is unused)."""
     rng = np.random.Generator(np.random.PCG64(seed_for(cfg, episode, 996)))
