@@ -145,6 +145,28 @@ int sv_workspace_init(const sv_model_cfg *cfg, int B, int T, int n_scored, void 
 int sv_workspace_region(const sv_model_cfg *cfg, int B, int T, int n_scored, int which,
                         size_t *offset, size_t *bytes);
 
+/* The draft tree of every episode, built on the device from the recorded top-K predictions of
+ * the draft model (Sec. 4.1: those predictions form a tree with several paths; Sec. 5.1: top 8,
+ * at most 50 nodes).  Candidate c of an episode has a parent (an earlier candidate, or -1 =
+ * the root), a token and the log-probability the drafter gave it; its score is the joint
+ * log-probability of its path, accumulated in float32 from the root down.  The T - 1 best
+ * candidates are kept (lower candidate index wins ties), numbered breadth first behind the
+ * root (by depth, then candidate index).  The outputs are what sv_tree / sv_relaxed_accept
+ * take.
+ *   cand_parent, cand_token: [device] int32 [B, n_cand];  cand_logp: [device] float32 [B, n_cand]
+ *   root_token: [device] int32 [B] (becomes draft_token of node 0)
+ *   parent, depth, draft_token: [device, out] int32 [B, T];  anc_mask: [device, out] uint64
+ *   [B, T, ceil(T/64)];  status: [device, out] int32 [B]: 0 = ok, bit 0 = some cand_parent is
+ *   not an earlier candidate, bit 1 = a kept candidate is deeper than d_cap, bit 2 = a kept
+ *   candidate's parent was not kept (log-probabilities above zero); a flagged episode gets a
+ *   valid placeholder tree (all nodes children of the root).
+ * SV_ERR_SHAPE unless 1 <= T <= SV_MAX_TREE_NODES, T - 1 <= n_cand <= 1024, B >= 1,
+ * 0 <= d_cap <= SV_MAX_DEPTH.  Nothing is read on the host. */
+int sv_tree_build_device(const int32_t *cand_parent, const float *cand_logp,
+                         const int32_t *cand_token, int n_cand, const int32_t *root_token, int B,
+                         int T, int d_cap, int32_t *parent, int32_t *depth, uint64_t *anc_mask,
+                         int32_t *draft_token, int32_t *status, void *stream);
+
 /* One decoder layer over all B*T tree nodes (Alg. 1's parallel verification, one layer of
  * M_V): RMSNorm, q/k/v projections, RoPE at position prefix_len[b] + depth, append of the
  * tree's keys/values to the cache, attention of node i over {prefix keys} + {tree nodes on

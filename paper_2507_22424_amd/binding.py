@@ -27,7 +27,7 @@ EXPORTS = ("sv_version", "sv_strerror", "sv_tree_build_masks", "sv_packed_layer_
            "sv_verify_layer",
            "sv_verify_layer_timed", "sv_verify_stack", "sv_verify_stack_persistent",
            "sv_action_head_argmax", "sv_relaxed_accept",
-           "sv_commit_path", "sv_advance_prefix")
+           "sv_commit_path", "sv_advance_prefix", "sv_tree_build_device")
 SV_N_TIMING_EVENTS = 9
 SV_TIMELINE_SLOTS = 16
 
@@ -100,6 +100,9 @@ def lib() -> C.CDLL:
         l.sv_commit_path.argtypes = [C.POINTER(ModelCfg), C.POINTER(KvView), C.c_int, C.c_void_p,
                                      C.c_void_p, C.c_int, C.c_int, C.c_void_p]
         l.sv_advance_prefix.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
+        l.sv_tree_build_device.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
+                                           C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = l
     return _lib
 
@@ -299,6 +302,25 @@ def sv_advance_prefix(prefix_len: torch.Tensor, accepted_len: torch.Tensor, B: i
     _check(lib().sv_advance_prefix(_dev(prefix_len, torch.int32, "prefix_len"),
                                    _dev(accepted_len, torch.int32, "accepted_len"), B, d_cap,
                                    _stream(stream)), "sv_advance_prefix")
+
+
+def sv_tree_build_device(cand_parent: torch.Tensor, cand_logp: torch.Tensor, cand_token: torch.Tensor,
+                         root_token: torch.Tensor, B: int, T: int, d_cap: int, parent: torch.Tensor,
+                         depth: torch.Tensor, anc_mask: torch.Tensor, draft_token: torch.Tensor,
+                         status: torch.Tensor, stream=None) -> None:
+    n_cand = cand_parent.numel() // B
+    W = (T + 63) // 64
+    if (cand_parent.numel() != B * n_cand or cand_logp.numel() != B * n_cand or
+            cand_token.numel() != B * n_cand or root_token.numel() != B or parent.numel() != B * T or
+            depth.numel() != B * T or draft_token.numel() != B * T or anc_mask.numel() != B * T * W or
+            status.numel() != B):
+        raise ValueError("tree_build_device: tensor sizes do not match B, T, n_cand")
+    _check(lib().sv_tree_build_device(
+        _dev(cand_parent, torch.int32, "cand_parent"), _dev(cand_logp, torch.float32, "cand_logp"),
+        _dev(cand_token, torch.int32, "cand_token"), n_cand, _dev(root_token, torch.int32, "root_token"),
+        B, T, d_cap, _dev(parent, torch.int32, "parent"), _dev(depth, torch.int32, "depth"),
+        _dev(anc_mask, torch.int64, "anc_mask"), _dev(draft_token, torch.int32, "draft_token"),
+        _dev(status, torch.int32, "status"), _stream(stream)), "sv_tree_build_device")
 
 
 # ---- holders that keep the device tensors behind the C structs alive -------------------

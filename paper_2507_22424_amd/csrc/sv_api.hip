@@ -13,6 +13,7 @@
 #include "sv_internal.h"
 #include "sv_kernels.h"
 #include "sv_stack_persistent.h"
+#include "sv_tree_build.h"
 
 namespace sv {
 
@@ -631,6 +632,22 @@ int sv_relaxed_accept(const sv_tree* tree, const int32_t* draft_token,
   relaxed_accept_kernel<<<B, 128, 0, (hipStream_t)stream>>>(
       tree->parent, tree->depth, tree->anc_mask, T, tree->n_words, draft_token, target_token,
       action_lo, n_bins, r, d_cap, accept_mask, accepted_len, best_node, path, out_tokens);
+  return launch_status();
+}
+
+int sv_tree_build_device(const int32_t* cand_parent, const float* cand_logp,
+                         const int32_t* cand_token, int n_cand, const int32_t* root_token, int B,
+                         int T, int d_cap, int32_t* parent, int32_t* depth, uint64_t* anc_mask,
+                         int32_t* draft_token, int32_t* status, void* stream) {
+  if (!cand_parent || !cand_logp || !cand_token || !root_token || !parent || !depth || !anc_mask ||
+      !draft_token || !status)
+    return SV_ERR_NULL;
+  if (B < 1 || B > (1 << 15) || T < 1 || T > SV_MAX_TREE_NODES || n_cand < T - 1 ||
+      n_cand > kMaxCandidates || d_cap < 0 || d_cap > SV_MAX_DEPTH)
+    return SV_ERR_SHAPE;
+  tree_build_kernel<<<B, 256, 0, (hipStream_t)stream>>>(cand_parent, cand_logp, cand_token, n_cand,
+                                                        root_token, T, (T + 63) / 64, d_cap, parent,
+                                                        depth, anc_mask, draft_token, status);
   return launch_status();
 }
 

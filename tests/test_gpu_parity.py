@@ -341,3 +341,98 @@ def test_commit_path_moves_exactly_the_accepted_rows(dtype):
             want_v[:, P + i] = v0[b][:, P + path[b, i]]
         assert torch.equal(k1[b], want_k) and torch.equal(v1[b], want_v), b
     assert kv.prefix_len.cpu().tolist() == [p + int(a) + 1 for p, a in zip(prefix, alen)]
+
+
+# ---- draft tree built on the device from recorded drafter candidates ------------------------
+
+def test_device_built_draft_tree_matches_the_oracle_and_feeds_the_verifier():
+    """sv_tree_build_device against oracle/draft_tree.py, bit for bit (paper's setting: top 8,
+    depth 5, 50 nodes; plus a 2-word mask case), then one layer + accept on the device-built
+    arrays equals the same calls on a host-built copy of that tree."""
+    from oracle import draft_tree as dt
+    for (top_k, depth, T, B) in ((8, 5, 50, 3), (8, 4, 50, 2), (6, 7, 128, 2), (4, 3, 1, 1)):
+        forests = [wl.candidate_forest(top_k, depth, seed=31 * b + T, n_bins=256, action_lo=768)
+                   for b in range(B)]
+        n_cand = len(forests[0]["parent"])
+        root = np.array([768 + 5 + b for b in range(B)], dtype=np.int32)
+        dev = lambda a, dtp: torch.from_numpy(np.ascontiguousarray(np.stack(a)).astype(dtp)).cuda()
+        W = (T + 63) // 64
+        parent = torch.full((B, T), -7, dtype=torch.int32, device="cuda")
+        depth_t = torch.full((B, T), -7, dtype=torch.int32, device="cuda")
+        token = torch.full((B, T), -7, dtype=torch.int32, device="cuda")
+        anc = torch.full((B, T, W), -1, dtype=torch.int64, device="cuda")
+        status = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+        sv.sv_tree_build_device(dev([f["parent"] for f in forests], np.int32),
+                                dev([f["logp"] for f in forests], np.float32),
+                                dev([f["token"] for f in forests], np.int32),
+                                torch.from_numpy(root).cuda(), B, T, depth, parent, depth_t, anc,
+                                token, status)
+        torch.cuda.synchronize()
+        assert status.cpu().tolist() == [0] * B
+        for b, f in enumerate(forests):
+            ref = dt.build_draft_tree(f["parent"], f["logp"], f["token"], int(root[b]), T)
+            assert parent[b].cpu().tolist() == ref["parent"].tolist(), (T, b)
+            assert depth_t[b].cpu().tolist() == ref["depth"].tolist()
+            assert token[b].cpu().tolist() == ref["token"].tolist()
+            _, anc_ref = vo.tree_structure(ref["parent"])
+            got = anc[b].cpu().numpy().view(np.uint64)
+            for i in range(T):
+                bits = [j for j in range(T) if (int(got[i, j >> 6]) >> (j & 63)) & 1]
+                assert bits == np.flatnonzero(anc_ref[i]).tolist()
+        say(f"[tree-build] top-{top_k} depth {depth} -> {T} nodes x {B} episodes: exact")
+
+    # the verifier on the device-built arrays (no host round trip) = the verifier on a
+    # host-built copy of the same tree
+    cfg = wl.C1.scaled(name="tree-dev", index=14, tree_nodes=15, max_depth=3)
+    f = wl.candidate_forest(4, 3, seed=77, n_bins=cfg.n_bins, action_lo=cfg.action_lo)
+    ref = dt.build_draft_tree(f["parent"], f["logp"], f["token"], cfg.action_lo + 1, 15)
+    vp = VerifyPass(cfg, [40], ref["parent"])
+    vp.load_layer(0, wl.layer_weights(cfg, 0))
+    vp.load_prefix(0, 0, *wl.prefix_kv(cfg, 0, 0, 40))
+    head = wl.head_weights(cfg)
+    vp.load_head(head["g_final"], head["w_lm"])
+    vp.set_hidden(wl.hidden_rows(cfg, 0))
+    vp.set_draft(ref["token"])
+    vp.step(2, want_logits=True)
+    torch.cuda.synchronize()
+    host = (vp.logits.clone(), vp.accepted_len.clone(), vp.out_tokens.clone(), vp.accept_mask.clone())
+    d_par = torch.zeros(15, dtype=torch.int32, device="cuda")
+    d_dep, d_tok = torch.zeros_like(d_par), torch.zeros_like(d_par)
+    d_anc = torch.zeros(15, 1, dtype=torch.int64, device="cuda")
+    d_st = torch.zeros(1, dtype=torch.int32, device="cuda")
+    one = lambda a, dtp: torch.from_numpy(np.ascontiguousarray(a).astype(dtp)).cuda()
+    sv.sv_tree_build_device(one(f["parent"], np.int32), one(f["logp"], np.float32), one(f["token"], np.int32),
+                            one([cfg.action_lo + 1], np.int32), 1, 15, 3, d_par, d_dep, d_anc, d_tok, d_st)
+    vp.tree.struct = sv.Tree(d_par.data_ptr(), d_dep.data_ptr(), d_anc.data_ptr(), 15, 1)
+    vp.draft.copy_(d_tok)
+    vp.step(2, want_logits=True)
+    torch.cuda.synchronize()
+    assert int(d_st[0]) == 0
+    for a, b in zip(host, (vp.logits, vp.accepted_len, vp.out_tokens, vp.accept_mask)):
+        assert torch.equal(a, b)
+
+
+def test_device_tree_build_flags_bad_candidates_and_stays_in_bounds():
+    B, T, n = 3, 10, 12
+    par = np.tile(np.arange(-1, n - 1, dtype=np.int32), (B, 1))       # chains
+    par[0, 5] = 7                                                      # parent listed later
+    lp = np.full((B, n), -0.5, dtype=np.float32)
+    lp[2, 6] = 3.0                                                     # "log-probability" above 0
+    lp[1, 3] = np.nan                                                  # sorts last, still a tree
+    tok = np.zeros((B, n), dtype=np.int32)
+    out = [torch.zeros(B, T, dtype=torch.int32, device="cuda") for _ in range(3)]
+    anc = torch.zeros(B, T, 1, dtype=torch.int64, device="cuda")
+    status = torch.zeros(B, dtype=torch.int32, device="cuda")
+    sv.sv_tree_build_device(torch.from_numpy(par).cuda(), torch.from_numpy(lp).cuda(),
+                            torch.from_numpy(tok).cuda(), torch.zeros(B, dtype=torch.int32, device="cuda"),
+                            B, T, 4, out[0], out[1], anc, out[2], status)
+    torch.cuda.synchronize()
+    st = status.cpu().tolist()
+    assert st[0] & 1 and st[2] & 4
+    for b in range(B):                     # whatever the status, the arrays describe a valid tree
+        p = out[0][b].cpu().tolist()
+        assert p[0] == -1 and all(0 <= p[i] < i for i in range(1, T))
+    # episode 1: the NaN candidate and everything below it rank last: a chain of three + ... no:
+    # only candidates 0..2 have finite scores, the other kept ones tie at -inf in index order,
+    # which is deeper than d_cap = 4 -> flagged
+    assert st[1] & 2
