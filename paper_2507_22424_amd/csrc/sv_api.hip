@@ -83,7 +83,8 @@ static WorkspaceLayout workspace_layout(const sv_model_cfg& c, int m_rows, int n
     L.counter_bytes = align_up((mt * (tiles_max + kXcds) * 2 + 64) * sizeof(int), kAlign);   // group counters + status word
     L.counters = o; o += L.counter_bytes;
     L.sumsq = o;    o = align_up(o + mt * (tiles_max + kXcds) * s_max * kMTile * 4, kAlign);
-    L.part = o;     o = align_up(o + mt * tiles_max * s_max * kTileFloats * 4, kAlign);
+    L.part_bytes = align_up(mt * tiles_max * s_max * kTileFloats * 4, 2 * kAlign);
+    L.part = o;     o += L.part_bytes;
     L.xhat = o;
     L.stack_ctl = L.stack_ctl_bytes = L.stack_sumsq = L.stack_part = L.stack_part_bytes = 0;
     if (mt == 1) {
@@ -100,7 +101,8 @@ static WorkspaceLayout workspace_layout(const sv_model_cfg& c, int m_rows, int n
     L.stack_ctl = L.stack_ctl_bytes = L.stack_sumsq = L.stack_part = L.stack_part_bytes = 0;
     L.counter_bytes = 0;
     L.counters = L.sumsq = o;
-    L.part = o;     o = align_up(o + mp * n_max * 4, kAlign);
+    L.part_bytes = align_up(mp * n_max * 4, kAlign);
+    L.part = o;     o += L.part_bytes;
     L.xhat = o;     o = align_up(o + mp * H * 4, kAlign);
   }
   L.q = o;           o = align_up(o + mp * D * 4, kAlign);
@@ -197,7 +199,9 @@ static int verify_layer_bf16(const sv_model_cfg& c, const char* packed, float* x
   memset(&a, 0, sizeof(a));
   a.M = M;
   a.n_xcd = n_xcd;
-  a.part = (float*)(ws + wl.part);
+  // partial tiles: packed data in the first half of the region, one inverse scale per tile behind it
+  a.part16 = (uint4*)(ws + wl.part);
+  a.pscale = (float*)(ws + wl.part + wl.part_bytes / 2);
   a.sumsq = (float*)(ws + wl.sumsq);
   a.group_cnt = counters;
   a.status = (int*)(ws + wl.counters + wl.counter_bytes) - 1;   // last word of the counter region
@@ -278,11 +282,11 @@ static bool stack_plan(const sv_model_cfg& c, int n_layers, const void* const* p
     a->plan[ph] = PhasePlan{NK[ph][0], NK[ph][1], p.S, p.gpx};
     const PhaseGeom g0 = phase_geom(a->plan[ph], n_xcd, 0, 0);
     if (g0.n_chunks > 1 && g0.t_max > 4) return false;     // accumulators of one tile per wave only
-    const size_t need = (size_t)p.gpx * g0.t_max * p.S * kTileFloats;
+    const size_t need = (size_t)p.gpx * g0.t_max * p.S;        // partial tiles per XCD
     if (need > part_xcd) part_xcd = need;
     if (n_xcd * p.gpx > gmax) gmax = n_xcd * p.gpx;
   }
-  if (gmax > 256 || part_xcd * n_xcd * 4 > wl.stack_part_bytes) return false;
+  if (gmax > 256 || part_xcd * n_xcd * kTileFloats * 4 > wl.stack_part_bytes) return false;
   for (int l = 0; l < n_layers; ++l) {
     a->L[l].packed = (const unsigned char*)packed[l];
     a->L[l].kc = (bf16_t*)kv[l].k;
@@ -297,8 +301,9 @@ static bool stack_plan(const sv_model_cfg& c, int n_layers, const void* const* p
   d->q = (float*)(ws + wl.q);
   d->attn = (float*)(ws + wl.attn);
   d->act = (float*)(ws + wl.act);
-  d->part = (float*)(ws + wl.stack_part);
-  a->part_xcd_floats = part_xcd;
+  d->part16 = (uint4*)(ws + wl.stack_part);           // data in the first half, scales behind
+  d->pscale = (float*)(ws + wl.stack_part + wl.stack_part_bytes / 2);
+  a->part_xcd_tiles = part_xcd;
   d->sumsq = (float*)(ws + wl.stack_sumsq);
   char* ctl = ws + wl.stack_ctl;
   d->group_cnt = (unsigned long long*)ctl;

@@ -53,7 +53,8 @@ constexpr int kBlkK = 128;       // granularity of K slices (8 fragments)
 constexpr int kChunkBlks = 4;    // K blocks of X resident in LDS at a time (512 k-values = 2 pieces)
 constexpr int kPieceFrags = 8;   // fragments per ring slot: 128 k-values, 8 KiB per wave
 constexpr int kRing = 4;         // ring slots: 32 KiB of weights in flight per wave
-constexpr int kTileFloats = kMTile * kFragRows;   // one partial tile, [64][32] float32
+constexpr int kTileFloats = kMTile * kFragRows;   // one partial tile, [64][32] values
+constexpr int kTileVec4 = kTileFloats / 8;        // .. as stored: scaled int16 pairs, [4][64 lanes] uint4 = 4 KiB
 constexpr int kXcds = 8;
 constexpr int kRedBatch = 6;       // reduction work items whose loads are in flight together
 
@@ -95,7 +96,8 @@ struct GemmArgs {
   int S;                 // K slices
   int gpx;               // tile groups per XCD (units per XCD = gpx * S)
   int n_xcd;             // XCDs of the device (8 on MI355X; 1 for a single-XCD partition)
-  float* part;           // [m_tiles][N/32][S][64][32] partial tiles
+  uint4* part16;         // [m_tiles][N/32][S] partial tiles, kTileVec4 uint4 each (scaled int16)
+  float* pscale;         // [m_tiles][N/32][S] inverse scale of each partial tile
   float* sumsq;          // [m_tiles][n_xcd*gpx][S][64] partial row sums of x^2 (PRO_GAIN)
   unsigned* group_cnt;   // [m_tiles][groups][2] arrival (4 bits per XCD) / departure counters, zero between launches
   int* status;           // sticky: != 0 once slices of one tile were seen on different XCDs
@@ -121,6 +123,46 @@ __device__ inline uint32_t pack_bf16x2(float a, float b) {
 }
 __device__ inline float bf16_lo_f32(uint32_t packed) { return __uint_as_float(packed << 16); }
 __device__ inline float bf16_hi_f32(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
+
+// ---- partial tiles in transit: 16-bit fixed point with one power-of-two scale per tile -----
+// A split-K partial tile is written once and read once; its bytes are HBM traffic on top of the
+// weights (the L2 does not hold them until the reduction).  Stored as int16 pairs, scaled by a
+// power of two that brings the tile's largest magnitude into [2^13, 2^14), they cost half the
+// bytes of float32, cannot overflow whatever the activations, and carry an absolute error of at
+// most 2^-14 of the tile maximum (what matters downstream is the error against the size of the
+// row, not of the single element; fp16 with its 11-bit mantissa measured 6 times worse there).
+// A tile that holds an infinity or a NaN is marked by a NaN scale and reads back as NaN.
+// Register r (0..31: the two accumulators of a wave, see the layout at the tile store) goes to
+// half r % 2 of dword r / 2 of the lane; dwords 4q..4q+3 form the lane's uint4 of store q.
+
+// |v| as an integer that orders like the magnitude, NaN above infinity above all numbers
+__device__ inline unsigned mag_bits(float v) { return __float_as_uint(v) & 0x7fffffffu; }
+__device__ inline unsigned wave_max_u32(unsigned v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const unsigned o = (unsigned)__shfl_xor((int)v, off, kWave);
+    v = v > o ? v : o;
+  }
+  return v;
+}
+// scale = 2^(13 - e) for a tile maximum in [2^e, 2^(e+1)), inv = 1 / scale (exponents clamped so
+// that both stay normal numbers); a non-finite maximum gives scale 0 and inv NaN.
+__device__ inline void partial_tile_scale(unsigned max_bits, float& scale, float& inv) {
+  const unsigned eb = max_bits >> 23;
+  unsigned se = 267u - eb;                 // >= 13 for every finite maximum
+  se = se > 240u ? 240u : se;
+  scale = eb == 255u ? 0.f : __uint_as_float(se << 23);
+  inv = eb == 255u ? __uint_as_float(0x7fc00000u) : __uint_as_float((254u - se) << 23);
+}
+// two values -> int16 pair, round to nearest even: adding 1.5 * 2^23 leaves the rounded integer
+// in the low mantissa bits (|a * scale| < 2^14 here)
+__device__ inline unsigned pack_q16x2(float a, float b, float scale) {
+  const unsigned ua = __float_as_uint(fmaf(a, scale, 12582912.0f));
+  const unsigned ub = __float_as_uint(fmaf(b, scale, 12582912.0f));
+  return (ua & 0xffffu) | (ub << 16);
+}
+__device__ inline float q16_lo(unsigned d) { return (float)((int)(d << 16) >> 16); }
+__device__ inline float q16_hi(unsigned d) { return (float)((int)d >> 16); }
 
 // XCD (accelerator complex die) this wave runs on: bits 3:0 of the XCC_ID hardware register.
 __device__ inline int xcd_actual(int n_xcd) {
@@ -311,9 +353,10 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
     // a slice longer than one LDS chunk is walked by all four waves together (re-staging needs
     // them all), also by a wave that has no tile; otherwise every wave just walks its own tiles
     int steps_left = (multi ? rounds : my_tiles) * np;
-    // partial tile of this wave's current tile and this slice
-    const float4* pt = reinterpret_cast<const float4*>(a.part) + lane +
-                       (((size_t)mt * n_tiles + t_begin + wave) * S + sp) * (kTileFloats / 4);
+    // partial tile of this wave's current tile and this slice (data, inverse scale)
+    const size_t pidx0 = ((size_t)mt * n_tiles + t_begin + wave) * S + sp;
+    const uint4* pt = a.part16 + pidx0 * kTileVec4 + lane;
+    const float* ps = a.pscale + pidx0;
 
     // One step: the piece in `buf` (piece cj of this wave's current tile) is multiplied and the
     // slot is refilled.  The loop is compute bound at one wave per SIMD, so the bookkeeping
@@ -373,25 +416,39 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
           };
           if (cj == 0) piece_block(std::true_type{}); else piece_block(std::false_type{});
           if (cj == np - 1) {
-            // Tile finished.  The partial tile goes out in register order, [8 quads][64 lanes][4]
-            // floats (each store instruction writes 1 KiB contiguous); the reducer reads it back
-            // with the same lane -> register mapping.  Register r of lane l is row
+            // Tile finished.  The partial tile goes out in register order as scaled int16 pairs
+            // (each store instruction writes 1 KiB contiguous); the reducer reads it back with
+            // the same lane -> register mapping.  Register r of lane l is row
             // 8*(r/4) + 4*(l/32) + r%4 (+32 for acc1), column l % 32 of the [64][32] tile.
             // The stores are issued from inline assembly on purpose: the compiler's wait-count
             // bookkeeping then sees loads only and keeps its waits exact; a store it knew of would
             // turn every later wait into a drain of the whole ring.  Unseen stores can only make
             // its waits longer, never too short; their own completion is awaited explicitly
             // before the arrival below.
+            unsigned tmax = 0u;
 #pragma unroll
-            for (int qd = 0; qd < 4; ++qd) {
-              const f32x4_t v0 = {acc0[4 * qd], acc0[4 * qd + 1], acc0[4 * qd + 2], acc0[4 * qd + 3]};
-              const f32x4_t v1 = {acc1[4 * qd], acc1[4 * qd + 1], acc1[4 * qd + 2], acc1[4 * qd + 3]};
+            for (int r = 0; r < 16; ++r) {
+              const unsigned m0_ = mag_bits(acc0[r]), m1_ = mag_bits(acc1[r]);
+              const unsigned mm = m0_ > m1_ ? m0_ : m1_;
+              tmax = tmax > mm ? tmax : mm;
+            }
+            float psc, pinv;
+            partial_tile_scale(wave_max_u32(tmax), psc, pinv);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              u32x4_t d;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const int r = 8 * (q & 1) + 2 * e;       // register inside acc0 (q < 2) or acc1
+                d[e] = q < 2 ? pack_q16x2(acc0[r], acc0[r + 1], psc) : pack_q16x2(acc1[r], acc1[r + 1], psc);
+              }
               // s_nop: a store of more than 64 bits reads its data registers a few cycles after
               // issue; the compiler cannot see that this is a store, so the wait states are explicit
-              asm volatile("global_store_dwordx4 %0, %1, off\n\ts_nop 3" ::"v"(pt + qd * 64), "v"(v0) : "memory");
-              asm volatile("global_store_dwordx4 %0, %1, off\n\ts_nop 3" ::"v"(pt + (qd + 4) * 64), "v"(v1) : "memory");
+              asm volatile("global_store_dwordx4 %0, %1, off\n\ts_nop 3" ::"v"(pt + q * 64), "v"(d) : "memory");
             }
-            pt += (size_t)4 * S * (kTileFloats / 4);     // this wave's next tile
+            if (lane == 0) asm volatile("global_store_dword %0, %1, off" ::"v"(ps), "v"(pinv) : "memory");
+            ps += 4 * S;
+            pt += (size_t)4 * S * kTileVec4;             // this wave's next tile
           }
         }
         if (++cj == np) {
@@ -451,7 +508,8 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
     const int n_items = t_count * 8;
     if (PRO == PRO_GAIN) __syncthreads();    // s_rstd is complete
     for (int it0 = sp + S * wave; it0 < n_items; it0 += 4 * S * kRedBatch) {
-      float4 part[kRedBatch][8];
+      uint2 part[kRedBatch][8];
+      float pinv[kRedBatch][8];
       float xres[kRedBatch][4];
 #pragma unroll
       for (int bi = 0; bi < kRedBatch; ++bi) {                        // all loads of the batch first
@@ -459,12 +517,14 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
         if (it >= n_items) break;
         const int tile = t_begin + (it >> 3), qd = it & 7;
         const int row0 = 8 * (qd & 3) + rbase + 32 * (qd >> 2);
-        const float4* pb = reinterpret_cast<const float4*>(
-                               a.part + ((size_t)mt * n_tiles + tile) * S * kTileFloats) + qd * 64 + lane;
+        // registers 4qd .. 4qd+3 of the tile = dwords 2qd, 2qd+1 = half of the uint4 of store qd/2
+        const size_t pidx = ((size_t)mt * n_tiles + tile) * S;
+        const uint2* pb = reinterpret_cast<const uint2*>(a.part16 + pidx * kTileVec4 + (qd >> 1) * 64 + lane) + (qd & 1);
 #pragma unroll
         for (int s2 = 0; s2 < 8; ++s2) {
           const int sc = min(s2, S - 1);
-          part[bi][s2] = pb[(size_t)sc * (kTileFloats / 4)];
+          part[bi][s2] = pb[(size_t)sc * (kTileVec4 * 2)];
+          pinv[bi][s2] = s2 < S ? a.pscale[pidx + sc] : 0.f;
         }
         if (EPI == EPI_RESID) {
 #pragma unroll
@@ -481,9 +541,10 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
         float v[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s2 = 0; s2 < 8; ++s2) {                              // fixed slice order
-          const float keep = s2 < S ? 1.0f : 0.0f;
-          v[0] += keep * part[bi][s2].x; v[1] += keep * part[bi][s2].y;
-          v[2] += keep * part[bi][s2].z; v[3] += keep * part[bi][s2].w;
+          const unsigned d0 = part[bi][s2].x, d1 = part[bi][s2].y;
+          const float w = pinv[bi][s2];                               // 0 beyond the last slice
+          v[0] += w * q16_lo(d0); v[1] += w * q16_hi(d0);
+          v[2] += w * q16_lo(d1); v[3] += w * q16_hi(d1);
         }
         if (PRO == PRO_GAIN) {
 #pragma unroll

@@ -93,7 +93,7 @@ inline PackedLayout packed_layout(const sv_model_cfg& c) {
 // float32 for both storage types.
 struct WorkspaceLayout {
   size_t counters, sumsq, part, xhat, q, attn, act, head_z, head_logits, total;
-  size_t counter_bytes;
+  size_t counter_bytes, part_bytes;
   // persistent stack kernel (bf16, one m tile): barrier words, per-XCD row sums and partial tiles
   size_t stack_ctl, stack_ctl_bytes, stack_sumsq, stack_part, stack_part_bytes;
   int m_pad, m_tiles;

@@ -64,7 +64,7 @@ struct StackArgs {
   PhasePlan plan[4];                       // qkv, o, gate/up, down
   int M, T, nh, n_xcd;
   float eps, theta;
-  size_t part_xcd_floats;                  // partial-tile floats per XCD region
+  size_t part_xcd_tiles;                   // partial tiles (tile x slice) per XCD region
   int gmax;                                // row length of group_cnt
   int n_words, p_max, cap;
 };
@@ -76,7 +76,8 @@ struct StackBufs {
   float* q;                                // [M, nh*128]
   float* attn;                             // [M, nh*128]
   float* act;                              // [M, F]
-  float* part;                             // [n_xcd][part_xcd_floats] partial tiles
+  uint4* part16;                           // [n_xcd][part_xcd_tiles] partial tiles (kTileVec4 uint4 each)
+  float* pscale;                           // [n_xcd][part_xcd_tiles] their inverse scales
   float* sumsq;                            // [n_xcd][32][64] row sums of x^2 per unit
   unsigned long long* group_cnt;           // [n_layers * 4][gmax] arrival words, zero at launch
   unsigned* grid_cnt;                      // [n_xcd] words 64 apart, zero at launch
@@ -449,21 +450,36 @@ __device__ inline void helper_gemm_phase(const StackArgs& a, const StackBufs& d,
     if ((lane & 3) == 0) my_ssq[hw + 4 * r] = v1;
   };
 
-  // partial tile of (local tile tl, slice s) of this group; the region belongs to this XCD
-  float* part_x = d.part + (size_t)xcd * a.part_xcd_floats;
-  auto part_tile = [&](int tl, int s) {
-    return part_x + (((size_t)gm.gl * gm.t_max + tl) * S + s) * kTileFloats;
-  };
+  // partial tile of (local tile tl, slice s) of this group, stored as in gemm_stream_bf16
+  // (scaled int16 pairs + one inverse scale); the regions belong to this XCD
+  uint4* part_x = d.part16 + (size_t)xcd * a.part_xcd_tiles * kTileVec4;
+  float* pscale_x = d.pscale + (size_t)xcd * a.part_xcd_tiles;
+  auto part_index = [&](int tl, int s) { return ((size_t)gm.gl * gm.t_max + tl) * S + s; };
   // takes stream wave hw's finished tile out of LDS and writes it as this slice's partial tile
   auto flush_tile = [&](int r) {
     const int tl = hw + 4 * r;
-    float4 t[8];
+    float4 t[8];                                       // t[qd] = registers 4qd .. 4qd+3 of the tile
 #pragma unroll
     for (int qd = 0; qd < 8; ++qd) t[qd] = tb[hw * (kTileFloats / 4) + qd * 64 + lane];
-    if (tl < gm.t_count) {
-      float4* dst = reinterpret_cast<float4*>(part_tile(tl, gm.sp)) + lane;
+    unsigned tmax = 0u;
 #pragma unroll
-      for (int qd = 0; qd < 8; ++qd) dst[qd * 64] = t[qd];
+    for (int qd = 0; qd < 8; ++qd) {
+      const unsigned ma = mag_bits(t[qd].x), mb = mag_bits(t[qd].y), mc = mag_bits(t[qd].z), md = mag_bits(t[qd].w);
+      const unsigned m1 = ma > mb ? ma : mb, m2 = mc > md ? mc : md, m3 = m1 > m2 ? m1 : m2;
+      tmax = tmax > m3 ? tmax : m3;
+    }
+    float psc, pinv;
+    partial_tile_scale(wave_max_u32(tmax), psc, pinv);
+    if (tl < gm.t_count) {
+      const size_t idx = part_index(tl, gm.sp);
+      uint4* dst = part_x + idx * kTileVec4 + lane;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float4 lo = t[2 * q], hi = t[2 * q + 1];
+        dst[q * 64] = make_uint4(pack_q16x2(lo.x, lo.y, psc), pack_q16x2(lo.z, lo.w, psc),
+                                 pack_q16x2(hi.x, hi.y, psc), pack_q16x2(hi.z, hi.w, psc));
+      }
+      if (lane == 0) pscale_x[idx] = pinv;
     }
   };
 
@@ -540,7 +556,8 @@ __device__ inline void helper_gemm_phase(const StackArgs& a, const StackBufs& d,
   const int n_items = gm.t_count * 8;
   constexpr int kBatch = 4;
   for (int it0 = gm.sp + S * hw; it0 < n_items; it0 += 4 * S * kBatch) {
-    float4 part[kBatch][8];
+    uint2 part[kBatch][8];
+    float pinv[kBatch][8];
     float xres[kBatch][4];
 #pragma unroll
     for (int bi = 0; bi < kBatch; ++bi) {
@@ -548,9 +565,14 @@ __device__ inline void helper_gemm_phase(const StackArgs& a, const StackBufs& d,
       if (it >= n_items) break;
       const int tl = it >> 3, qd = it & 7;
       const int row0 = 8 * (qd & 3) + rbase + 32 * (qd >> 2);
-      const float4* pb = reinterpret_cast<const float4*>(part_tile(tl, 0)) + qd * 64 + lane;
+      const size_t idx = part_index(tl, 0);
+      const uint2* pb = reinterpret_cast<const uint2*>(part_x + idx * kTileVec4 + (qd >> 1) * 64 + lane) + (qd & 1);
 #pragma unroll
-      for (int s2 = 0; s2 < 8; ++s2) part[bi][s2] = pb[(size_t)min(s2, S - 1) * (kTileFloats / 4)];
+      for (int s2 = 0; s2 < 8; ++s2) {
+        const int sl = min(s2, S - 1);
+        part[bi][s2] = pb[(size_t)sl * (kTileVec4 * 2)];
+        pinv[bi][s2] = s2 < S ? pscale_x[idx + sl] : 0.f;
+      }
       if (EPI == EPI_RESID) {
         const int tile = gm.t_begin + tl;
 #pragma unroll
@@ -567,9 +589,10 @@ __device__ inline void helper_gemm_phase(const StackArgs& a, const StackBufs& d,
       float v[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int s2 = 0; s2 < 8; ++s2) {                               // fixed slice order
-        const float keep = s2 < S ? 1.0f : 0.0f;
-        v[0] += keep * part[bi][s2].x; v[1] += keep * part[bi][s2].y;
-        v[2] += keep * part[bi][s2].z; v[3] += keep * part[bi][s2].w;
+        const unsigned d0 = part[bi][s2].x, d1 = part[bi][s2].y;
+        const float w = pinv[bi][s2];                                // 0 beyond the last slice
+        v[0] += w * q16_lo(d0); v[1] += w * q16_hi(d0);
+        v[2] += w * q16_lo(d1); v[3] += w * q16_hi(d1);
       }
       if (PRO == PRO_GAIN) {
 #pragma unroll
