@@ -176,6 +176,9 @@ int sv_tree_build_device(const int32_t *cand_parent, const float *cand_logp,
  *   kv, tree:  [host] structs of [device] pointers, see above; tree->n_nodes = T
  *   workspace: [device], 256-byte aligned, ws_bytes >= sv_workspace_bytes(cfg, B, T, *),
  *              prepared once with sv_workspace_init; calls sharing a workspace must not overlap
+ * bf16 models: the projections are split along K and their partial sums travel in 16 bits with
+ * one scale per 64-row x 32-column tile (error <= 2^-14 of the tile's largest partial sum); an
+ * infinity or NaN anywhere in such a tile makes the whole tile (all its rows) NaN.
  * SV_ERR_SHAPE if B < 1, T outside 1..SV_MAX_TREE_NODES, capacity < prefix_len_max + T, or
  * cfg sizes are unsupported for the dtype (see sv_pack_layer). */
 int sv_verify_layer(const sv_model_cfg *cfg, const void *packed, float *x,

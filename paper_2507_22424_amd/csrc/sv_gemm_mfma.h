@@ -9,17 +9,18 @@
 //     weight rows x 16 k-values, lane l holding the 8 consecutive k-values (l / 32) * 8 .. + 7
 //     of row l % 32 - and the fragments of one 32-row tile are stored one after the other
 //     along K.  A wavefront reads a tile as one contiguous stream, 1 KiB per load
-//     instruction, straight into operand registers, 16 KiB ahead of the math.
+//     instruction, straight into operand registers, through a ring of four 8 KiB pieces whose
+//     loads are issued unconditionally so that the wait before every MFMA is exact.
 //   * activations stay float32 in memory; when a workgroup stages its K slice of X into LDS
 //     (once, in fragment order) each value is split into hi + lo bf16 parts and both are
 //     multiplied, so the product is accurate to ~2^-17 instead of 2^-9 at no cost in HBM
-//     bytes (the matrix cores idle most of the time on this path).  This keeps a 32-layer
-//     pass inside the 2e-2 bar.  With X resident, the main loop has no barrier: each of the
+//     bytes.  This keeps a 32-layer pass inside the 2e-2 bar.  With X resident, the main loop has no barrier: each of the
 //     four waves only streams weights, reads X fragments from LDS and issues MFMAs.
 //   * work unit = (group of 32-row tiles, K slice), one per workgroup, one workgroup per CU.
 //     The hardware deals workgroups to the eight XCDs round robin (workgroup i runs on XCD
 //     i % 8), so unit = f(workgroup id) puts all slices of a tile on one XCD and their partial
-//     tiles meet in that XCD's L2: writer = plain stores, wait for completion, then an atomic
+//     tiles (16-bit fixed point with a per-tile scale: they are HBM traffic, the kernel is bound
+//     by its total traffic) meet in that XCD's L2: writer = plain stores, wait for completion, then an atomic
 //     on the group's arrival counter; once all slices have arrived (a short, bounded wait) every
 //     wave invalidates its L1 and takes an equal share of the group's output: it adds the
 //     partials in slice order (bit-reproducible) and runs the epilogue.  This is the
