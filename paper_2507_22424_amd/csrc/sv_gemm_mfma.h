@@ -182,7 +182,6 @@ template <int PRO, int EPI>
 __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
   // X chunk: [32 k-steps][2 m-halves][hi, lo][64 slots] x 16 bytes = 128 KiB
   __shared__ uint4 xs[32 * 2 * 2 * 64];
-  __shared__ float s_rstd[kMTile];          // PRO_GAIN: 1 / rms of each row, known after the barrier
   __shared__ int s_pos[kMTile];             // EPI_QKV: rotary position of each row of the m tile
   __shared__ int s_crow[kMTile];            // EPI_QKV: cache row (b * nh * cap + P + t) of each row
   const int tid = threadIdx.x, lane = tid & 63;
@@ -490,24 +489,23 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
     }
     __syncthreads();
     asm volatile("buffer_inv sc0" ::: "memory");                      // drop stale L1 lines (the L2 is shared)
-    if (PRO == PRO_GAIN) {                   // row sums of all slices -> 1 / rms, once per workgroup
-      if (tid < kMTile) {
-        float part8[8], t = 0.f;
+    // Row sums of all slices -> 1 / rms: every wave keeps the value of row `lane` and fetches
+    // the rows it needs with a lane read.  The loads are only issued here; they are consumed
+    // behind the first batch of partial-tile loads, so the two round trips overlap.
+    float ss8[8];
+    if (PRO == PRO_GAIN) {
 #pragma unroll
-        for (int s2 = 0; s2 < 8; ++s2)
-          part8[s2] = a.sumsq[(((size_t)mt * G + g) * S + min(s2, S - 1)) * kMTile + tid];
-#pragma unroll
-        for (int s2 = 0; s2 < 8; ++s2) t += s2 < S ? part8[s2] : 0.f;
-        s_rstd[tid] = 1.0f / sqrtf(t / (float)K + a.eps);
-      }
+      for (int s2 = 0; s2 < 8; ++s2)
+        ss8[s2] = a.sumsq[(((size_t)mt * G + g) * S + min(s2, S - 1)) * kMTile + lane];
     }
+    float rstd_lane = 1.0f;
+    bool have_rstd = false;
 
     // Work item = one quad of one tile: the 8 rows x 32 columns that register quad `qd` of the
     // partial-tile layout holds (rows 8*(qd%4) + 4*(lane/32) + 0..3, +32 for qd >= 4).  Items of
     // the group are dealt round robin to (slice, wave): item i -> slice i % S, wave (i / S) % 4.
     const int ln = lane & 31;
     const int n_items = t_count * 8;
-    if (PRO == PRO_GAIN) __syncthreads();    // s_rstd is complete
     for (int it0 = sp + S * wave; it0 < n_items; it0 += 4 * S * kRedBatch) {
       uint2 part[kRedBatch][8];
       float pinv[kRedBatch][8];
@@ -533,6 +531,13 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
             xres[bi][j] = a.x_io[(size_t)min(m0 + row0 + j, a.M - 1) * a.N + tile * 32 + ln];
         }
       }
+      if (PRO == PRO_GAIN && !have_rstd) {
+        float t = 0.f;
+#pragma unroll
+        for (int s2 = 0; s2 < 8; ++s2) t += s2 < S ? ss8[s2] : 0.f;
+        rstd_lane = 1.0f / sqrtf(t / (float)K + a.eps);
+        have_rstd = true;
+      }
 #pragma unroll
       for (int bi = 0; bi < kRedBatch; ++bi) {
         const int it = it0 + 4 * S * bi;
@@ -549,7 +554,7 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
         }
         if (PRO == PRO_GAIN) {
 #pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] *= s_rstd[row0 + j];
+          for (int j = 0; j < 4; ++j) v[j] *= __shfl(rstd_lane, row0 + j, kWave);
         }
         if (EPI == EPI_RESID) {
 #pragma unroll
