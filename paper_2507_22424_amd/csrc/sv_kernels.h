@@ -282,7 +282,14 @@ __global__ __launch_bounds__(64) void argmax_rows(const float* __restrict__ part
   int bi = 0x7fffffff;
   for (int i = threadIdx.x; i < n; i += 64) {
     float v = 0.f;
-    for (int p = 0; p < planes; ++p) v += parts[(size_t)p * plane + row * n + i];
+    for (int p0 = 0; p0 < planes; p0 += 16) {          // 16 plane loads in flight, added in order
+      float pv[16];
+#pragma unroll
+      for (int p = 0; p < 16; ++p)
+        pv[p] = p0 + p < planes ? parts[(size_t)(p0 + p) * plane + row * n + i] : 0.f;
+#pragma unroll
+      for (int p = 0; p < 16; ++p) v += p0 + p < planes ? pv[p] : 0.f;
+    }
     if (logits_out) logits_out[row * n + i] = v;
     if (v > best || (v == best && i < bi)) {
       best = v;
