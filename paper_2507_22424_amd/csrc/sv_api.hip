@@ -49,7 +49,7 @@ static GemmPlan plan_gemm(int n_rows, int k, int n_xcd) {
   if (p.gpx > tiles_per_xcd) p.gpx = tiles_per_xcd;
   if (p.gpx < 1) p.gpx = 1;
   // a slice that spans several LDS chunks keeps its accumulators in registers: one tile per wave
-  const int chunks = ceil_div(ceil_div(npair, p.S), 2);
+  const int chunks = ceil_div(ceil_div(2 * npair, p.S), 4);     // LDS chunks of the longest slice
   if (chunks > 1 && ceil_div(tiles_per_xcd, p.gpx) > 4) p.gpx = ceil_div(tiles_per_xcd, 4);
   return p;
 }

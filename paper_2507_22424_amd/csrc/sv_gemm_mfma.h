@@ -190,7 +190,7 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
   const int K = a.K, S = a.S;
   const int n_tiles = a.N / kFragRows;
   const int G = a.n_xcd * a.gpx;
-  const int npair = K / (2 * kBlkK);         // 256-k blocks along K
+  const int npieces = K / kBlkK;             // 128-k pieces along K
   const int xcd = blockIdx.x % a.n_xcd;      // where the dispatcher puts this workgroup
   const int u = blockIdx.x / a.n_xcd;        // unit inside that XCD's share
   if (u >= a.gpx * S) return;
@@ -210,9 +210,9 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
     const int tq = n_tiles / G, trem = n_tiles % G;
     const int t_begin = g * tq + min(g, trem);
     const int t_count = tq + (g < trem ? 1 : 0);
-    const int pq = npair / S, prem = npair % S;
-    const int p_begin = 2 * (sp * pq + min(sp, prem));   // first piece (128 k-values) of the slice
-    const int np = 2 * (pq + (sp < prem ? 1 : 0));       // pieces in the slice
+    const int pq = npieces / S, prem = npieces % S;
+    const int p_begin = sp * pq + min(sp, prem);         // first piece (128 k-values) of the slice
+    const int np = pq + (sp < prem ? 1 : 0);             // pieces in the slice
     const int n_chunks = (np + 3) >> 2;                  // LDS chunks of 4 pieces
     const int my_tiles = t_count > wave ? (t_count - wave + 3) / 4 : 0;   // tiles wave, wave+4, ..
     const int rounds = (t_count + 3) / 4;                // the same for the four waves

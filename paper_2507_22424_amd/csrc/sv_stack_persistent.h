@@ -101,7 +101,7 @@ struct PhaseGeom {
 
 __host__ __device__ inline PhaseGeom phase_geom(const PhasePlan& p, int n_xcd, int xcd, int u) {
   PhaseGeom r;
-  const int n_tiles = p.N / kFragRows, G = n_xcd * p.gpx, npair = p.K / (2 * kBlkK);
+  const int n_tiles = p.N / kFragRows, G = n_xcd * p.gpx, npieces = p.K / kBlkK;
   r.gl = u / p.S;
   r.sp = u % p.S;
   r.g = xcd * p.gpx + r.gl;
@@ -109,9 +109,9 @@ __host__ __device__ inline PhaseGeom phase_geom(const PhasePlan& p, int n_xcd, i
   r.t_max = tq + (trem ? 1 : 0);
   r.t_begin = r.g * tq + (r.g < trem ? r.g : trem);
   r.t_count = tq + (r.g < trem ? 1 : 0);
-  const int pq = npair / p.S, prem = npair % p.S;
-  r.p_begin = 2 * (r.sp * pq + (r.sp < prem ? r.sp : prem));
-  r.np = 2 * (pq + (r.sp < prem ? 1 : 0));
+  const int pq = npieces / p.S, prem = npieces % p.S;
+  r.p_begin = r.sp * pq + (r.sp < prem ? r.sp : prem);
+  r.np = pq + (r.sp < prem ? 1 : 0);
   r.active = u < p.gpx * p.S && r.t_count > 0 && r.np > 0;
   if (!r.active) {
     r.t_count = 0;
