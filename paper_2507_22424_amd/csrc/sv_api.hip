@@ -36,6 +36,7 @@ static int check_cfg(const sv_model_cfg* c) {
 // one tile per wave (4 per group) because the accumulators then stay in registers.
 struct GemmPlan {
   int S, gpx;
+  bool multi;                                // a K slice spans more than one LDS chunk
 };
 
 static GemmPlan plan_gemm(int n_rows, int k, int n_xcd) {
@@ -45,12 +46,14 @@ static GemmPlan plan_gemm(int n_rows, int k, int n_xcd) {
   p.S = npair / 2;                           // about one LDS chunk (2 pieces) per slice
   if (p.S > 8) p.S = 8;
   if (p.S < 1) p.S = 1;
+  if (p.S > 1) p.S &= ~1;                    // the reduction deals quads to waves for S = 1 or even
   p.gpx = 32 / p.S;                          // aim at 32 units per XCD (one per CU)
   if (p.gpx > tiles_per_xcd) p.gpx = tiles_per_xcd;
   if (p.gpx < 1) p.gpx = 1;
   // a slice that spans several LDS chunks keeps its accumulators in registers: one tile per wave
   const int chunks = ceil_div(ceil_div(2 * npair, p.S), 4);     // LDS chunks of the longest slice
   if (chunks > 1 && ceil_div(tiles_per_xcd, p.gpx) > 4) p.gpx = ceil_div(tiles_per_xcd, 4);
+  p.multi = chunks > 1;
   return p;
 }
 
@@ -209,12 +212,24 @@ static int verify_layer_bf16(const sv_model_cfg& c, const char* packed, float* x
   float* q = (float*)(ws + wl.q);
   float* attn = (float*)(ws + wl.attn);
   float* act = (float*)(ws + wl.act);
-  dim3 grid(1, wl.m_tiles, 1);
+  dim3 grid(n_xcd, 1, wl.m_tiles);           // workgroup (x, y) -> XCD x, unit y
+  bool multi = false;
   auto shape = [&](int N, int K) {
     const GemmPlan p = plan_gemm(N, K, n_xcd);
     a.N = N; a.K = K; a.S = p.S; a.gpx = p.gpx;
-    grid.x = n_xcd * p.gpx * p.S;            // workgroup i -> XCD i % n_xcd, unit i / n_xcd
+    const int n_tiles = N / kFragRows, G = n_xcd * p.gpx, npieces = K / kBlkK;
+    a.tq = n_tiles / G; a.trem = n_tiles % G;
+    a.pq = npieces / p.S; a.prem = npieces % p.S;
+    a.inv_S = (65536u + p.S - 1) / p.S;      // exact for the unit numbers that occur (< 4096)
+    grid.y = p.gpx * p.S;
+    multi = p.multi;
   };
+  // the kernel form for the shape just planned: single- or multi-chunk K slices
+#define SV_LAUNCH_GEMM(PRO, EPI)                                        \
+  do {                                                                  \
+    if (multi) gemm_stream_bf16<PRO, EPI, true><<<grid, 256, 0, st>>>(a); \
+    else gemm_stream_bf16<PRO, EPI, false><<<grid, 256, 0, st>>>(a);      \
+  } while (0)
 
   a.X = x; a.gain = (const float*)(packed + pl.g1); a.Wp = (const uint4*)(packed + pl.wqkv);
   shape(3 * D, H);
@@ -222,7 +237,7 @@ static int verify_layer_bf16(const sv_model_cfg& c, const char* packed, float* x
   a.prefix_len = kv.prefix_len; a.p_max = kv.prefix_len_max; a.cap = kv.capacity; a.T = T_;
   a.nh = c.n_heads; a.theta = c.rope_theta;
   mark(0);
-  gemm_stream_bf16<PRO_GAIN, EPI_QKV><<<grid, 256, 0, st>>>(a);
+  SV_LAUNCH_GEMM(PRO_GAIN, EPI_QKV);
   mark(1);
   mark(2);
   tree_attention_mfma<4><<<dim3(B * ceil_div(T_, kAttQ), c.n_heads), 256, 0, st>>>(
@@ -232,20 +247,21 @@ static int verify_layer_bf16(const sv_model_cfg& c, const char* packed, float* x
   a.X = attn; a.gain = nullptr; a.Wp = (const uint4*)(packed + pl.wo);
   shape(H, D);
   a.x_io = x;
-  gemm_stream_bf16<PRO_PLAIN, EPI_RESID><<<grid, 256, 0, st>>>(a);
+  SV_LAUNCH_GEMM(PRO_PLAIN, EPI_RESID);
   mark(4);
   a.X = x; a.gain = (const float*)(packed + pl.g2); a.Wp = (const uint4*)(packed + pl.wgu);
   shape(2 * F, H);
   a.act = act;
   mark(5);
-  gemm_stream_bf16<PRO_GAIN, EPI_SWIGLU><<<grid, 256, 0, st>>>(a);
+  SV_LAUNCH_GEMM(PRO_GAIN, EPI_SWIGLU);
   mark(6);
   a.X = act; a.gain = nullptr; a.Wp = (const uint4*)(packed + pl.wd);
   shape(H, F);
   a.x_io = x;
   mark(7);
-  gemm_stream_bf16<PRO_PLAIN, EPI_RESID><<<grid, 256, 0, st>>>(a);
+  SV_LAUNCH_GEMM(PRO_PLAIN, EPI_RESID);
   mark(8);
+#undef SV_LAUNCH_GEMM
   return launch_status();
 }
 

@@ -94,12 +94,17 @@ struct GemmArgs {
   const float* gain;     // [K] RMSNorm gain (PRO_GAIN) or unused
   const uint4* Wp;       // packed weights, N rows
   int M, N, K;
-  int S;                 // K slices
+  int S;                 // K slices: 1 or even, at most 8
   int gpx;               // tile groups per XCD (units per XCD = gpx * S)
+  // quotients the host works out once (the kernels do no integer division on their way to the
+  // first load): tiles per group and remainder, 128-k pieces per slice and remainder,
+  // ceil(2^16 / S) for unit -> (group, slice)
+  int tq, trem, pq, prem;
+  unsigned inv_S;
   int n_xcd;             // XCDs of the device (8 on MI355X; 1 for a single-XCD partition)
   uint4* part16;         // [m_tiles][N/32][S] partial tiles, kTileVec4 uint4 each (scaled int16)
   float* pscale;         // [m_tiles][N/32][S] inverse scale of each partial tile
-  float* sumsq;          // [m_tiles][n_xcd*gpx][S][64] partial row sums of x^2 (PRO_GAIN)
+  float* sumsq;          // [m_tiles][n_xcd*gpx][S][64] row sums of x^2 over each K slice (RMSNorm, row scales of the partial tiles)
   unsigned* group_cnt;   // [m_tiles][groups][2] arrival (4 bits per XCD) / departure counters, zero between launches
   int* status;           // sticky: != 0 once slices of one tile were seen on different XCDs
   float eps;
@@ -132,7 +137,18 @@ __device__ inline float bf16_hi_f32(uint32_t packed) { return __uint_as_float(pa
 // bytes of float32, cannot overflow whatever the activations, and carry an absolute error of at
 // most 2^-14 of the tile maximum (what matters downstream is the error against the size of the
 // row, not of the single element; fp16 with its 11-bit mantissa measured 6 times worse there).
-// A tile that holds an infinity or a NaN is marked by a NaN scale and reads back as NaN.
+//  - Rows of different size.  Where the activations are the raw residual stream (PRO_GAIN: the
+//    normalisation is applied after the reduction), every row is first divided by a power of two
+//    close to the norm of its activations over the slice - half the exponent of the row's sum of
+//    squares, which the staging pass has anyway.  What is left of a row is bounded by the norm
+//    of the weight rows alone, so rows of very different size that share a tile (episodes at
+//    different scales, an outlier token) keep the same relative precision.  The other two
+//    products take normalised quantities (attention output, SwiGLU output) and skip this.
+//  - Infinities and NaNs.  A tile whose maximum is not finite takes a slower path: the scale
+//    comes from its finite elements, every other element is stored as the code -32768 (never
+//    produced otherwise) and the tile's inverse scale is stored negative; the reader turns the
+//    code back into NaN.  So a NaN stays in the elements it reaches by the arithmetic of the
+//    model, as with float32 partial sums (an infinity comes back as NaN).
 // Register r (0..31: the two accumulators of a wave, see the layout at the tile store) goes to
 // half r % 2 of dword r / 2 of the lane; dwords 4q..4q+3 form the lane's uint4 of store q.
 
@@ -146,14 +162,19 @@ __device__ inline unsigned wave_max_u32(unsigned v) {
   }
   return v;
 }
-// scale = 2^(13 - e) for a tile maximum in [2^e, 2^(e+1)), inv = 1 / scale (exponents clamped so
-// that both stay normal numbers); a non-finite maximum gives scale 0 and inv NaN.
+constexpr unsigned kInfBits = 0x7f800000u;
+__device__ inline unsigned finite_mag_bits(float v) {
+  const unsigned m = mag_bits(v);
+  return m < kInfBits ? m : 0u;
+}
+// scale = 2^(13 - e) for a finite tile maximum in [2^e, 2^(e+1)), inv = 1 / scale (exponents
+// clamped so that both stay normal numbers)
 __device__ inline void partial_tile_scale(unsigned max_bits, float& scale, float& inv) {
   const unsigned eb = max_bits >> 23;
   unsigned se = 267u - eb;                 // >= 13 for every finite maximum
   se = se > 240u ? 240u : se;
-  scale = eb == 255u ? 0.f : __uint_as_float(se << 23);
-  inv = eb == 255u ? __uint_as_float(0x7fc00000u) : __uint_as_float((254u - se) << 23);
+  scale = __uint_as_float(se << 23);
+  inv = __uint_as_float((254u - se) << 23);
 }
 // two values -> int16 pair, round to nearest even: adding 1.5 * 2^23 leaves the rounded integer
 // in the low mantissa bits (|a * scale| < 2^14 here)
@@ -161,6 +182,23 @@ __device__ inline unsigned pack_q16x2(float a, float b, float scale) {
   const unsigned ua = __float_as_uint(fmaf(a, scale, 12582912.0f));
   const unsigned ub = __float_as_uint(fmaf(b, scale, 12582912.0f));
   return (ua & 0xffffu) | (ub << 16);
+}
+// h = floor(exponent(ssq) / 2), -64 .. 64: the row is stored times 2^-h and read back times 2^h
+__device__ inline int row_half_exp(float ssq) { return ((int)((__float_as_uint(ssq) >> 23) & 255u) - 127) >> 1; }
+__device__ inline float row_scale(float ssq) { return __uint_as_float((unsigned)(127 - row_half_exp(ssq)) << 23); }
+// the reader keeps h + 64 of four slices in the bytes of one word
+__device__ inline unsigned row_exp_bytes(float s0, float s1, float s2, float s3) {
+  return (unsigned)(row_half_exp(s0) + 64) | (unsigned)(row_half_exp(s1) + 64) << 8 |
+         (unsigned)(row_half_exp(s2) + 64) << 16 | (unsigned)(row_half_exp(s3) + 64) << 24;
+}
+__device__ inline float row_scale_inv(unsigned bytes, int i) {
+  return __uint_as_float((63u + ((bytes >> (8 * i)) & 255u)) << 23);
+}
+// the same for a tile with non-finite elements: those become the code 0x8000
+__device__ inline unsigned pack_q16x2_coded(float a, float b, float scale) {
+  const unsigned ua = mag_bits(a) < kInfBits ? __float_as_uint(fmaf(a, scale, 12582912.0f)) & 0xffffu : 0x8000u;
+  const unsigned ub = mag_bits(b) < kInfBits ? __float_as_uint(fmaf(b, scale, 12582912.0f)) & 0xffffu : 0x8000u;
+  return ua | (ub << 16);
 }
 __device__ inline float q16_lo(unsigned d) { return (float)((int)(d << 16) >> 16); }
 __device__ inline float q16_hi(unsigned d) { return (float)((int)d >> 16); }
@@ -175,25 +213,248 @@ __device__ inline int xcd_actual(int n_xcd) {
 // readers apply the same permutation, which keeps their 16-lane groups conflict free.
 __device__ inline int frag_slot(int l, int s) { return ((l & 31) ^ (((s & 7) << 1) | (l >> 5))) | (l & 32); }
 
-// grid = (workgroups, m_tiles), block = 256, 1 workgroup per CU (LDS).  K must be a multiple
+// Second half of gemm_stream_bf16: group barrier, then every wave of every slice reduces its
+// share of the group's tiles and applies the epilogue.  `a` is the kernel-argument segment read
+// through a pointer the compiler cannot trace back to the kernel's own copy, and every index is
+// derived again from it: nothing of this phase stays live in scalar registers across the main
+// loop, where spilled scalars cost stalls between the matrix instructions.
+typedef const __attribute__((address_space(4))) GemmArgs* gemm_args_ptr_t;
+template <int PRO, int EPI>
+__device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, const int* s_pos, const int* s_crow,
+                                                  int tid, int lane, int wave) {
+  GemmArgs a;                                // one batch of scalar loads; registers from here on
+  {
+    static_assert(sizeof(GemmArgs) % 4 == 0, "copied word by word");
+    const __attribute__((address_space(4))) unsigned* src = (const __attribute__((address_space(4))) unsigned*)ap;
+    unsigned* dst = reinterpret_cast<unsigned*>(&a);
+#pragma unroll
+    for (unsigned i = 0; i < sizeof(GemmArgs) / 4; ++i) dst[i] = src[i];
+  }
+  const int mt = blockIdx.z, m0 = mt * kMTile;
+  const int K = a.K, S = a.S;
+  const int n_tiles = a.N / kFragRows;
+  const int G = a.n_xcd * a.gpx;
+  const int xcd = blockIdx.x, u = blockIdx.y;
+  const int ug = (int)(((unsigned)u * a.inv_S) >> 16);   // u / S
+  const int g = xcd * a.gpx + ug, sp = u - ug * S;
+  const int tq = a.tq, trem = a.trem;
+  const int t_begin = g * tq + min(g, trem);
+  const int t_count = tq + (g < trem ? 1 : 0);
+  const int rbase = 4 * (lane >> 5);
+
+  // ---- group barrier, then every wave of every slice reduces its share ----
+  // Arrival = add 1 to the 4-bit field of the XCD this workgroup really runs on; all S
+  // arrivals in one field means the slices shared an L2, as planned.  The workgroups of a
+  // group are dispatched within 64 consecutive workgroup ids, so they are resident together
+  // and the wait below is short; it is bounded all the same (status bit 2 on give-up).
+  __builtin_amdgcn_s_waitcnt(0);           // this wave's partial tiles are in L2
+  __syncthreads();
+  unsigned* gcnt = a.group_cnt + ((size_t)mt * G + g) * 2;
+  if (tid == 0) {
+    const unsigned field = 4u * (unsigned)xcd_actual(a.n_xcd);
+    __hip_atomic_fetch_add(gcnt, 1u << field, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned v = 0, n = 0;
+    for (int spin = 0; spin < (1 << 16); ++spin) {
+      v = __hip_atomic_load(gcnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // not from L1
+      n = 0;
+#pragma unroll
+      for (int x = 0; x < kXcds; ++x) n += (v >> (4 * x)) & 15u;
+      if (n >= (unsigned)S) break;
+    }
+    int bad = 0;
+    if (n < (unsigned)S) bad |= 2;                                  // gave up waiting
+    else if (v != ((unsigned)S << field)) bad |= 1;                 // slices on several XCDs
+    if (bad) atomicOr(a.status, bad);
+  }
+  __syncthreads();
+  asm volatile("buffer_inv sc0" ::: "memory");                      // drop stale L1 lines (the L2 is shared)
+  // Row sums of all slices -> 1 / rms: every wave keeps the value of row `lane` and fetches
+  // the rows it needs with a lane read.  The loads are only issued here; they are consumed
+  // behind the first batch of partial-tile loads, so the two round trips overlap.
+  float ss8[8];
+  if (PRO == PRO_GAIN) {
+#pragma unroll
+    for (int s2 = 0; s2 < 8; ++s2)
+      ss8[s2] = a.sumsq[(((size_t)mt * G + g) * S + min(s2, S - 1)) * kMTile + lane];
+  }
+  float rstd_lane = 1.0f;
+  unsigned rexp_lo = 0, rexp_hi = 0;       // row `lane`: h + 64 of slices 0..3 / 4..7
+  bool have_rstd = false;
+
+  // Work item = one quad of one tile: the 8 rows x 32 columns that register quad `qd` of the
+  // partial-tile layout holds (rows 8*(qd%4) + 4*(lane/32) + 0..3, +32 for qd >= 4).  The 4 * S
+  // waves of the group's slices share the items so that a wave keeps its quad (S is 1 or
+  // even): wave number wk = slice + S * wave takes quad wk % 8 of the tiles wk / 8,
+  // wk / 8 + S / 2, ..; with S = 1 there are four waves, each takes two quads in turn.  What
+  // depends on the rows only - 1 / rms and the row scales of the eight slices - is then
+  // fetched once per quad: rinv[s][j] = 2^h of slice s and row row0 + j.
+  const int ln = lane & 31;
+  const int wk = sp + S * wave;
+  const int t_step = S > 1 ? S >> 1 : 1;
+  for (int qd = wk & 7; qd < 8; qd += 4 * S) {
+    const int row0 = 8 * (qd & 3) + rbase + 32 * (qd >> 2);
+    float rinv[8][4], rstd4[4];
+    bool have_rows = false;
+    for (int tl0 = wk >> 3; tl0 < t_count; tl0 += t_step * kRedBatch) {
+    uint2 part[kRedBatch][8];
+    float pinv[kRedBatch][8];
+    float xres[kRedBatch][4];
+#pragma unroll
+    for (int bi = 0; bi < kRedBatch; ++bi) {                        // all loads of the batch first
+      const int tl = tl0 + t_step * bi;
+      if (tl >= t_count) break;
+      const int tile = t_begin + tl;
+      // registers 4qd .. 4qd+3 of the tile = dwords 2qd, 2qd+1 = half of the uint4 of store qd/2
+      const size_t pidx = ((size_t)mt * n_tiles + tile) * S;
+      const uint2* pb = reinterpret_cast<const uint2*>(a.part16 + pidx * kTileVec4 + (qd >> 1) * 64 + lane) + (qd & 1);
+#pragma unroll
+      for (int s2 = 0; s2 < 8; ++s2) {
+        const int sc = min(s2, S - 1);
+        part[bi][s2] = pb[(size_t)sc * (kTileVec4 * 2)];
+        pinv[bi][s2] = s2 < S ? a.pscale[pidx + sc] : 0.f;
+      }
+      if (EPI == EPI_RESID) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          xres[bi][j] = a.x_io[(size_t)min(m0 + row0 + j, a.M - 1) * a.N + tile * 32 + ln];
+      }
+    }
+    // The phase is bound by the round trips of these loads, not by arithmetic: keep the whole
+    // batch in flight together (left alone, the compiler sinks loads towards their uses).
+    asm volatile("" ::: "memory");
+    if (PRO == PRO_GAIN && !have_rstd) {
+      float t = 0.f;
+#pragma unroll
+      for (int s2 = 0; s2 < 8; ++s2) t += s2 < S ? ss8[s2] : 0.f;
+      rstd_lane = 1.0f / sqrtf(t / (float)K + a.eps);
+      rexp_lo = row_exp_bytes(ss8[0], ss8[1], ss8[2], ss8[3]);
+      rexp_hi = row_exp_bytes(ss8[4], ss8[5], ss8[6], ss8[7]);
+      have_rstd = true;
+    }
+    if (PRO == PRO_GAIN && !have_rows) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const unsigned elo = (unsigned)__shfl((int)rexp_lo, row0 + j, kWave);
+        const unsigned ehi = (unsigned)__shfl((int)rexp_hi, row0 + j, kWave);
+#pragma unroll
+        for (int s2 = 0; s2 < 8; ++s2) rinv[s2][j] = row_scale_inv(s2 < 4 ? elo : ehi, s2 & 3);
+        rstd4[j] = __shfl(rstd_lane, row0 + j, kWave);
+      }
+      have_rows = true;
+    }
+#pragma unroll
+    for (int bi = 0; bi < kRedBatch; ++bi) {
+      const int tl = tl0 + t_step * bi;
+      if (tl >= t_count) break;
+      const int tile = t_begin + tl;
+      float v[4] = {0.f, 0.f, 0.f, 0.f};
+      int any_flag = 0;                                             // sign bits of the inverse scales
+#pragma unroll
+      for (int s2 = 0; s2 < 8; ++s2) {                              // fixed slice order
+        const unsigned d0 = part[bi][s2].x, d1 = part[bi][s2].y;
+        const float w = fabsf(pinv[bi][s2]);                        // 0 beyond the last slice
+        any_flag |= __float_as_int(pinv[bi][s2]);
+        const float q[4] = {q16_lo(d0), q16_hi(d0), q16_lo(d1), q16_hi(d1)};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          // tile scale first, row scale second: neither product can overflow on its own
+          if (PRO == PRO_GAIN)
+            v[j] = fmaf(w * q[j], rinv[s2][j], v[j]);
+          else
+            v[j] += w * q[j];
+        }
+      }
+      if (any_flag < 0) {                  // rare: a tile with non-finite elements among the eight
+        const float nan = __uint_as_float(0x7fc00000u);
+#pragma unroll
+        for (int s2 = 0; s2 < 8; ++s2) {
+          if (__float_as_int(pinv[bi][s2]) >= 0) continue;
+          const unsigned d0 = part[bi][s2].x, d1 = part[bi][s2].y;
+          if ((d0 & 0xffffu) == 0x8000u) v[0] = nan;
+          if ((d0 >> 16) == 0x8000u) v[1] = nan;
+          if ((d1 & 0xffffu) == 0x8000u) v[2] = nan;
+          if ((d1 >> 16) == 0x8000u) v[3] = nan;
+        }
+      }
+      if (PRO == PRO_GAIN) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] *= rstd4[j];
+      }
+      if (EPI == EPI_RESID) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (m0 + row0 + j < a.M)
+            a.x_io[(size_t)(m0 + row0 + j) * a.N + tile * 32 + ln] = xres[bi][j] + v[j];
+      }
+      if (EPI == EPI_SWIGLU) {             // lanes 0..15 gate, 16..31 up of the same column
+        const int F = a.N / 2;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float up = __shfl_xor(v[j], 16, kWave);
+          if (ln < 16 && m0 + row0 + j < a.M)
+            a.act[(size_t)(m0 + row0 + j) * F + tile * 16 + ln] = v[j] / (1.0f + expf(-v[j])) * up;
+        }
+      }
+      if (EPI == EPI_QKV) {
+        const int tiles_per_mat = a.nh * 4;  // 128 rows per head = 4 tiles
+        const int which = tile / tiles_per_mat;                  // 0 q, 1 k, 2 v
+        const int head = (tile % tiles_per_mat) / 4, uq = tile % 4;
+        const int jr = 16 * uq + (ln & 15);                      // rotary pair index, 0..63
+        const int dcol = jr + 64 * (ln >> 4);                    // column inside the head
+        // angle in turns = position * theta^(-2j/128) / (2 pi)
+        const float turn_freq = exp2f(-(float)jr * (1.0f / 64.0f) * log2f(a.theta)) * 0.15915494309189535f;
+        const float sgn = (ln & 16) ? 1.0f : -1.0f;
+        const int D = a.nh * 128;
+        bf16_t* cache = which == 1 ? a.kc : a.vc;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int ml = row0 + j;
+          float val = v[j];
+          const float partner = __shfl_xor(val, 16, kWave);
+          if (which != 2) {
+            float turns = (float)s_pos[ml] * turn_freq;
+            turns -= floorf(turns);        // reduced to [0, 1) before the hardware sin / cos
+            val = val * __builtin_amdgcn_cosf(turns) + sgn * partner * __builtin_amdgcn_sinf(turns);
+          }
+          if (m0 + ml < a.M) {
+            if (which == 0)
+              a.q_out[(size_t)(m0 + ml) * D + head * 128 + dcol] = val;
+            else
+              cache[((size_t)s_crow[ml] + (size_t)head * a.cap) * 128 + dcol] = f32_to_bf16(val);
+          }
+        }
+      }
+    }
+    }
+  }
+  // the last workgroup to get here clears the group's two words for the next launch
+  if (tid == 0 &&
+      __hip_atomic_fetch_add(gcnt + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(S - 1)) {
+    gcnt[0] = 0;
+    gcnt[1] = 0;
+  }
+}
+
+// grid = (n_xcd, gpx * S, m_tiles), block = 256, 1 workgroup per CU (LDS).  K must be a multiple
 // of 256: slices are made of pieces of 16 fragments (2 K blocks), a chunk of X in LDS holds up
 // to two pieces.
-template <int PRO, int EPI>
+// MULTI: a K slice may span several LDS chunks (the host knows from its plan); the single-chunk
+// form carries no re-staging code and nothing of it in registers through the main loop.
+template <int PRO, int EPI, bool MULTI>
 __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
   // X chunk: [32 k-steps][2 m-halves][hi, lo][64 slots] x 16 bytes = 128 KiB
   __shared__ uint4 xs[32 * 2 * 2 * 64];
   __shared__ int s_pos[kMTile];             // EPI_QKV: rotary position of each row of the m tile
   __shared__ int s_crow[kMTile];            // EPI_QKV: cache row (b * nh * cap + P + t) of each row
+  __shared__ float s_rowscale[kMTile];      // 2^-h of each row for this slice's partial tiles
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: bookkeeping stays in scalar registers
-  const int mt = blockIdx.y, m0 = mt * kMTile;
+  const int mt = blockIdx.z, m0 = mt * kMTile;
   const int K = a.K, S = a.S;
   const int n_tiles = a.N / kFragRows;
   const int G = a.n_xcd * a.gpx;
-  const int npieces = K / kBlkK;             // 128-k pieces along K
-  const int xcd = blockIdx.x % a.n_xcd;      // where the dispatcher puts this workgroup
-  const int u = blockIdx.x / a.n_xcd;        // unit inside that XCD's share
-  if (u >= a.gpx * S) return;
+  const int xcd = blockIdx.x;                // workgroups are dealt to the XCDs in turn, x fastest
+  const int u = blockIdx.y;                  // unit inside that XCD's share
 
   if (EPI == EPI_QKV && tid < kMTile) {
     const int m = min(m0 + tid, a.M - 1);
@@ -205,12 +466,13 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
   }
 
   {
-    const int g = xcd * a.gpx + u / S;       // tile group (contiguous tiles), K slice
-    const int sp = u % S;
-    const int tq = n_tiles / G, trem = n_tiles % G;
+    const int ug = (int)(((unsigned)u * a.inv_S) >> 16);   // u / S
+    const int g = xcd * a.gpx + ug;          // tile group (contiguous tiles), K slice
+    const int sp = u - ug * S;
+    const int tq = a.tq, trem = a.trem;
     const int t_begin = g * tq + min(g, trem);
     const int t_count = tq + (g < trem ? 1 : 0);
-    const int pq = npieces / S, prem = npieces % S;
+    const int pq = a.pq, prem = a.prem;
     const int p_begin = sp * pq + min(sp, prem);         // first piece (128 k-values) of the slice
     const int np = pq + (sp < prem ? 1 : 0);             // pieces in the slice
     const int n_chunks = (np + 3) >> 2;                  // LDS chunks of 4 pieces
@@ -339,8 +601,10 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
       // bit 0 from bit 2
       const int r = ((lane >> 5) & 1) * 8 + ((lane >> 4) & 1) * 4 + ((lane >> 3) & 1) * 2 + ((lane >> 2) & 1);
       // (inline assembly for the same reason as the partial-tile stores below)
-      if ((lane & 3) == 0)
+      if ((lane & 3) == 0) {
         asm volatile("global_store_dword %0, %1, off" ::"v"(a.sumsq + unit_id * kMTile + wave + 4 * r), "v"(v1) : "memory");
+        s_rowscale[wave + 4 * r] = row_scale(v1);   // (an infinite or NaN sum: any scale will do, the values are not finite either)
+      }
     };
     stage(0, true);
     if (PRO == PRO_GAIN && n_chunks == 1) publish_ssq();
@@ -348,7 +612,7 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
 
     f32x16_t acc0 = {}, acc1 = {};
     const int rbase = 4 * (lane >> 5);
-    const bool multi = n_chunks > 1;
+    const bool multi = MULTI && n_chunks > 1;
     int ct = 0, cj = 0;                                  // piece being consumed: tile count, piece
     // a slice longer than one LDS chunk is walked by all four waves together (re-staging needs
     // them all), also by a wave that has no tile; otherwise every wave just walks its own tiles
@@ -367,7 +631,7 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
       if (steps_left > 0) {
         --steps_left;
         const int jq = cj & 3;
-        if (multi && jq == 0 && cj > 0) {
+        if (MULTI && multi && jq == 0 && cj > 0) {
           // re-stage X for the next chunk: the accumulators carry over; the barriers order LDS
           // traffic only, weight loads stay in flight
           asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -425,23 +689,62 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
             // turn every later wait into a drain of the whole ring.  Unseen stores can only make
             // its waits longer, never too short; their own completion is awaited explicitly
             // before the arrival below.
+            float t0[16], t1[16];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              float4 ra = make_float4(1.f, 1.f, 1.f, 1.f), rb = ra;
+              if (PRO == PRO_GAIN) {                     // rows brought to a common size
+                ra = *reinterpret_cast<const float4*>(&s_rowscale[8 * i + rbase]);
+                rb = *reinterpret_cast<const float4*>(&s_rowscale[32 + 8 * i + rbase]);
+              }
+              t0[4 * i] = acc0[4 * i] * ra.x;         t1[4 * i] = acc1[4 * i] * rb.x;
+              t0[4 * i + 1] = acc0[4 * i + 1] * ra.y; t1[4 * i + 1] = acc1[4 * i + 1] * rb.y;
+              t0[4 * i + 2] = acc0[4 * i + 2] * ra.z; t1[4 * i + 2] = acc1[4 * i + 2] * rb.z;
+              t0[4 * i + 3] = acc0[4 * i + 3] * ra.w; t1[4 * i + 3] = acc1[4 * i + 3] * rb.w;
+            }
             unsigned tmax = 0u;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-              const unsigned m0_ = mag_bits(acc0[r]), m1_ = mag_bits(acc1[r]);
+              const unsigned m0_ = mag_bits(t0[r]), m1_ = mag_bits(t1[r]);
               const unsigned mm = m0_ > m1_ ? m0_ : m1_;
               tmax = tmax > mm ? tmax : mm;
             }
+            unsigned wmax = (unsigned)__builtin_amdgcn_readfirstlane((int)wave_max_u32(tmax));
+            const bool clean = wmax < kInfBits;
+            if (!clean) {                                // rare: the maximum of the finite elements
+              tmax = 0u;
+#pragma unroll
+              for (int r = 0; r < 16; ++r) {
+                const unsigned m0_ = finite_mag_bits(t0[r]), m1_ = finite_mag_bits(t1[r]);
+                const unsigned mm = m0_ > m1_ ? m0_ : m1_;
+                tmax = tmax > mm ? tmax : mm;
+              }
+              wmax = (unsigned)__builtin_amdgcn_readfirstlane((int)wave_max_u32(tmax));
+            }
             float psc, pinv;
-            partial_tile_scale(wave_max_u32(tmax), psc, pinv);
+            partial_tile_scale(wmax, psc, pinv);
+            u32x4_t dq[4];
+            if (clean) {
+#pragma unroll
+              for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  const int r = 8 * (q & 1) + 2 * e;     // register inside acc0 (q < 2) or acc1
+                  dq[q][e] = q < 2 ? pack_q16x2(t0[r], t0[r + 1], psc) : pack_q16x2(t1[r], t1[r + 1], psc);
+                }
+            } else {
+              pinv = -pinv;                              // tells the reader to look for the code
+#pragma unroll
+              for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  const int r = 8 * (q & 1) + 2 * e;
+                  dq[q][e] = q < 2 ? pack_q16x2_coded(t0[r], t0[r + 1], psc) : pack_q16x2_coded(t1[r], t1[r + 1], psc);
+                }
+            }
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-              u32x4_t d;
-#pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                const int r = 8 * (q & 1) + 2 * e;       // register inside acc0 (q < 2) or acc1
-                d[e] = q < 2 ? pack_q16x2(acc0[r], acc0[r + 1], psc) : pack_q16x2(acc1[r], acc1[r + 1], psc);
-              }
+              const u32x4_t d = dq[q];
               // s_nop: a store of more than 64 bits reads its data registers a few cycles after
               // issue; the compiler cannot see that this is a store, so the wait states are explicit
               asm volatile("global_store_dwordx4 %0, %1, off\n\ts_nop 3" ::"v"(pt + q * 64), "v"(d) : "memory");
@@ -463,151 +766,10 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
       for (int sl = 0; sl < kRing; ++sl) step(ring[sl]);
     }
 
-    // ---- group barrier, then every wave of every slice reduces its share ----
-    // Arrival = add 1 to the 4-bit field of the XCD this workgroup really runs on; all S
-    // arrivals in one field means the slices shared an L2, as planned.  The workgroups of a
-    // group are dispatched within 64 consecutive workgroup ids, so they are resident together
-    // and the wait below is short; it is bounded all the same (status bit 2 on give-up).
-    __builtin_amdgcn_s_waitcnt(0);           // this wave's partial tiles are in L2
-    __syncthreads();
-    unsigned* gcnt = a.group_cnt + ((size_t)mt * G + g) * 2;
-    if (tid == 0) {
-      const unsigned field = 4u * (unsigned)xcd_actual(a.n_xcd);
-      __hip_atomic_fetch_add(gcnt, 1u << field, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      unsigned v = 0, n = 0;
-      for (int spin = 0; spin < (1 << 16); ++spin) {
-        v = __hip_atomic_load(gcnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // not from L1
-        n = 0;
-#pragma unroll
-        for (int x = 0; x < kXcds; ++x) n += (v >> (4 * x)) & 15u;
-        if (n >= (unsigned)S) break;
-      }
-      int bad = 0;
-      if (n < (unsigned)S) bad |= 2;                                  // gave up waiting
-      else if (v != ((unsigned)S << field)) bad |= 1;                 // slices on several XCDs
-      if (bad) atomicOr(a.status, bad);
-    }
-    __syncthreads();
-    asm volatile("buffer_inv sc0" ::: "memory");                      // drop stale L1 lines (the L2 is shared)
-    // Row sums of all slices -> 1 / rms: every wave keeps the value of row `lane` and fetches
-    // the rows it needs with a lane read.  The loads are only issued here; they are consumed
-    // behind the first batch of partial-tile loads, so the two round trips overlap.
-    float ss8[8];
-    if (PRO == PRO_GAIN) {
-#pragma unroll
-      for (int s2 = 0; s2 < 8; ++s2)
-        ss8[s2] = a.sumsq[(((size_t)mt * G + g) * S + min(s2, S - 1)) * kMTile + lane];
-    }
-    float rstd_lane = 1.0f;
-    bool have_rstd = false;
-
-    // Work item = one quad of one tile: the 8 rows x 32 columns that register quad `qd` of the
-    // partial-tile layout holds (rows 8*(qd%4) + 4*(lane/32) + 0..3, +32 for qd >= 4).  Items of
-    // the group are dealt round robin to (slice, wave): item i -> slice i % S, wave (i / S) % 4.
-    const int ln = lane & 31;
-    const int n_items = t_count * 8;
-    for (int it0 = sp + S * wave; it0 < n_items; it0 += 4 * S * kRedBatch) {
-      uint2 part[kRedBatch][8];
-      float pinv[kRedBatch][8];
-      float xres[kRedBatch][4];
-#pragma unroll
-      for (int bi = 0; bi < kRedBatch; ++bi) {                        // all loads of the batch first
-        const int it = it0 + 4 * S * bi;
-        if (it >= n_items) break;
-        const int tile = t_begin + (it >> 3), qd = it & 7;
-        const int row0 = 8 * (qd & 3) + rbase + 32 * (qd >> 2);
-        // registers 4qd .. 4qd+3 of the tile = dwords 2qd, 2qd+1 = half of the uint4 of store qd/2
-        const size_t pidx = ((size_t)mt * n_tiles + tile) * S;
-        const uint2* pb = reinterpret_cast<const uint2*>(a.part16 + pidx * kTileVec4 + (qd >> 1) * 64 + lane) + (qd & 1);
-#pragma unroll
-        for (int s2 = 0; s2 < 8; ++s2) {
-          const int sc = min(s2, S - 1);
-          part[bi][s2] = pb[(size_t)sc * (kTileVec4 * 2)];
-          pinv[bi][s2] = s2 < S ? a.pscale[pidx + sc] : 0.f;
-        }
-        if (EPI == EPI_RESID) {
-#pragma unroll
-          for (int j = 0; j < 4; ++j)
-            xres[bi][j] = a.x_io[(size_t)min(m0 + row0 + j, a.M - 1) * a.N + tile * 32 + ln];
-        }
-      }
-      if (PRO == PRO_GAIN && !have_rstd) {
-        float t = 0.f;
-#pragma unroll
-        for (int s2 = 0; s2 < 8; ++s2) t += s2 < S ? ss8[s2] : 0.f;
-        rstd_lane = 1.0f / sqrtf(t / (float)K + a.eps);
-        have_rstd = true;
-      }
-#pragma unroll
-      for (int bi = 0; bi < kRedBatch; ++bi) {
-        const int it = it0 + 4 * S * bi;
-        if (it >= n_items) break;
-        const int tile = t_begin + (it >> 3), qd = it & 7;
-        const int row0 = 8 * (qd & 3) + rbase + 32 * (qd >> 2);
-        float v[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int s2 = 0; s2 < 8; ++s2) {                              // fixed slice order
-          const unsigned d0 = part[bi][s2].x, d1 = part[bi][s2].y;
-          const float w = pinv[bi][s2];                               // 0 beyond the last slice
-          v[0] += w * q16_lo(d0); v[1] += w * q16_hi(d0);
-          v[2] += w * q16_lo(d1); v[3] += w * q16_hi(d1);
-        }
-        if (PRO == PRO_GAIN) {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] *= __shfl(rstd_lane, row0 + j, kWave);
-        }
-        if (EPI == EPI_RESID) {
-#pragma unroll
-          for (int j = 0; j < 4; ++j)
-            if (m0 + row0 + j < a.M)
-              a.x_io[(size_t)(m0 + row0 + j) * a.N + tile * 32 + ln] = xres[bi][j] + v[j];
-        }
-        if (EPI == EPI_SWIGLU) {             // lanes 0..15 gate, 16..31 up of the same column
-          const int F = a.N / 2;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const float up = __shfl_xor(v[j], 16, kWave);
-            if (ln < 16 && m0 + row0 + j < a.M)
-              a.act[(size_t)(m0 + row0 + j) * F + tile * 16 + ln] = v[j] / (1.0f + expf(-v[j])) * up;
-          }
-        }
-        if (EPI == EPI_QKV) {
-          const int tiles_per_mat = a.nh * 4;  // 128 rows per head = 4 tiles
-          const int which = tile / tiles_per_mat;                  // 0 q, 1 k, 2 v
-          const int head = (tile % tiles_per_mat) / 4, uq = tile % 4;
-          const int jr = 16 * uq + (ln & 15);                      // rotary pair index, 0..63
-          const int dcol = jr + 64 * (ln >> 4);                    // column inside the head
-          // angle in turns = position * theta^(-2j/128) / (2 pi)
-          const float turn_freq = exp2f(-(float)jr * (1.0f / 64.0f) * log2f(a.theta)) * 0.15915494309189535f;
-          const float sgn = (ln & 16) ? 1.0f : -1.0f;
-          const int D = a.nh * 128;
-          bf16_t* cache = which == 1 ? a.kc : a.vc;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const int ml = row0 + j;
-            float val = v[j];
-            const float partner = __shfl_xor(val, 16, kWave);
-            if (which != 2) {
-              float turns = (float)s_pos[ml] * turn_freq;
-              turns -= floorf(turns);        // reduced to [0, 1) before the hardware sin / cos
-              val = val * __builtin_amdgcn_cosf(turns) + sgn * partner * __builtin_amdgcn_sinf(turns);
-            }
-            if (m0 + ml < a.M) {
-              if (which == 0)
-                a.q_out[(size_t)(m0 + ml) * D + head * 128 + dcol] = val;
-              else
-                cache[((size_t)s_crow[ml] + (size_t)head * a.cap) * 128 + dcol] = f32_to_bf16(val);
-            }
-          }
-        }
-      }
-    }
-    // the last workgroup to get here clears the group's two words for the next launch
-    if (tid == 0 &&
-        __hip_atomic_fetch_add(gcnt + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(S - 1)) {
-      gcnt[0] = 0;
-      gcnt[1] = 0;
-    }
+    // ---- second half: group barrier, reduction, epilogue (arguments read afresh) ----
+    gemm_args_ptr_t ap = (gemm_args_ptr_t)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(ap));
+    gemm_reduce_phase<PRO, EPI>(ap, s_pos, s_crow, tid, lane, wave);
   }
 }
 

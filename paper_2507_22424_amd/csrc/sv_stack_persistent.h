@@ -448,6 +448,7 @@ __device__ inline void helper_gemm_phase(const StackArgs& a, const StackBufs& d,
     v1 += __shfl_xor(v1, 1, kWave);
     const int r = ((lane >> 5) & 1) * 8 + ((lane >> 4) & 1) * 4 + ((lane >> 3) & 1) * 2 + ((lane >> 2) & 1);
     if ((lane & 3) == 0) my_ssq[hw + 4 * r] = v1;
+    __builtin_amdgcn_s_waitcnt(0);     // in L2 before the barrier behind which flush_tile reads all rows
   };
 
   // partial tile of (local tile tl, slice s) of this group, stored as in gemm_stream_bf16
@@ -461,6 +462,14 @@ __device__ inline void helper_gemm_phase(const StackArgs& a, const StackBufs& d,
     float4 t[8];                                       // t[qd] = registers 4qd .. 4qd+3 of the tile
 #pragma unroll
     for (int qd = 0; qd < 8; ++qd) t[qd] = tb[hw * (kTileFloats / 4) + qd * 64 + lane];
+    if (PRO == PRO_GAIN) {
+#pragma unroll
+      for (int qd = 0; qd < 8; ++qd) {                 // rows brought to a common size, as in gemm_stream_bf16
+        const float4 sq = *reinterpret_cast<const float4*>(my_ssq + 8 * (qd & 3) + 4 * (lane >> 5) + 32 * (qd >> 2));
+        t[qd].x *= row_scale(sq.x); t[qd].y *= row_scale(sq.y);
+        t[qd].z *= row_scale(sq.z); t[qd].w *= row_scale(sq.w);
+      }
+    }
     unsigned tmax = 0u;
 #pragma unroll
     for (int qd = 0; qd < 8; ++qd) {
@@ -468,16 +477,34 @@ __device__ inline void helper_gemm_phase(const StackArgs& a, const StackBufs& d,
       const unsigned m1 = ma > mb ? ma : mb, m2 = mc > md ? mc : md, m3 = m1 > m2 ? m1 : m2;
       tmax = tmax > m3 ? tmax : m3;
     }
+    unsigned wmax = (unsigned)__builtin_amdgcn_readfirstlane((int)wave_max_u32(tmax));
+    const bool clean = wmax < kInfBits;
+    if (!clean) {                                      // rare: the maximum of the finite elements
+      tmax = 0u;
+#pragma unroll
+      for (int qd = 0; qd < 8; ++qd) {
+        const unsigned ma = finite_mag_bits(t[qd].x), mb = finite_mag_bits(t[qd].y);
+        const unsigned mc = finite_mag_bits(t[qd].z), md = finite_mag_bits(t[qd].w);
+        const unsigned m1 = ma > mb ? ma : mb, m2 = mc > md ? mc : md, m3 = m1 > m2 ? m1 : m2;
+        tmax = tmax > m3 ? tmax : m3;
+      }
+      wmax = (unsigned)__builtin_amdgcn_readfirstlane((int)wave_max_u32(tmax));
+    }
     float psc, pinv;
-    partial_tile_scale(wave_max_u32(tmax), psc, pinv);
+    partial_tile_scale(wmax, psc, pinv);
+    if (!clean) pinv = -pinv;
     if (tl < gm.t_count) {
       const size_t idx = part_index(tl, gm.sp);
       uint4* dst = part_x + idx * kTileVec4 + lane;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const float4 lo = t[2 * q], hi = t[2 * q + 1];
-        dst[q * 64] = make_uint4(pack_q16x2(lo.x, lo.y, psc), pack_q16x2(lo.z, lo.w, psc),
-                                 pack_q16x2(hi.x, hi.y, psc), pack_q16x2(hi.z, hi.w, psc));
+        if (clean)
+          dst[q * 64] = make_uint4(pack_q16x2(lo.x, lo.y, psc), pack_q16x2(lo.z, lo.w, psc),
+                                   pack_q16x2(hi.x, hi.y, psc), pack_q16x2(hi.z, hi.w, psc));
+        else
+          dst[q * 64] = make_uint4(pack_q16x2_coded(lo.x, lo.y, psc), pack_q16x2_coded(lo.z, lo.w, psc),
+                                   pack_q16x2_coded(hi.x, hi.y, psc), pack_q16x2_coded(hi.z, hi.w, psc));
       }
       if (lane == 0) pscale_x[idx] = pinv;
     }
@@ -533,11 +560,18 @@ __device__ inline void helper_gemm_phase(const StackArgs& a, const StackBufs& d,
 
   // per-row values kept one per lane (lane = row), fetched with a lane read where needed
   float rstd_lane = 1.0f;
+  unsigned rexp_lo = 0, rexp_hi = 0;         // row `lane`: h + 64 of slices 0..3 / 4..7
   if (PRO == PRO_GAIN) {
-    float t = 0.f;
     const float* ss = d.sumsq + ((size_t)xcd * kUnitsPerXcd + gm.gl * S) * kMTile + lane;
-    for (int s2 = 0; s2 < S; ++s2) t += ss[(size_t)s2 * kMTile];
+    float ss8[8];
+#pragma unroll
+    for (int s2 = 0; s2 < 8; ++s2) ss8[s2] = ss[(size_t)min(s2, S - 1) * kMTile];
+    float t = 0.f;
+#pragma unroll
+    for (int s2 = 0; s2 < 8; ++s2) t += s2 < S ? ss8[s2] : 0.f;
     rstd_lane = 1.0f / sqrtf(t / (float)K + a.eps);
+    rexp_lo = row_exp_bytes(ss8[0], ss8[1], ss8[2], ss8[3]);
+    rexp_hi = row_exp_bytes(ss8[4], ss8[5], ss8[6], ss8[7]);
   }
   int pos_lane = 0, crow_lane = 0;
   if (EPI == EPI_QKV) {
@@ -555,6 +589,8 @@ __device__ inline void helper_gemm_phase(const StackArgs& a, const StackBufs& d,
   const int rbase = 4 * (lane >> 5);
   const int n_items = gm.t_count * 8;
   constexpr int kBatch = 4;
+  int cur_qd = -1;
+  float rinv[8][4], rstd4[4];
   for (int it0 = gm.sp + S * hw; it0 < n_items; it0 += 4 * S * kBatch) {
     uint2 part[kBatch][8];
     float pinv[kBatch][8];
@@ -587,16 +623,47 @@ __device__ inline void helper_gemm_phase(const StackArgs& a, const StackBufs& d,
       const int tile = gm.t_begin + tl;
       const int row0 = 8 * (qd & 3) + rbase + 32 * (qd >> 2);
       float v[4] = {0.f, 0.f, 0.f, 0.f};
+      if (PRO == PRO_GAIN && qd != cur_qd) {                         // as in gemm_stream_bf16
+        cur_qd = qd;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const unsigned elo = (unsigned)__shfl((int)rexp_lo, row0 + j, kWave);
+          const unsigned ehi = (unsigned)__shfl((int)rexp_hi, row0 + j, kWave);
+#pragma unroll
+          for (int s2 = 0; s2 < 8; ++s2) rinv[s2][j] = row_scale_inv(s2 < 4 ? elo : ehi, s2 & 3);
+          rstd4[j] = __shfl(rstd_lane, row0 + j, kWave);
+        }
+      }
+      int any_flag = 0;
 #pragma unroll
       for (int s2 = 0; s2 < 8; ++s2) {                               // fixed slice order
         const unsigned d0 = part[bi][s2].x, d1 = part[bi][s2].y;
-        const float w = pinv[bi][s2];                                // 0 beyond the last slice
-        v[0] += w * q16_lo(d0); v[1] += w * q16_hi(d0);
-        v[2] += w * q16_lo(d1); v[3] += w * q16_hi(d1);
+        const float w = fabsf(pinv[bi][s2]);                         // 0 beyond the last slice
+        any_flag |= __float_as_int(pinv[bi][s2]);
+        const float q[4] = {q16_lo(d0), q16_hi(d0), q16_lo(d1), q16_hi(d1)};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (PRO == PRO_GAIN)
+            v[j] = fmaf(w * q[j], rinv[s2][j], v[j]);
+          else
+            v[j] += w * q[j];
+        }
+      }
+      if (any_flag < 0) {                    // rare: a tile with non-finite elements among the eight
+        const float nan = __uint_as_float(0x7fc00000u);
+#pragma unroll
+        for (int s2 = 0; s2 < 8; ++s2) {
+          if (__float_as_int(pinv[bi][s2]) >= 0) continue;
+          const unsigned d0 = part[bi][s2].x, d1 = part[bi][s2].y;
+          if ((d0 & 0xffffu) == 0x8000u) v[0] = nan;
+          if ((d0 >> 16) == 0x8000u) v[1] = nan;
+          if ((d1 & 0xffffu) == 0x8000u) v[2] = nan;
+          if ((d1 >> 16) == 0x8000u) v[3] = nan;
+        }
       }
       if (PRO == PRO_GAIN) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] *= __shfl(rstd_lane, row0 + j, kWave);
+        for (int j = 0; j < 4; ++j) v[j] *= rstd4[j];
       }
       if (EPI == EPI_RESID) {
 #pragma unroll

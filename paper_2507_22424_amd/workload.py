@@ -158,6 +158,14 @@ def hidden_rows(cfg: VerifyConfig, episode: int) -> torch.Tensor:
                    cfg.torch_dtype)
 
 
+def row_magnitudes(cfg: VerifyConfig, episode: int, decades: float) -> torch.Tensor:
+    """One positive factor per tree node, 10^u with u uniform in [-decades, decades]: input rows of
+    very different size inside one batch (an outlier token, episodes at different scales)."""
+    rng = np.random.Generator(np.random.PCG64(seed_for(cfg, episode, 996)))
+    u = rng.uniform(-decades, decades, size=cfg.tree_nodes)
+    return torch.from_numpy((10.0 ** u).astype(np.float32))
+
+
 def prefix_lengths(cfg: VerifyConfig) -> np.ndarray:
     rng = np.random.Generator(np.random.PCG64(seed_for(cfg, 0, 997)))
     return rng.integers(cfg.prefix_lo, cfg.prefix_hi + 1, size=cfg.n_episodes).astype(np.int32)

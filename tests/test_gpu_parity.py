@@ -205,6 +205,41 @@ def test_bf16_degenerate_trees_and_prefixes(T, B, P):
     check_accept_paths(s, (0, 2))
 
 
+def test_bf16_rows_of_very_different_size_keep_their_relative_precision():
+    """Rows that share a 64-row tile and differ by up to 10^8 in size: every row still meets the
+    bar measured against its own size (the split-K partial sums travel as 16-bit fixed point, so
+    this holds only because each row is normalised before the tile's scale is chosen)."""
+    cfg = _small_bf16(T=30, B=2, P=60, name="bf16-row-sizes")
+    s = SideBySide(cfg, hidden_transform=lambda b, h: h * wl.row_magnitudes(cfg, b, 4.0)[:, None])
+    assert s.persistent_checked
+    check_forward(s, TOL["bf16"])
+
+
+def test_bf16_nan_in_one_episode_stays_in_that_episode():
+    """A NaN in an input row of episode 1: episode 0, which shares the row tile, the partial
+    tiles and the launches with it, is unaffected and still matches the oracle; the poisoned
+    row itself comes out as NaN on both sides."""
+    cfg = _small_bf16(T=24, B=2, P=50, name="bf16-nan-row")
+    T = cfg.tree_nodes
+
+    def poison(b, h):
+        if b == 1:
+            h = h.clone()
+            h[5, 17] = float("nan")
+        return h
+
+    with np.errstate(invalid="ignore"):              # the oracle meets the NaN too
+        s = SideBySide(cfg, hidden_transform=poison)
+    assert np.isnan(s.ref_x[T + 5]).any() and np.isnan(s.gpu_x[T + 5]).any()
+    assert np.isfinite(s.ref_x[:T]).all() and np.isfinite(s.gpu_x[:T]).all()
+    assert np.isfinite(s.gpu_logits[:T]).all()
+    err_x = np.max(np.abs(s.gpu_x[:T] - s.ref_x[:T]), axis=-1) / np.max(np.abs(s.ref_x[:T]), axis=-1)
+    say(f"[{cfg.name}] episode 0 beside a NaN episode: x err {err_x.max():.3e}, "
+        f"logit err {s.logit_err[:T].max():.3e}")
+    assert err_x.max() <= TOL["bf16"] and s.logit_err[:T].max() <= TOL["bf16"]
+    assert s.tolerated_ties(TOL["bf16"], n_rows=T)[1] == 0
+
+
 def test_accept_depth_cap_below_tree_depth():
     """A node deeper than d_cap counts as rejected: accepted' = accepted and depth <= d_cap."""
     rng = np.random.default_rng(77)
