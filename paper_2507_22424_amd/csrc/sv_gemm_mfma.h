@@ -14,16 +14,18 @@
 //   * activations stay float32 in memory; when a workgroup stages its K slice of X into LDS
 //     (once, in fragment order) each value is split into hi + lo bf16 parts and both are
 //     multiplied, so the product is accurate to ~2^-17 instead of 2^-9 at no cost in HBM
-//     bytes.  This keeps a 32-layer pass inside the 2e-2 bar.  With X resident, the main loop has no barrier: each of the
-//     four waves only streams weights, reads X fragments from LDS and issues MFMAs.
+//     bytes.  This keeps a 32-layer pass inside the 2e-2 bar.  With X resident, the main loop
+//     has no barrier: each of the four waves only streams weights, reads X fragments from LDS
+//     and issues MFMAs.
 //   * work unit = (group of 32-row tiles, K slice), one per workgroup, one workgroup per CU.
 //     The hardware deals workgroups to the eight XCDs round robin (workgroup i runs on XCD
-//     i % 8), so unit = f(workgroup id) puts all slices of a tile on one XCD and their partial
-//     tiles (16-bit fixed point with a per-tile scale: they are HBM traffic, the kernel is bound
-//     by its total traffic) meet in that XCD's L2: writer = plain stores, wait for completion, then an atomic
-//     on the group's arrival counter; once all slices have arrived (a short, bounded wait) every
-//     wave invalidates its L1 and takes an equal share of the group's output: it adds the
-//     partials in slice order (bit-reproducible) and runs the epilogue.  This is the
+//     i % 8; the grid's x dimension is the XCD), so all slices of a tile run on one XCD and
+//     their partial tiles (16-bit fixed point with a per-tile scale: they are HBM traffic, the
+//     kernel is bound by its total traffic) meet in that XCD's L2: writer = plain stores, wait
+//     for completion, then an atomic on the group's arrival counter; once all slices have
+//     arrived (a short, bounded wait) every wave invalidates its L1 and takes an equal share of
+//     the group's output: it adds the partials in slice order (bit-reproducible) and runs the
+//     epilogue (gemm_reduce_phase; one load round trip, which is what that phase costs).  This is the
 //     synchronisation the compiler itself emits between CUs that share an L2; the device-wide
 //     release (an L2 write-back per workgroup) measured 2x slower end to end.  The placement
 //     is checked, not assumed: every arrival adds to the 4-bit field of the XCD it really ran
@@ -219,8 +221,9 @@ __device__ inline int frag_slot(int l, int s) { return ((l & 31) ^ (((s & 7) << 
 // derived again from it: nothing of this phase stays live in scalar registers across the main
 // loop, where spilled scalars cost stalls between the matrix instructions.
 typedef const __attribute__((address_space(4))) GemmArgs* gemm_args_ptr_t;
+typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
 template <int PRO, int EPI>
-__device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, const int* s_pos, const int* s_crow,
+__device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos, int* s_crow,
                                                   int tid, int lane, int wave) {
   GemmArgs a;                                // one batch of scalar loads; registers from here on
   {
@@ -230,6 +233,20 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, const int*
 #pragma unroll
     for (unsigned i = 0; i < sizeof(GemmArgs) / 4; ++i) dst[i] = src[i];
   }
+  // pointers read from memory are generic to the compiler: name their address space, or every
+  // access becomes a flat one
+#define SV_GLOBAL(T, p) ((__attribute__((address_space(1))) T*)(p))
+  const auto part16 = SV_GLOBAL(const uint4, a.part16);
+  const auto pscale = SV_GLOBAL(const float, a.pscale);
+  const auto sumsq = SV_GLOBAL(const float, a.sumsq);
+  const auto status = SV_GLOBAL(int, a.status);
+  const auto x_io = SV_GLOBAL(float, a.x_io);
+  const auto act = SV_GLOBAL(float, a.act);
+  const auto q_out = SV_GLOBAL(float, a.q_out);
+  const auto kc = SV_GLOBAL(unsigned short, a.kc);
+  const auto vc = SV_GLOBAL(unsigned short, a.vc);
+  const auto depth = SV_GLOBAL(const int32_t, a.depth);
+  const auto prefix_len = SV_GLOBAL(const int32_t, a.prefix_len);
   const int mt = blockIdx.z, m0 = mt * kMTile;
   const int K = a.K, S = a.S;
   const int n_tiles = a.N / kFragRows;
@@ -249,7 +266,19 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, const int*
   // and the wait below is short; it is bounded all the same (status bit 2 on give-up).
   __builtin_amdgcn_s_waitcnt(0);           // this wave's partial tiles are in L2
   __syncthreads();
-  unsigned* gcnt = a.group_cnt + ((size_t)mt * G + g) * 2;
+  const auto gcnt = SV_GLOBAL(unsigned, a.group_cnt) + ((size_t)mt * G + g) * 2;
+#undef SV_GLOBAL
+  if (EPI == EPI_QKV && tid >= 64 && tid < 64 + kMTile) {
+    // rotary position and cache row of each row of the m tile, by the second wave while the
+    // first one waits for the group (ordered before their use by the barrier below)
+    const int r = tid - 64;
+    const int m = min(m0 + r, a.M - 1);
+    const int b = m / a.T, t = m - b * a.T;
+    int P = prefix_len[b];
+    P = P < 0 ? 0 : (P > a.p_max ? a.p_max : P);
+    s_pos[r] = P + depth[m];
+    s_crow[r] = b * a.nh * a.cap + P + t;    // + head * cap, times 128, in the epilogue
+  }
   if (tid == 0) {
     const unsigned field = 4u * (unsigned)xcd_actual(a.n_xcd);
     __hip_atomic_fetch_add(gcnt, 1u << field, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -264,7 +293,7 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, const int*
     int bad = 0;
     if (n < (unsigned)S) bad |= 2;                                  // gave up waiting
     else if (v != ((unsigned)S << field)) bad |= 1;                 // slices on several XCDs
-    if (bad) atomicOr(a.status, bad);
+    if (bad) __hip_atomic_fetch_or(status, bad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   __syncthreads();
   asm volatile("buffer_inv sc0" ::: "memory");                      // drop stale L1 lines (the L2 is shared)
@@ -275,7 +304,7 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, const int*
   if (PRO == PRO_GAIN) {
 #pragma unroll
     for (int s2 = 0; s2 < 8; ++s2)
-      ss8[s2] = a.sumsq[(((size_t)mt * G + g) * S + min(s2, S - 1)) * kMTile + lane];
+      ss8[s2] = sumsq[(((size_t)mt * G + g) * S + min(s2, S - 1)) * kMTile + lane];
   }
   float rstd_lane = 1.0f;
   unsigned rexp_lo = 0, rexp_hi = 0;       // row `lane`: h + 64 of slices 0..3 / 4..7
@@ -296,135 +325,139 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, const int*
     float rinv[8][4], rstd4[4];
     bool have_rows = false;
     for (int tl0 = wk >> 3; tl0 < t_count; tl0 += t_step * kRedBatch) {
-    uint2 part[kRedBatch][8];
-    float pinv[kRedBatch][8];
-    float xres[kRedBatch][4];
+      u32x2_t part[kRedBatch][8];
+      float pinv[kRedBatch][8];
+      float xres[kRedBatch][4];
 #pragma unroll
-    for (int bi = 0; bi < kRedBatch; ++bi) {                        // all loads of the batch first
-      const int tl = tl0 + t_step * bi;
-      if (tl >= t_count) break;
-      const int tile = t_begin + tl;
-      // registers 4qd .. 4qd+3 of the tile = dwords 2qd, 2qd+1 = half of the uint4 of store qd/2
-      const size_t pidx = ((size_t)mt * n_tiles + tile) * S;
-      const uint2* pb = reinterpret_cast<const uint2*>(a.part16 + pidx * kTileVec4 + (qd >> 1) * 64 + lane) + (qd & 1);
-#pragma unroll
-      for (int s2 = 0; s2 < 8; ++s2) {
-        const int sc = min(s2, S - 1);
-        part[bi][s2] = pb[(size_t)sc * (kTileVec4 * 2)];
-        pinv[bi][s2] = s2 < S ? a.pscale[pidx + sc] : 0.f;
-      }
-      if (EPI == EPI_RESID) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          xres[bi][j] = a.x_io[(size_t)min(m0 + row0 + j, a.M - 1) * a.N + tile * 32 + ln];
-      }
-    }
-    // The phase is bound by the round trips of these loads, not by arithmetic: keep the whole
-    // batch in flight together (left alone, the compiler sinks loads towards their uses).
-    asm volatile("" ::: "memory");
-    if (PRO == PRO_GAIN && !have_rstd) {
-      float t = 0.f;
-#pragma unroll
-      for (int s2 = 0; s2 < 8; ++s2) t += s2 < S ? ss8[s2] : 0.f;
-      rstd_lane = 1.0f / sqrtf(t / (float)K + a.eps);
-      rexp_lo = row_exp_bytes(ss8[0], ss8[1], ss8[2], ss8[3]);
-      rexp_hi = row_exp_bytes(ss8[4], ss8[5], ss8[6], ss8[7]);
-      have_rstd = true;
-    }
-    if (PRO == PRO_GAIN && !have_rows) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const unsigned elo = (unsigned)__shfl((int)rexp_lo, row0 + j, kWave);
-        const unsigned ehi = (unsigned)__shfl((int)rexp_hi, row0 + j, kWave);
-#pragma unroll
-        for (int s2 = 0; s2 < 8; ++s2) rinv[s2][j] = row_scale_inv(s2 < 4 ? elo : ehi, s2 & 3);
-        rstd4[j] = __shfl(rstd_lane, row0 + j, kWave);
-      }
-      have_rows = true;
-    }
-#pragma unroll
-    for (int bi = 0; bi < kRedBatch; ++bi) {
-      const int tl = tl0 + t_step * bi;
-      if (tl >= t_count) break;
-      const int tile = t_begin + tl;
-      float v[4] = {0.f, 0.f, 0.f, 0.f};
-      int any_flag = 0;                                             // sign bits of the inverse scales
-#pragma unroll
-      for (int s2 = 0; s2 < 8; ++s2) {                              // fixed slice order
-        const unsigned d0 = part[bi][s2].x, d1 = part[bi][s2].y;
-        const float w = fabsf(pinv[bi][s2]);                        // 0 beyond the last slice
-        any_flag |= __float_as_int(pinv[bi][s2]);
-        const float q[4] = {q16_lo(d0), q16_hi(d0), q16_lo(d1), q16_hi(d1)};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          // tile scale first, row scale second: neither product can overflow on its own
-          if (PRO == PRO_GAIN)
-            v[j] = fmaf(w * q[j], rinv[s2][j], v[j]);
-          else
-            v[j] += w * q[j];
-        }
-      }
-      if (any_flag < 0) {                  // rare: a tile with non-finite elements among the eight
-        const float nan = __uint_as_float(0x7fc00000u);
+      for (int bi = 0; bi < kRedBatch; ++bi) {                        // all loads of the batch first
+        const int tl = tl0 + t_step * bi;
+        if (tl >= t_count) break;
+        const int tile = t_begin + tl;
+        // registers 4qd .. 4qd+3 of the tile = dwords 2qd, 2qd+1 = half of the uint4 of store qd/2
+        const size_t pidx = ((size_t)mt * n_tiles + tile) * S;
+        const auto pb = (const __attribute__((address_space(1))) u32x2_t*)(part16 + pidx * kTileVec4 + (qd >> 1) * 64 + lane) + (qd & 1);
 #pragma unroll
         for (int s2 = 0; s2 < 8; ++s2) {
-          if (__float_as_int(pinv[bi][s2]) >= 0) continue;
+          const int sc = min(s2, S - 1);
+          part[bi][s2] = pb[(size_t)sc * (kTileVec4 * 2)];
+          pinv[bi][s2] = s2 < S ? pscale[pidx + sc] : 0.f;
+        }
+        if (EPI == EPI_RESID) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            xres[bi][j] = x_io[(size_t)min(m0 + row0 + j, a.M - 1) * a.N + tile * 32 + ln];
+        }
+      }
+      // The phase is bound by the round trips of these loads, not by arithmetic: keep the whole
+      // batch in flight together (left alone, the compiler sinks loads towards their uses).
+      asm volatile("" ::: "memory");
+      if (PRO == PRO_GAIN && !have_rstd) {
+        // the row sums were requested before the batch; their first use must not move ahead of
+        // the batch's loads, or the two round trips happen one after the other
+#pragma unroll
+        for (int s2 = 0; s2 < 8; ++s2) asm volatile("" : "+v"(ss8[s2]));
+        float t = 0.f;
+#pragma unroll
+        for (int s2 = 0; s2 < 8; ++s2) t += s2 < S ? ss8[s2] : 0.f;
+        rstd_lane = 1.0f / sqrtf(t / (float)K + a.eps);
+        rexp_lo = row_exp_bytes(ss8[0], ss8[1], ss8[2], ss8[3]);
+        rexp_hi = row_exp_bytes(ss8[4], ss8[5], ss8[6], ss8[7]);
+        have_rstd = true;
+      }
+      if (PRO == PRO_GAIN && !have_rows) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const unsigned elo = (unsigned)__shfl((int)rexp_lo, row0 + j, kWave);
+          const unsigned ehi = (unsigned)__shfl((int)rexp_hi, row0 + j, kWave);
+#pragma unroll
+          for (int s2 = 0; s2 < 8; ++s2) rinv[s2][j] = row_scale_inv(s2 < 4 ? elo : ehi, s2 & 3);
+          rstd4[j] = __shfl(rstd_lane, row0 + j, kWave);
+        }
+        have_rows = true;
+      }
+#pragma unroll
+      for (int bi = 0; bi < kRedBatch; ++bi) {
+        const int tl = tl0 + t_step * bi;
+        if (tl >= t_count) break;
+        const int tile = t_begin + tl;
+        float v[4] = {0.f, 0.f, 0.f, 0.f};
+        int any_flag = 0;                                             // sign bits of the inverse scales
+#pragma unroll
+        for (int s2 = 0; s2 < 8; ++s2) {                              // fixed slice order
           const unsigned d0 = part[bi][s2].x, d1 = part[bi][s2].y;
-          if ((d0 & 0xffffu) == 0x8000u) v[0] = nan;
-          if ((d0 >> 16) == 0x8000u) v[1] = nan;
-          if ((d1 & 0xffffu) == 0x8000u) v[2] = nan;
-          if ((d1 >> 16) == 0x8000u) v[3] = nan;
-        }
-      }
-      if (PRO == PRO_GAIN) {
+          const float w = fabsf(pinv[bi][s2]);                        // 0 beyond the last slice
+          any_flag |= __float_as_int(pinv[bi][s2]);
+          const float q[4] = {q16_lo(d0), q16_hi(d0), q16_lo(d1), q16_hi(d1)};
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] *= rstd4[j];
-      }
-      if (EPI == EPI_RESID) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          if (m0 + row0 + j < a.M)
-            a.x_io[(size_t)(m0 + row0 + j) * a.N + tile * 32 + ln] = xres[bi][j] + v[j];
-      }
-      if (EPI == EPI_SWIGLU) {             // lanes 0..15 gate, 16..31 up of the same column
-        const int F = a.N / 2;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const float up = __shfl_xor(v[j], 16, kWave);
-          if (ln < 16 && m0 + row0 + j < a.M)
-            a.act[(size_t)(m0 + row0 + j) * F + tile * 16 + ln] = v[j] / (1.0f + expf(-v[j])) * up;
-        }
-      }
-      if (EPI == EPI_QKV) {
-        const int tiles_per_mat = a.nh * 4;  // 128 rows per head = 4 tiles
-        const int which = tile / tiles_per_mat;                  // 0 q, 1 k, 2 v
-        const int head = (tile % tiles_per_mat) / 4, uq = tile % 4;
-        const int jr = 16 * uq + (ln & 15);                      // rotary pair index, 0..63
-        const int dcol = jr + 64 * (ln >> 4);                    // column inside the head
-        // angle in turns = position * theta^(-2j/128) / (2 pi)
-        const float turn_freq = exp2f(-(float)jr * (1.0f / 64.0f) * log2f(a.theta)) * 0.15915494309189535f;
-        const float sgn = (ln & 16) ? 1.0f : -1.0f;
-        const int D = a.nh * 128;
-        bf16_t* cache = which == 1 ? a.kc : a.vc;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int ml = row0 + j;
-          float val = v[j];
-          const float partner = __shfl_xor(val, 16, kWave);
-          if (which != 2) {
-            float turns = (float)s_pos[ml] * turn_freq;
-            turns -= floorf(turns);        // reduced to [0, 1) before the hardware sin / cos
-            val = val * __builtin_amdgcn_cosf(turns) + sgn * partner * __builtin_amdgcn_sinf(turns);
-          }
-          if (m0 + ml < a.M) {
-            if (which == 0)
-              a.q_out[(size_t)(m0 + ml) * D + head * 128 + dcol] = val;
+          for (int j = 0; j < 4; ++j) {
+            // tile scale first, row scale second: neither product can overflow on its own
+            if (PRO == PRO_GAIN)
+              v[j] = fmaf(w * q[j], rinv[s2][j], v[j]);
             else
-              cache[((size_t)s_crow[ml] + (size_t)head * a.cap) * 128 + dcol] = f32_to_bf16(val);
+              v[j] += w * q[j];
+          }
+        }
+        if (any_flag < 0) {                  // rare: a tile with non-finite elements among the eight
+          const float nan = __uint_as_float(0x7fc00000u);
+#pragma unroll
+          for (int s2 = 0; s2 < 8; ++s2) {
+            if (__float_as_int(pinv[bi][s2]) >= 0) continue;
+            const unsigned d0 = part[bi][s2].x, d1 = part[bi][s2].y;
+            if ((d0 & 0xffffu) == 0x8000u) v[0] = nan;
+            if ((d0 >> 16) == 0x8000u) v[1] = nan;
+            if ((d1 & 0xffffu) == 0x8000u) v[2] = nan;
+            if ((d1 >> 16) == 0x8000u) v[3] = nan;
+          }
+        }
+        if (PRO == PRO_GAIN) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) v[j] *= rstd4[j];
+        }
+        if (EPI == EPI_RESID) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            if (m0 + row0 + j < a.M)
+              x_io[(size_t)(m0 + row0 + j) * a.N + tile * 32 + ln] = xres[bi][j] + v[j];
+        }
+        if (EPI == EPI_SWIGLU) {             // lanes 0..15 gate, 16..31 up of the same column
+          const int F = a.N / 2;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const float up = __shfl_xor(v[j], 16, kWave);
+            if (ln < 16 && m0 + row0 + j < a.M)
+              act[(size_t)(m0 + row0 + j) * F + tile * 16 + ln] = v[j] / (1.0f + expf(-v[j])) * up;
+          }
+        }
+        if (EPI == EPI_QKV) {
+          const int tiles_per_mat = a.nh * 4;  // 128 rows per head = 4 tiles
+          const int which = tile / tiles_per_mat;                  // 0 q, 1 k, 2 v
+          const int head = (tile % tiles_per_mat) / 4, uq = tile % 4;
+          const int jr = 16 * uq + (ln & 15);                      // rotary pair index, 0..63
+          const int dcol = jr + 64 * (ln >> 4);                    // column inside the head
+          // angle in turns = position * theta^(-2j/128) / (2 pi)
+          const float turn_freq = exp2f(-(float)jr * (1.0f / 64.0f) * log2f(a.theta)) * 0.15915494309189535f;
+          const float sgn = (ln & 16) ? 1.0f : -1.0f;
+          const int D = a.nh * 128;
+          const auto cache = which == 1 ? kc : vc;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int ml = row0 + j;
+            float val = v[j];
+            const float partner = __shfl_xor(val, 16, kWave);
+            if (which != 2) {
+              float turns = (float)s_pos[ml] * turn_freq;
+              turns -= floorf(turns);        // reduced to [0, 1) before the hardware sin / cos
+              val = val * __builtin_amdgcn_cosf(turns) + sgn * partner * __builtin_amdgcn_sinf(turns);
+            }
+            if (m0 + ml < a.M) {
+              if (which == 0)
+                q_out[(size_t)(m0 + ml) * D + head * 128 + dcol] = val;
+              else
+                cache[((size_t)s_crow[ml] + (size_t)head * a.cap) * 128 + dcol] = f32_to_bf16(val).bits;
+            }
           }
         }
       }
-    }
     }
   }
   // the last workgroup to get here clears the group's two words for the next launch
@@ -455,15 +488,6 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
   const int G = a.n_xcd * a.gpx;
   const int xcd = blockIdx.x;                // workgroups are dealt to the XCDs in turn, x fastest
   const int u = blockIdx.y;                  // unit inside that XCD's share
-
-  if (EPI == EPI_QKV && tid < kMTile) {
-    const int m = min(m0 + tid, a.M - 1);
-    const int b = m / a.T, t = m - b * a.T;
-    int P = a.prefix_len[b];
-    P = P < 0 ? 0 : (P > a.p_max ? a.p_max : P);
-    s_pos[tid] = P + a.depth[m];
-    s_crow[tid] = b * a.nh * a.cap + P + t;  // + head * cap, times 128, in the epilogue
-  }
 
   {
     const int ug = (int)(((unsigned)u * a.inv_S) >> 16);   // u / S
