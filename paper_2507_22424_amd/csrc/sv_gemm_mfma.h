@@ -501,7 +501,6 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
     const int np = pq + (sp < prem ? 1 : 0);             // pieces in the slice
     const int n_chunks = (np + 3) >> 2;                  // LDS chunks of 4 pieces
     const int my_tiles = t_count > wave ? (t_count - wave + 3) / 4 : 0;   // tiles wave, wave+4, ..
-    const int rounds = (t_count + 3) / 4;                // the same for the four waves
     const size_t unit_id = ((size_t)mt * G + g) * S + sp;
     const size_t tile_stride = (size_t)(K / kFragK) * 64;                 // uint4 per tile
     typedef const __attribute__((address_space(1))) u32x4_t* wptr_t;
@@ -536,21 +535,17 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) ssq[r] = 0.f;
 
-    // Stage chunk c of this slice: wave w converts rows w, w+4, .. ; lane = 8-wide k chunk.
-    // `with_ring`: the ring is filled right behind the X loads (loads return in issue order,
-    // so X is not held up by the slower weight loads, and both overlap the conversion).
-    auto stage = [&](int c, bool with_ring) {
+    // Staging chunk c of this slice, in two halves: wave w handles rows w, w+4, .. ; lane = 8-wide
+    // k chunk.  x_load issues all 32 loads of the lane's 16 rows (and the gain), x_convert splits
+    // the values into hi + lo bf16 and writes them to LDS in fragment order.
+    auto x_load = [&](int c, float4 (&xa)[16], float4 (&xb)[16], float4& g0, float4& g1) {
       const int nkc = min(4, np - 4 * c) * 16;     // 8-wide chunks per row in this K chunk
-      const bool on = lane < nkc;
-      const int k = (p_begin + 4 * c) * kBlkK + (on ? lane : 0) * 8;
-      float4 g0 = make_float4(1.f, 1.f, 1.f, 1.f), g1 = g0;
+      const int k = (p_begin + 4 * c) * kBlkK + (lane < nkc ? lane : 0) * 8;
+      g0 = g1 = make_float4(1.f, 1.f, 1.f, 1.f);
       if (PRO == PRO_GAIN) {
         g0 = *reinterpret_cast<const float4*>(a.gain + k);
         g1 = *reinterpret_cast<const float4*>(a.gain + k + 4);
       }
-      const int s = lane >> 1;                     // k-step inside the chunk
-      // all 32 loads of this lane's 16 rows are issued before the first conversion
-      float4 xa[16], xb[16];
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int m = m0 + wave + 4 * r;
@@ -558,25 +553,25 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
         xa[r] = *reinterpret_cast<const float4*>(p);
         xb[r] = *reinterpret_cast<const float4*>(p + 4);
       }
-      if (with_ring) {
-#pragma unroll
-        for (int sl = 0; sl < kRing; ++sl) issue(ring[sl]);
-      }
+    };
+    auto x_convert = [&](int c, const float4 (&xa)[16], const float4 (&xb)[16], const float4& g0,
+                         const float4& g1) {
+      const int nkc = min(4, np - 4 * c) * 16;
+      const bool on = lane < nkc;
+      const int s = lane >> 1;                     // k-step inside the chunk
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
+        // (rows beyond M repeat row M - 1: they cost nothing extra and are never written out)
         const int ml = wave + 4 * r;
-        const float keep = (on && (m0 + ml < a.M)) ? 1.0f : 0.0f;
         float v[8] = {xa[r].x, xa[r].y, xa[r].z, xa[r].w, xb[r].x, xb[r].y, xb[r].z, xb[r].w};
         if (PRO == PRO_GAIN) {
           float t = 0.f;
 #pragma unroll
           for (int e = 0; e < 8; ++e) t += v[e] * v[e];
-          ssq[r] += t * keep;
+          ssq[r] += on ? t : 0.f;
           v[0] *= g0.x; v[1] *= g0.y; v[2] *= g0.z; v[3] *= g0.w;
           v[4] *= g1.x; v[5] *= g1.y; v[6] *= g1.z; v[7] *= g1.w;
         }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] *= keep;
         uint4 hi4, lo4;
         hi4.x = pack_bf16x2(v[0], v[1]); hi4.y = pack_bf16x2(v[2], v[3]);
         hi4.z = pack_bf16x2(v[4], v[5]); hi4.w = pack_bf16x2(v[6], v[7]);
@@ -630,17 +625,22 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
         s_rowscale[wave + 4 * r] = row_scale(v1);   // (an infinite or NaN sum: any scale will do, the values are not finite either)
       }
     };
-    stage(0, true);
+    {
+      // chunk 0; the ring is filled right behind the X loads (loads return in issue order, so X
+      // is not held up by the slower weight loads, and both overlap the conversion)
+      float4 xa[16], xb[16], g0, g1;
+      x_load(0, xa, xb, g0, g1);
+#pragma unroll
+      for (int sl = 0; sl < kRing; ++sl) issue(ring[sl]);
+      x_convert(0, xa, xb, g0, g1);
+    }
     if (PRO == PRO_GAIN && n_chunks == 1) publish_ssq();
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // X chunk 0 is in LDS; weight loads stay in flight
 
     f32x16_t acc0 = {}, acc1 = {};
     const int rbase = 4 * (lane >> 5);
-    const bool multi = MULTI && n_chunks > 1;
     int ct = 0, cj = 0;                                  // piece being consumed: tile count, piece
-    // a slice longer than one LDS chunk is walked by all four waves together (re-staging needs
-    // them all), also by a wave that has no tile; otherwise every wave just walks its own tiles
-    int steps_left = (multi ? rounds : my_tiles) * np;
+    int steps_left = my_tiles * np;                      // single-chunk form: every wave walks its own tiles
     // partial tile of this wave's current tile and this slice (data, inverse scale)
     const size_t pidx0 = ((size_t)mt * n_tiles + t_begin + wave) * S + sp;
     const uint4* pt = a.part16 + pidx0 * kTileVec4 + lane;
@@ -652,17 +652,9 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
     // a zero addend instead of cleared accumulators, finished tiles are stored straight from the
     // accumulator registers.
     auto step = [&](u32x4_t* buf) {
-      if (steps_left > 0) {
+      if (MULTI || steps_left > 0) {
         --steps_left;
         const int jq = cj & 3;
-        if (MULTI && multi && jq == 0 && cj > 0) {
-          // re-stage X for the next chunk: the accumulators carry over; the barriers order LDS
-          // traffic only, weight loads stay in flight
-          asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-          stage(cj >> 2, false);
-          if (PRO == PRO_GAIN && (cj >> 2) == n_chunks - 1) publish_ssq();
-          asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        }
         if (ct < my_tiles) {
           const uint4* xf = xs + (size_t)(jq * kPieceFrags * 4) * 64;
           // One basic block per piece: 32 LDS reads and 32 MFMAs.  The schedule is pinned so
@@ -785,9 +777,31 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
       }
       issue(buf);
     };
-    while (steps_left > 0) {
+    if (MULTI) {
+      // A slice of several LDS chunks: a group has at most four tiles here, one per wave, whose
+      // accumulators carry over from chunk to chunk, and all four waves walk the chunks together
+      // (also a wave without a tile: re-staging needs them all).  The X rows of the next chunk
+      // are requested before the four pieces of the current one are multiplied, so that their
+      // round trip runs under the matrix work; every load keeps a fixed place in the order of
+      // issue, and the waits stay exact.  The barriers order LDS traffic only.
+      for (int c = 0; c < n_chunks; ++c) {
+        const int cn = min(c + 1, n_chunks - 1);         // (the last round re-reads its own rows, unused)
+        float4 xa[16], xb[16], g0, g1;
+        x_load(cn, xa, xb, g0, g1);
 #pragma unroll
-      for (int sl = 0; sl < kRing; ++sl) step(ring[sl]);
+        for (int sl = 0; sl < kRing; ++sl) step(ring[sl]);
+        if (c + 1 < n_chunks) {
+          asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // chunk c has been read by all
+          x_convert(cn, xa, xb, g0, g1);
+          if (PRO == PRO_GAIN && cn == n_chunks - 1) publish_ssq();
+          asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        }
+      }
+    } else {
+      while (steps_left > 0) {
+#pragma unroll
+        for (int sl = 0; sl < kRing; ++sl) step(ring[sl]);
+      }
     }
 
     // ---- second half: group barrier, reduction, epilogue (arguments read afresh) ----

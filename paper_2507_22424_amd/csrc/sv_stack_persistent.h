@@ -392,18 +392,15 @@ __device__ inline void helper_gemm_phase(const StackArgs& a, const StackBufs& d,
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int ml = hw + 4 * r;
-      const float keep = (on && ml < M) ? 1.0f : 0.0f;
       float v[8] = {xa[r].x, xa[r].y, xa[r].z, xa[r].w, xb[r].x, xb[r].y, xb[r].z, xb[r].w};
       if (PRO == PRO_GAIN) {
         float t = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) t += v[e] * v[e];
-        ssq[r] += t * keep;
+        ssq[r] += on ? t : 0.f;
         v[0] *= g0.x; v[1] *= g0.y; v[2] *= g0.z; v[3] *= g0.w;
         v[4] *= g1.x; v[5] *= g1.y; v[6] *= g1.z; v[7] *= g1.w;
       }
-#pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] *= keep;
       uint4 hi4, lo4;
       hi4.x = pack_bf16x2(v[0], v[1]); hi4.y = pack_bf16x2(v[2], v[3]);
       hi4.z = pack_bf16x2(v[4], v[5]); hi4.w = pack_bf16x2(v[6], v[7]);
