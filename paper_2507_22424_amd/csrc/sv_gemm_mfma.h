@@ -156,13 +156,23 @@ __device__ inline float bf16_hi_f32(uint32_t packed) { return __uint_as_float(pa
 
 // |v| as an integer that orders like the magnitude, NaN above infinity above all numbers
 __device__ inline unsigned mag_bits(float v) { return __float_as_uint(v) & 0x7fffffffu; }
+// maximum over the wave, in all-VALU data-parallel-primitive steps (a butterfly of lane
+// permutes through LDS costs several hundred cycles of latency per tile): a running maximum
+// inside each row of 16 lanes, then the row results handed on to the last lane, which is read.
+// Lanes a step has no source for take the 0 given as the old value.
 __device__ inline unsigned wave_max_u32(unsigned v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) {
-    const unsigned o = (unsigned)__shfl_xor((int)v, off, kWave);
+  auto step = [&](auto ctrl, auto rows) {
+    const unsigned o = (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, decltype(ctrl)::value, decltype(rows)::value, 0xf, false);
     v = v > o ? v : o;
-  }
-  return v;
+  };
+  typedef std::integral_constant<int, 0xf> all_rows;
+  step(std::integral_constant<int, 0x111>{}, all_rows{});                          // row_shr:1
+  step(std::integral_constant<int, 0x112>{}, all_rows{});                          // row_shr:2
+  step(std::integral_constant<int, 0x114>{}, all_rows{});                          // row_shr:4
+  step(std::integral_constant<int, 0x118>{}, all_rows{});                          // row_shr:8: lane 15 of a row has the row's maximum
+  step(std::integral_constant<int, 0x142>{}, std::integral_constant<int, 0xa>{});  // row_bcast:15 into rows 1 and 3
+  step(std::integral_constant<int, 0x143>{}, std::integral_constant<int, 0xc>{});  // row_bcast:31 into rows 2 and 3
+  return (unsigned)__builtin_amdgcn_readlane((int)v, 63);
 }
 constexpr unsigned kInfBits = 0x7f800000u;
 __device__ inline unsigned finite_mag_bits(float v) {
@@ -183,7 +193,7 @@ __device__ inline void partial_tile_scale(unsigned max_bits, float& scale, float
 __device__ inline unsigned pack_q16x2(float a, float b, float scale) {
   const unsigned ua = __float_as_uint(fmaf(a, scale, 12582912.0f));
   const unsigned ub = __float_as_uint(fmaf(b, scale, 12582912.0f));
-  return (ua & 0xffffu) | (ub << 16);
+  return __builtin_amdgcn_perm(ub, ua, 0x05040100u);     // low halves of ua (bits 15:0) and ub (bits 31:16)
 }
 // h = floor(exponent(ssq) / 2), -64 .. 64: the row is stored times 2^-h and read back times 2^h
 __device__ inline int row_half_exp(float ssq) { return ((int)((__float_as_uint(ssq) >> 23) & 255u) - 127) >> 1; }
@@ -204,6 +214,17 @@ __device__ inline unsigned pack_q16x2_coded(float a, float b, float scale) {
 }
 __device__ inline float q16_lo(unsigned d) { return (float)((int)(d << 16) >> 16); }
 __device__ inline float q16_hi(unsigned d) { return (float)((int)d >> 16); }
+
+// Value of the lane 16 places away (lane ^ 16) without a trip through LDS: the gfx950 row swap
+// returns {rows 0,0,2,2} and {rows 1,1,3,3} of its operand (rows of 16 lanes).
+__device__ inline float lane_xor16(float v, int lane) {
+  const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float((lane & 16) ? r[0] : r[1]);
+}
+// x * sigmoid(x) with the hardware exponential and reciprocal (1 ulp each)
+__device__ inline float silu_fast(float x) {
+  return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x));
+}
 
 // XCD (accelerator complex die) this wave runs on: bits 3:0 of the XCC_ID hardware register.
 __device__ inline int xcd_actual(int n_xcd) {
@@ -281,14 +302,16 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
   }
   if (tid == 0) {
     const unsigned field = 4u * (unsigned)xcd_actual(a.n_xcd);
-    __hip_atomic_fetch_add(gcnt, 1u << field, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    unsigned v = 0, n = 0;
+    // the value the add returns is the first look at the counter: the last slice to arrive -
+    // the one the group's finish time hangs on - goes on without a second round trip
+    unsigned v = __hip_atomic_fetch_add(gcnt, 1u << field, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + (1u << field);
+    unsigned n = 0;
     for (int spin = 0; spin < (1 << 16); ++spin) {
-      v = __hip_atomic_load(gcnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // not from L1
       n = 0;
 #pragma unroll
       for (int x = 0; x < kXcds; ++x) n += (v >> (4 * x)) & 15u;
       if (n >= (unsigned)S) break;
+      v = __hip_atomic_load(gcnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // not from L1
     }
     int bad = 0;
     if (n < (unsigned)S) bad |= 2;                                  // gave up waiting
@@ -423,9 +446,9 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
           const int F = a.N / 2;
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
-            const float up = __shfl_xor(v[j], 16, kWave);
+            const float up = lane_xor16(v[j], lane);
             if (ln < 16 && m0 + row0 + j < a.M)
-              act[(size_t)(m0 + row0 + j) * F + tile * 16 + ln] = v[j] / (1.0f + expf(-v[j])) * up;
+              act[(size_t)(m0 + row0 + j) * F + tile * 16 + ln] = silu_fast(v[j]) * up;
           }
         }
         if (EPI == EPI_QKV) {
@@ -443,7 +466,7 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
           for (int j = 0; j < 4; ++j) {
             const int ml = row0 + j;
             float val = v[j];
-            const float partner = __shfl_xor(val, 16, kWave);
+            const float partner = lane_xor16(val, lane);
             if (which != 2) {
               float turns = (float)s_pos[ml] * turn_freq;
               turns -= floorf(turns);        // reduced to [0, 1) before the hardware sin / cos
@@ -639,6 +662,17 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
 
     f32x16_t acc0 = {}, acc1 = {};
     const int rbase = 4 * (lane >> 5);
+    // row scales of this lane's 32 accumulator rows: known from here on in the single-chunk
+    // form (kept in registers: a tile's end is on the critical path), read at the tile's end
+    // in the other, where the row sums are complete only with the last chunk
+    float4 rsa[4], rsb[4];
+    if (PRO == PRO_GAIN && !MULTI) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        rsa[i] = *reinterpret_cast<const float4*>(&s_rowscale[8 * i + rbase]);
+        rsb[i] = *reinterpret_cast<const float4*>(&s_rowscale[32 + 8 * i + rbase]);
+      }
+    }
     int ct = 0, cj = 0;                                  // piece being consumed: tile count, piece
     int steps_left = my_tiles * np;                      // single-chunk form: every wave walks its own tiles
     // partial tile of this wave's current tile and this slice (data, inverse scale)
@@ -710,8 +744,8 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
             for (int i = 0; i < 4; ++i) {
               float4 ra = make_float4(1.f, 1.f, 1.f, 1.f), rb = ra;
               if (PRO == PRO_GAIN) {                     // rows brought to a common size
-                ra = *reinterpret_cast<const float4*>(&s_rowscale[8 * i + rbase]);
-                rb = *reinterpret_cast<const float4*>(&s_rowscale[32 + 8 * i + rbase]);
+                ra = MULTI ? *reinterpret_cast<const float4*>(&s_rowscale[8 * i + rbase]) : rsa[i];
+                rb = MULTI ? *reinterpret_cast<const float4*>(&s_rowscale[32 + 8 * i + rbase]) : rsb[i];
               }
               t0[4 * i] = acc0[4 * i] * ra.x;         t1[4 * i] = acc1[4 * i] * rb.x;
               t0[4 * i + 1] = acc0[4 * i + 1] * ra.y; t1[4 * i + 1] = acc1[4 * i + 1] * rb.y;
@@ -725,7 +759,7 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
               const unsigned mm = m0_ > m1_ ? m0_ : m1_;
               tmax = tmax > mm ? tmax : mm;
             }
-            unsigned wmax = (unsigned)__builtin_amdgcn_readfirstlane((int)wave_max_u32(tmax));
+            unsigned wmax = wave_max_u32(tmax);
             const bool clean = wmax < kInfBits;
             if (!clean) {                                // rare: the maximum of the finite elements
               tmax = 0u;
@@ -735,7 +769,7 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
                 const unsigned mm = m0_ > m1_ ? m0_ : m1_;
                 tmax = tmax > mm ? tmax : mm;
               }
-              wmax = (unsigned)__builtin_amdgcn_readfirstlane((int)wave_max_u32(tmax));
+              wmax = wave_max_u32(tmax);
             }
             float psc, pinv;
             partial_tile_scale(wmax, psc, pinv);

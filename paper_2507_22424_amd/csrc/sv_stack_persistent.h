@@ -474,7 +474,7 @@ __device__ inline void helper_gemm_phase(const StackArgs& a, const StackBufs& d,
       const unsigned m1 = ma > mb ? ma : mb, m2 = mc > md ? mc : md, m3 = m1 > m2 ? m1 : m2;
       tmax = tmax > m3 ? tmax : m3;
     }
-    unsigned wmax = (unsigned)__builtin_amdgcn_readfirstlane((int)wave_max_u32(tmax));
+    unsigned wmax = wave_max_u32(tmax);
     const bool clean = wmax < kInfBits;
     if (!clean) {                                      // rare: the maximum of the finite elements
       tmax = 0u;
@@ -485,7 +485,7 @@ __device__ inline void helper_gemm_phase(const StackArgs& a, const StackBufs& d,
         const unsigned m1 = ma > mb ? ma : mb, m2 = mc > md ? mc : md, m3 = m1 > m2 ? m1 : m2;
         tmax = tmax > m3 ? tmax : m3;
       }
-      wmax = (unsigned)__builtin_amdgcn_readfirstlane((int)wave_max_u32(tmax));
+      wmax = wave_max_u32(tmax);
     }
     float psc, pinv;
     partial_tile_scale(wmax, psc, pinv);
@@ -671,9 +671,9 @@ __device__ inline void helper_gemm_phase(const StackArgs& a, const StackBufs& d,
         const int F = N / 2;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          const float up = __shfl_xor(v[j], 16, kWave);
+          const float up = lane_xor16(v[j], lane);
           if (ln < 16 && row0 + j < M)
-            st_dev(d.act + (size_t)(row0 + j) * F + tile * 16 + ln, v[j] / (1.0f + expf(-v[j])) * up);
+            st_dev(d.act + (size_t)(row0 + j) * F + tile * 16 + ln, silu_fast(v[j]) * up);
         }
       }
       if (EPI == EPI_QKV) {
@@ -690,7 +690,7 @@ __device__ inline void helper_gemm_phase(const StackArgs& a, const StackBufs& d,
         for (int j = 0; j < 4; ++j) {
           const int ml = row0 + j;
           float val = v[j];
-          const float partner = __shfl_xor(val, 16, kWave);
+          const float partner = lane_xor16(val, lane);
           const int pos = __shfl(pos_lane, ml, kWave);
           const int crow = __shfl(crow_lane, ml, kWave);
           if (which != 2) {
