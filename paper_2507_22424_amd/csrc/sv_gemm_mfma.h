@@ -221,6 +221,42 @@ __device__ inline float lane_xor16(float v, int lane) {
   const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
   return __uint_as_float((lane & 16) ? r[0] : r[1]);
 }
+// 16 per-lane partial sums (one per row) -> row totals over the 64 lanes, by halving: after the
+// exchanges over the lane distances 32, 16, 8, 4 every lane holds one row's sum over a group of
+// lanes, two more steps finish it; lane l ends with the total of row index
+// 8 * bit5(l) + 4 * bit4(l) + 2 * bit3(l) + bit2(l).  All exchanges stay in the vector ALU:
+// half and row swaps (gfx950), row rotation, half-row mirror + quad reversal, quad permutes.
+template <int CTRL>
+__device__ inline float dpp_f32(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+__device__ inline float row_sums_butterfly(const float (&ssq)[16], int lane) {
+  float v8[8], v4[4], v2[2], v1;
+  const bool h8 = lane & 8, h4 = lane & 4;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {        // lanes 0..31 keep rows i, lanes 32..63 rows i + 8
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(ssq[i]), __float_as_uint(ssq[i + 8]), false, false);
+    v8[i] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {        // rows of 16 lanes: even ones keep value i, odd ones i + 4
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v8[i]), __float_as_uint(v8[i + 4]), false, false);
+    v4[i] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const float mine = h8 ? v4[i + 2] : v4[i], other = h8 ? v4[i] : v4[i + 2];
+    v2[i] = mine + dpp_f32<0x128>(other);                               // row_ror:8 = lane ^ 8
+  }
+  {
+    const float mine = h4 ? v2[1] : v2[0], other = h4 ? v2[0] : v2[1];
+    v1 = mine + dpp_f32<0x1B>(dpp_f32<0x141>(other));                   // half-row mirror, quads reversed = lane ^ 4
+  }
+  v1 += dpp_f32<0x4E>(v1);                                              // lane ^ 2
+  v1 += dpp_f32<0xB1>(v1);                                              // lane ^ 1
+  return v1;
+}
+
 // x * sigmoid(x) with the hardware exponential and reciprocal (1 ulp each)
 __device__ inline float silu_fast(float x) {
   return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x));
@@ -360,10 +396,21 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
         const size_t pidx = ((size_t)mt * n_tiles + tile) * S;
         const auto pb = (const __attribute__((address_space(1))) u32x2_t*)(part16 + pidx * kTileVec4 + (qd >> 1) * 64 + lane) + (qd & 1);
 #pragma unroll
-        for (int s2 = 0; s2 < 8; ++s2) {
-          const int sc = min(s2, S - 1);
-          part[bi][s2] = pb[(size_t)sc * (kTileVec4 * 2)];
-          pinv[bi][s2] = s2 < S ? pscale[pidx + sc] : 0.f;
+        for (int s2 = 0; s2 < 8; ++s2) part[bi][s2] = pb[(size_t)min(s2, S - 1) * (kTileVec4 * 2)];
+        if (S == 8) {
+          // the eight scales of the tile in two loads (the load queue holds 63 requests: a batch
+          // of six items must not need more, or its loads go out in two rounds)
+          typedef float f32x4a_t __attribute__((ext_vector_type(4)));
+          const auto pv = (const __attribute__((address_space(1))) f32x4a_t*)(pscale + pidx);
+          const f32x4a_t p0 = pv[0], p1 = pv[1];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            pinv[bi][e] = p0[e];
+            pinv[bi][4 + e] = p1[e];
+          }
+        } else {
+#pragma unroll
+          for (int s2 = 0; s2 < 8; ++s2) pinv[bi][s2] = s2 < S ? pscale[pidx + min(s2, S - 1)] : 0.f;
         }
         if (EPI == EPI_RESID) {
 #pragma unroll
@@ -613,32 +660,7 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
     // Row sums of x^2 over this K slice, published once the whole slice has been staged and
     // completed (waitcnt) before the barrier that precedes any tile arrival of this workgroup.
     auto publish_ssq = [&]() {
-      // 16 row sums per lane -> totals over the 64 lanes with a halving butterfly: after the
-      // exchanges over distances 32, 16, 8, 4 each lane holds one row's sum over 16 lanes-groups,
-      // two more steps finish it; lane l ends with the total of row index (l >> 2) & 15.
-      float v8[8], v4[4], v2[2], v1;
-      const bool h32 = lane & 32, h16 = lane & 16, h8 = lane & 8, h4 = lane & 4;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const float mine = h32 ? ssq[i + 8] : ssq[i], other = h32 ? ssq[i] : ssq[i + 8];
-        v8[i] = mine + __shfl_xor(other, 32, kWave);
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float mine = h16 ? v8[i + 4] : v8[i], other = h16 ? v8[i] : v8[i + 4];
-        v4[i] = mine + __shfl_xor(other, 16, kWave);
-      }
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const float mine = h8 ? v4[i + 2] : v4[i], other = h8 ? v4[i] : v4[i + 2];
-        v2[i] = mine + __shfl_xor(other, 8, kWave);
-      }
-      {
-        const float mine = h4 ? v2[1] : v2[0], other = h4 ? v2[0] : v2[1];
-        v1 = mine + __shfl_xor(other, 4, kWave);
-      }
-      v1 += __shfl_xor(v1, 2, kWave);
-      v1 += __shfl_xor(v1, 1, kWave);
+      const float v1 = row_sums_butterfly(ssq, lane);
       // row index held by this lane: bit 3 from lane bit 5, bit 2 from bit 4, bit 1 from bit 3,
       // bit 0 from bit 2
       const int r = ((lane >> 5) & 1) * 8 + ((lane >> 4) & 1) * 4 + ((lane >> 3) & 1) * 2 + ((lane >> 2) & 1);

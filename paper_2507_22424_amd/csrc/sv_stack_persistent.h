@@ -420,29 +420,7 @@ __device__ inline void helper_gemm_phase(const StackArgs& a, const StackBufs& d,
   // lane l ends with the total of row index (l >> 2) & 15 of this wave's rows).
   float* my_ssq = d.sumsq + ((size_t)xcd * kUnitsPerXcd + u) * kMTile;
   auto publish_ssq = [&]() {
-    float v8[8], v4[4], v2[2], v1;
-    const bool h32 = lane & 32, h16 = lane & 16, h8 = lane & 8, h4 = lane & 4;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const float mine = h32 ? ssq[i + 8] : ssq[i], other = h32 ? ssq[i] : ssq[i + 8];
-      v8[i] = mine + __shfl_xor(other, 32, kWave);
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float mine = h16 ? v8[i + 4] : v8[i], other = h16 ? v8[i] : v8[i + 4];
-      v4[i] = mine + __shfl_xor(other, 16, kWave);
-    }
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const float mine = h8 ? v4[i + 2] : v4[i], other = h8 ? v4[i] : v4[i + 2];
-      v2[i] = mine + __shfl_xor(other, 8, kWave);
-    }
-    {
-      const float mine = h4 ? v2[1] : v2[0], other = h4 ? v2[0] : v2[1];
-      v1 = mine + __shfl_xor(other, 4, kWave);
-    }
-    v1 += __shfl_xor(v1, 2, kWave);
-    v1 += __shfl_xor(v1, 1, kWave);
+    const float v1 = row_sums_butterfly(ssq, lane);
     const int r = ((lane >> 5) & 1) * 8 + ((lane >> 4) & 1) * 4 + ((lane >> 3) & 1) * 2 + ((lane >> 2) & 1);
     if ((lane & 3) == 0) my_ssq[hw + 4 * r] = v1;
     __builtin_amdgcn_s_waitcnt(0);     // in L2 before the barrier behind which flush_tile reads all rows
