@@ -139,15 +139,16 @@ __device__ inline void tree_attention_body(
     // writes elements 0..3, the odd group elements 4..7, as (even key | odd key << 16).
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
+      // the gfx950 row swap of a value with itself returns what the even lane groups hold and
+      // what the odd ones hold - the two rows, in both lanes of the pair, without a trip through LDS
       const uint4 mine = vreg[i];
-      uint4 other;
-      other.x = __shfl_xor(mine.x, 16, kWave);
-      other.y = __shfl_xor(mine.y, 16, kWave);
-      other.z = __shfl_xor(mine.z, 16, kWave);
-      other.w = __shfl_xor(mine.w, 16, kWave);
+      const auto sx = __builtin_amdgcn_permlane16_swap(mine.x, mine.x, false, false);
+      const auto sy = __builtin_amdgcn_permlane16_swap(mine.y, mine.y, false, false);
+      const auto sz = __builtin_amdgcn_permlane16_swap(mine.z, mine.z, false, false);
+      const auto sw = __builtin_amdgcn_permlane16_swap(mine.w, mine.w, false, false);
       const bool odd = g & 1;
-      const uint4 ev = odd ? other : mine;   // row of key 4i + (g & ~1)
-      const uint4 od = odd ? mine : other;   // row of key 4i + (g | 1)
+      const uint4 ev = make_uint4(sx[0], sy[0], sz[0], sw[0]);   // row of key 4i + (g & ~1)
+      const uint4 od = make_uint4(sx[1], sy[1], sz[1], sw[1]);   // row of key 4i + (g | 1)
       // the two 32-bit words (= 4 elements) this lane transposes
       const unsigned e_w0 = odd ? ev.z : ev.x, e_w1 = odd ? ev.w : ev.y;
       const unsigned o_w0 = odd ? od.z : od.x, o_w1 = odd ? od.w : od.y;
@@ -165,15 +166,23 @@ __device__ inline void tree_attention_body(
     // ---- mask + online softmax (per lane: query column c) ----
     float p[8];
     float tile_max = kNegBig;
+    if (key0 + kAttKeys <= P) {              // a tile of prefix keys only: every key is visible
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int kidx = key0 + 16 * (e >> 2) + 4 * g + (e & 3);
-      const int tn_ = kidx - P;              // tree node of this key, if >= 0
-      bool vis = kidx < P;
-      if (tn_ >= 0 && tn_ < T) vis = ((tn_ < 64 ? mask0 >> tn_ : mask1 >> (tn_ - 64)) & 1ull) != 0;
-      const float sv_ = e < 4 ? s0[e & 3] : s1[e & 3];
-      p[e] = vis ? sv_ : kNegBig;
-      tile_max = fmaxf(tile_max, p[e]);
+      for (int e = 0; e < 8; ++e) {
+        p[e] = e < 4 ? s0[e & 3] : s1[e & 3];
+        tile_max = fmaxf(tile_max, p[e]);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int kidx = key0 + 16 * (e >> 2) + 4 * g + (e & 3);
+        const int tn_ = kidx - P;
+        bool vis = kidx < P;
+        if (tn_ >= 0 && tn_ < T) vis = ((tn_ < 64 ? mask0 >> tn_ : mask1 >> (tn_ - 64)) & 1ull) != 0;
+        const float sv_ = e < 4 ? s0[e & 3] : s1[e & 3];
+        p[e] = vis ? sv_ : kNegBig;
+        tile_max = fmaxf(tile_max, p[e]);
+      }
     }
     tile_max = fmaxf(tile_max, __shfl_xor(tile_max, 16, kWave));
     tile_max = fmaxf(tile_max, __shfl_xor(tile_max, 32, kWave));
