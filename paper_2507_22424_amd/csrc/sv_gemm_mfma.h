@@ -624,13 +624,15 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
         xb[r] = *reinterpret_cast<const float4*>(p + 4);
       }
     };
+    // `before_row(r)` runs ahead of row r's conversion (the first chunk slips the ring's loads in)
     auto x_convert = [&](int c, const float4 (&xa)[16], const float4 (&xb)[16], const float4& g0,
-                         const float4& g1) {
+                         const float4& g1, auto before_row) {
       const int nkc = min(4, np - 4 * c) * 16;
       const bool on = lane < nkc;
       const int s = lane >> 1;                     // k-step inside the chunk
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
+        before_row(r);
         // (rows beyond M repeat row M - 1: they cost nothing extra and are never written out)
         const int ml = wave + 4 * r;
         float v[8] = {xa[r].x, xa[r].y, xa[r].z, xa[r].w, xb[r].x, xb[r].y, xb[r].z, xb[r].w};
@@ -671,13 +673,20 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
       }
     };
     {
-      // chunk 0; the ring is filled right behind the X loads (loads return in issue order, so X
-      // is not held up by the slower weight loads, and both overlap the conversion)
+      // Chunk 0.  Only the ring's first piece is requested right behind the X loads, the others
+      // while the rows are converted: a thousand waves asking for their whole ring at once put
+      // 32 MB of weight requests in front of each other's X rows, and the X round trip - which
+      // nothing can overlap - grows with the queue.  Spread over the conversion the same loads
+      // still arrive before the main loop wants them (measured: 3.5 us per layer).
       float4 xa[16], xb[16], g0, g1;
       x_load(0, xa, xb, g0, g1);
-#pragma unroll
-      for (int sl = 0; sl < kRing; ++sl) issue(ring[sl]);
-      x_convert(0, xa, xb, g0, g1);
+      issue(ring[0]);
+      x_convert(0, xa, xb, g0, g1, [&](int r) {
+        static_assert(kRing == 4, "one slot every fourth row");
+        if (r == 4) issue(ring[1]);
+        if (r == 8) issue(ring[2]);
+        if (r == 12) issue(ring[3]);
+      });
     }
     if (PRO == PRO_GAIN && n_chunks == 1) publish_ssq();
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // X chunk 0 is in LDS; weight loads stay in flight
@@ -848,7 +857,7 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
         for (int sl = 0; sl < kRing; ++sl) step(ring[sl]);
         if (c + 1 < n_chunks) {
           asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // chunk c has been read by all
-          x_convert(cn, xa, xb, g0, g1);
+          x_convert(cn, xa, xb, g0, g1, [](int) {});
           if (PRO == PRO_GAIN && cn == n_chunks - 1) publish_ssq();
           asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
         }
