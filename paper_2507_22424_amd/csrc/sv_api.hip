@@ -83,7 +83,7 @@ static WorkspaceLayout workspace_layout(const sv_model_cfg& c, int m_rows, int n
   if (c.dtype == SV_BF16) {
     // sized for the worst split (8 slices), independent of the device
     const size_t tiles_max = n_max / kFragRows, s_max = 8;
-    L.counter_bytes = align_up((mt * (tiles_max + kXcds) * 2 + 64) * sizeof(int), kAlign);   // group counters + status word
+    L.counter_bytes = align_up((mt * (tiles_max + kXcds) * kCntStride + 64) * sizeof(int), kAlign);   // group counters + status word
     L.counters = o; o += L.counter_bytes;
     L.sumsq = o;    o = align_up(o + mt * (tiles_max + kXcds) * s_max * kMTile * 4, kAlign);
     L.part_bytes = align_up(mt * tiles_max * s_max * kTileFloats * 4, 2 * kAlign);

@@ -59,6 +59,7 @@ constexpr int kRing = 4;         // ring slots: 32 KiB of weights in flight per 
 constexpr int kTileFloats = kMTile * kFragRows;   // one partial tile, [64][32] values
 constexpr int kTileVec4 = kTileFloats / 8;        // .. as stored: scaled int16 pairs, [4][64 lanes] uint4 = 4 KiB
 constexpr int kXcds = 8;
+constexpr int kCntStride = 32;     // 32-bit words per group's counters: a 128-byte line of its own
 constexpr int kRedBatch = 6;       // reduction work items whose loads are in flight together
 
 enum { PRO_PLAIN = 0, PRO_GAIN = 1 };
@@ -107,7 +108,7 @@ struct GemmArgs {
   uint4* part16;         // [m_tiles][N/32][S] partial tiles, kTileVec4 uint4 each (scaled int16)
   float* pscale;         // [m_tiles][N/32][S] inverse scale of each partial tile
   float* sumsq;          // [m_tiles][n_xcd*gpx][S][64] row sums of x^2 over each K slice (RMSNorm, row scales of the partial tiles)
-  unsigned* group_cnt;   // [m_tiles][groups][2] arrival (4 bits per XCD) / departure counters, zero between launches
+  unsigned* group_cnt;   // [m_tiles][groups][kCntStride]: arrival (4 bits per XCD) and departure counters in the first two words, zero between launches
   int* status;           // sticky: != 0 once slices of one tile were seen on different XCDs
   float eps;
   float* x_io;           // EPI_RESID: x_io [M, N] += Y
@@ -323,7 +324,8 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
   // and the wait below is short; it is bounded all the same (status bit 2 on give-up).
   __builtin_amdgcn_s_waitcnt(0);           // this wave's partial tiles are in L2
   __syncthreads();
-  const auto gcnt = SV_GLOBAL(unsigned, a.group_cnt) + ((size_t)mt * G + g) * 2;
+  // (one line per group: arrivals and polls of different groups do not queue behind each other)
+  const auto gcnt = SV_GLOBAL(unsigned, a.group_cnt) + ((size_t)mt * G + g) * kCntStride;
 #undef SV_GLOBAL
   if (EPI == EPI_QKV && tid >= 64 && tid < 64 + kMTile) {
     // rotary position and cache row of each row of the m tile, by the second wave while the
@@ -347,6 +349,7 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
 #pragma unroll
       for (int x = 0; x < kXcds; ++x) n += (v >> (4 * x)) & 15u;
       if (n >= (unsigned)S) break;
+      __builtin_amdgcn_s_sleep(8);           // ~0.25 us: polls are device-scope round trips, keep them few
       v = __hip_atomic_load(gcnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // not from L1
     }
     int bad = 0;
