@@ -91,10 +91,10 @@ static WorkspaceLayout workspace_layout(const sv_model_cfg& c, int m_rows, int n
     L.xhat = o;
     L.stack_ctl = L.stack_ctl_bytes = L.stack_sumsq = L.stack_part = L.stack_part_bytes = 0;
     if (mt == 1) {
-      // group words [32 layers][4 phases][256 groups] x 8 B, then grid (8 x 64), workgroup
-      // counters (256) and flags (256 x 16) as 32-bit words, then the launch description
-      L.stack_ctl_bytes = align_up((size_t)kStackMaxLayers * 4 * 256 * 8 + (8 * 64 + 256 + 256 * 16) * 4 +
-                                   sizeof(StackArgs), kAlign);
+      // group words [32 layers][4 phases][256 groups] x 128 B, then grid (8 x 64), workgroup
+      // counters (256 x 32) and flags (256 x 32) as 32-bit words, then the launch description
+      L.stack_ctl_bytes = align_up((size_t)kStackMaxLayers * 4 * 256 * 8 * kStackCntStride +
+                                   (8 * 64 + 256 * 32 + 256 * 32) * 4 + sizeof(StackArgs), kAlign);
       L.stack_ctl = o;   o += L.stack_ctl_bytes;
       L.stack_sumsq = o; o = align_up(o + (size_t)kXcds * kUnitsPerXcd * kMTile * 4, kAlign);
       L.stack_part_bytes = (tiles_max + kXcds * kUnitsPerXcd) * s_max * kTileFloats * 4;
@@ -324,11 +324,11 @@ static bool stack_plan(const sv_model_cfg& c, int n_layers, const void* const* p
   char* ctl = ws + wl.stack_ctl;
   d->group_cnt = (unsigned long long*)ctl;
   a->gmax = 256;
-  unsigned* words = (unsigned*)(ctl + (size_t)kStackMaxLayers * 4 * 256 * 8);
+  unsigned* words = (unsigned*)(ctl + (size_t)kStackMaxLayers * 4 * 256 * 8 * kStackCntStride);
   d->grid_cnt = words;
   d->wg_cnt = words + 8 * 64;
-  d->wg_flag = words + 8 * 64 + 256;
-  *a_dev = (StackArgs*)(words + 8 * 64 + 256 + 256 * 16);
+  d->wg_flag = words + 8 * 64 + 256 * 32;
+  *a_dev = (StackArgs*)(words + 8 * 64 + 256 * 32 + 256 * 32);
   d->status = (int*)(ws + wl.counters + wl.counter_bytes) - 1;
   d->depth = tree.depth;
   d->prefix_len = kv[0].prefix_len;

@@ -37,6 +37,7 @@
 
 namespace sv {
 
+constexpr int kStackCntStride = 16;  // 64-bit words between the arrival words of two groups (128 bytes)
 constexpr int kStackMaxLayers = 32;   // layers per launch (pointer table in the kernel arguments)
 constexpr int kRingSlots = 4;         // weight pieces in flight per stream wave
 constexpr int kRingFrags = 8;         // fragments per piece: 128 k-values, 8 KiB per wave
@@ -79,10 +80,10 @@ struct StackBufs {
   uint4* part16;                           // [n_xcd][part_xcd_tiles] partial tiles (kTileVec4 uint4 each)
   float* pscale;                           // [n_xcd][part_xcd_tiles] their inverse scales
   float* sumsq;                            // [n_xcd][32][64] row sums of x^2 per unit
-  unsigned long long* group_cnt;           // [n_layers * 4][gmax] arrival words, zero at launch
+  unsigned long long* group_cnt;           // [n_layers * 4][gmax] arrival words, kStackCntStride apart, zero at launch
   unsigned* grid_cnt;                      // [n_xcd] words 64 apart, zero at launch
-  unsigned* wg_cnt;                        // [grid] zero at launch
-  unsigned* wg_flag;                       // [grid] words 16 apart, zero at launch
+  unsigned* wg_cnt;                        // [grid] words 32 apart (a line each), zero at launch
+  unsigned* wg_flag;                       // [grid] words 32 apart, zero at launch
   int* status;
   const int32_t* depth;
   const int32_t* prefix_len;
@@ -330,6 +331,7 @@ __device__ inline void grid_sync(SyncCtx& s, int hw, int lane) {
                                                               __HIP_MEMORY_SCOPE_AGENT)
                                           : target;
         ok = __all(v >= target);
+        if (!ok) __builtin_amdgcn_s_sleep(8);   // device-scope polls are round trips to the memory side: keep them few
       }
       if (lane == 0) {
         if (!ok) atomicOr(s.status, 4);
@@ -509,7 +511,8 @@ __device__ inline void helper_gemm_phase(const StackArgs& a, const StackBufs& d,
 
   // ---- group barrier: all 4*S helper waves of the group's slices have written their tiles ----
   __builtin_amdgcn_s_waitcnt(0);
-  unsigned long long* gcnt = d.group_cnt + (size_t)(layer * 4 + ph) * a.gmax + gm.g;
+  // (a 128-byte line per group: arrivals and polls of different groups must not share one)
+  unsigned long long* gcnt = d.group_cnt + ((size_t)(layer * 4 + ph) * a.gmax + gm.g) * kStackCntStride;
   {
     const unsigned field = 8u * (unsigned)xcd_actual(a.n_xcd);
     if (lane == 0)
@@ -523,6 +526,7 @@ __device__ inline void helper_gemm_phase(const StackArgs& a, const StackBufs& d,
 #pragma unroll
         for (int x = 0; x < kXcds; ++x) n += (unsigned)(v >> (8 * x)) & 255u;
         if (n >= 4u * (unsigned)S) break;
+        __builtin_amdgcn_s_sleep(8);
       }
       int bad = 0;
       if (n < 4u * (unsigned)S) bad |= 2;
@@ -718,8 +722,8 @@ __global__ __launch_bounds__(512) void verify_stack_persistent(const StackArgs* 
 
   const int hw = wave - 4, htid = tid - 256;
   SyncCtx sc;
-  sc.wg_cnt = d.wg_cnt + blockIdx.x;
-  sc.wg_flag = d.wg_flag + 16 * blockIdx.x;
+  sc.wg_cnt = d.wg_cnt + 32 * blockIdx.x;
+  sc.wg_flag = d.wg_flag + 32 * blockIdx.x;
   sc.grid_cnt = d.grid_cnt;
   sc.status = d.status;
   sc.n_xcd = a.n_xcd;
