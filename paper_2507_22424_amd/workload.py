@@ -130,6 +130,27 @@ def layer_weights(cfg: VerifyConfig, layer: int) -> Dict[str, torch.Tensor]:
     return out
 
 
+def layer_weights_w8(cfg: VerifyConfig, layer: int) -> Dict[str, torch.Tensor]:
+    """Decoder layer `layer` with 8-bit matrices: gains as in layer_weights; every matrix `w*` as
+    uint8 E4M3 codes [out, in] (a standard normal draw converted by torch's float8_e4m3fn type)
+    plus `w*_scale`, float32 [out], about 0.02 with a spread of a few tens of percent per row - so
+    the dequantised matrix looks like the bf16 one."""
+    H, F, D = cfg.hidden, cfg.mlp_dim, cfg.n_heads * cfg.head_dim
+    shapes = {"g1": (H,), "wq": (D, H), "wk": (D, H), "wv": (D, H), "wo": (H, D),
+              "g2": (H,), "wg": (F, H), "wu": (F, H), "wd": (H, F)}
+    seed = seed_for(cfg, 0, layer) + 7777
+    out = {}
+    for i, name in enumerate(LAYER_TENSORS):
+        if name.startswith("g"):
+            out[name] = _normal(shapes[name], seed, i, torch.bfloat16, 0.02, 1.0)
+        else:
+            z = _normal(shapes[name], seed, i, torch.float32, 1.0)
+            out[name] = z.to(torch.float8_e4m3fn).view(torch.uint8)
+            u = torch.rand(shapes[name][0], generator=_gen(seed, 100 + i), dtype=torch.float32)
+            out[name + "_scale"] = 0.02 * (0.75 + 0.5 * u)
+    return out
+
+
 def all_layer_weights(cfg: VerifyConfig, workers: int = 8) -> List[Dict[str, torch.Tensor]]:
     """All layers; the draws are independent per layer so they run in threads."""
     with ThreadPoolExecutor(max_workers=max(1, workers)) as ex:
