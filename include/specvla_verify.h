@@ -42,18 +42,24 @@ extern "C" {
 #define SV_ERR_TREE (-3)      /* parent array is not a tree in the stated form, or too deep */
 #define SV_ERR_TOKEN (-4)     /* action range / threshold arguments are inconsistent */
 #define SV_ERR_WORKSPACE (-5) /* workspace or packed buffer too small or misaligned */
-#define SV_ERR_DTYPE (-6)     /* cfg->dtype is neither SV_F32 nor SV_BF16 */
+#define SV_ERR_DTYPE (-6)     /* cfg->dtype is none of SV_F32, SV_BF16, SV_BF16_W8 (or the wrong one for the call) */
 #define SV_ERR_LAUNCH (-7)    /* the HIP runtime reported an error at launch */
 
 #define SV_F32 0
 #define SV_BF16 1
+/* A bf16 model (gains, KV cache, LM head and activations as with SV_BF16) whose seven matrices
+ * per layer are stored in 8 bits - E4M3 codes of the OCP 8-bit floating point specification -
+ * with one float32 scale per output row: W[n][k] = value(code[n][k]) * scale[n].  The paper's
+ * App. C runs the verifier on weights held in fewer bits; on a path bound by the bytes of the
+ * weights this halves them.  Packed with sv_pack_layer_w8; every other call is the same. */
+#define SV_BF16_W8 2
 
 #define SV_MAX_TREE_NODES 128 /* T <= 128: the ancestor mask has at most two 64-bit words */
 #define SV_MAX_DEPTH 31       /* depth of a node, in edges */
 
 /* Shape of the verifier (Sec. 4.1, 5.1: OpenVLA = Llama-2 backbone). */
 typedef struct sv_model_cfg {
-  int32_t dtype;      /* SV_F32 or SV_BF16: storage type of weights and KV cache */
+  int32_t dtype;      /* SV_F32, SV_BF16 or SV_BF16_W8: storage type of weights and KV cache */
   int32_t hidden;     /* H */
   int32_t n_heads;    /* nh (multi-head attention, n_kv_heads = n_heads) */
   int32_t head_dim;   /* d; nh * d is the attention width (need not equal H) */
@@ -120,6 +126,20 @@ int sv_packed_layer_bytes(const sv_model_cfg *cfg, size_t *bytes);
  * and d <= 128. */
 int sv_pack_layer(const sv_model_cfg *cfg, const sv_layer_weights *raw, void *packed,
                   size_t packed_bytes, void *stream);
+
+/* The row scales of a layer's matrices for SV_BF16_W8: [device] float32, sq, sk, sv: [nh*d];
+ * so, sd: [H]; sg, su: [F]. */
+typedef struct sv_layer_scales {
+  const float *sq, *sk, *sv, *so, *sg, *su, *sd;
+} sv_layer_scales;
+
+/* sv_pack_layer for cfg->dtype = SV_BF16_W8 (App. C: weights in fewer bits): raw->g1, g2 are
+ * bf16 gains, raw->wq .. wd uint8 E4M3 codes in the shapes of sv_layer_weights, scales their
+ * row scales.  Same size rules as SV_BF16; packed_bytes >= sv_packed_layer_bytes(cfg).
+ * SV_ERR_DTYPE for any other dtype (and sv_pack_layer returns it for SV_BF16_W8). */
+int sv_pack_layer_w8(const sv_model_cfg *cfg, const sv_layer_weights *raw,
+                     const sv_layer_scales *scales, void *packed, size_t packed_bytes,
+                     void *stream);
 
 /* Host-only.  Bytes of device scratch that sv_verify_layer / sv_action_head_argmax need for
  * B episodes of T nodes and up to n_scored scored vocabulary rows -> *bytes. */

@@ -19,12 +19,12 @@ namespace sv {
 
 static int check_cfg(const sv_model_cfg* c) {
   if (!c) return SV_ERR_NULL;
-  if (c->dtype != SV_F32 && c->dtype != SV_BF16) return SV_ERR_DTYPE;
+  if (c->dtype != SV_F32 && c->dtype != SV_BF16 && c->dtype != SV_BF16_W8) return SV_ERR_DTYPE;
   if (c->hidden < 1 || c->n_heads < 1 || c->head_dim < 2 || c->mlp_dim < 1 || c->vocab < 1)
     return SV_ERR_SHAPE;
   if ((c->head_dim & 1) || c->head_dim > 128) return SV_ERR_SHAPE;
   if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return SV_ERR_SHAPE;
-  if (c->dtype == SV_BF16) {
+  if (c->dtype != SV_F32) {
     if (c->hidden % 256 || c->head_dim != 128 || c->n_heads % 2 || c->mlp_dim % 256)
       return SV_ERR_SHAPE;
   }
@@ -80,7 +80,7 @@ static WorkspaceLayout workspace_layout(const sv_model_cfg& c, int m_rows, int n
   if (2 * F > n_max) n_max = 2 * F;
   if (H > n_max) n_max = H;
   size_t o = 0;
-  if (c.dtype == SV_BF16) {
+  if (c.dtype != SV_F32) {
     // sized for the worst split (8 slices), independent of the device
     const size_t tiles_max = n_max / kFragRows, s_max = 8;
     L.counter_bytes = align_up((mt * (tiles_max + kXcds) * kCntStride + 64) * sizeof(int), kAlign);   // group counters + status word
@@ -225,13 +225,20 @@ static int verify_layer_bf16(const sv_model_cfg& c, const char* packed, float* x
     multi = p.multi;
   };
   // the kernel form for the shape just planned: single- or multi-chunk K slices
-#define SV_LAUNCH_GEMM(PRO, EPI)                                        \
-  do {                                                                  \
-    if (multi) gemm_stream_bf16<PRO, EPI, true><<<grid, 256, 0, st>>>(a); \
-    else gemm_stream_bf16<PRO, EPI, false><<<grid, 256, 0, st>>>(a);      \
+#define SV_LAUNCH_GEMM(PRO, EPI)                                                     \
+  do {                                                                               \
+    if (w8) {                                                                        \
+      if (multi) gemm_stream_bf16<PRO, EPI, true, true><<<grid, 256, 0, st>>>(a);    \
+      else gemm_stream_bf16<PRO, EPI, false, true><<<grid, 256, 0, st>>>(a);         \
+    } else {                                                                         \
+      if (multi) gemm_stream_bf16<PRO, EPI, true, false><<<grid, 256, 0, st>>>(a);   \
+      else gemm_stream_bf16<PRO, EPI, false, false><<<grid, 256, 0, st>>>(a);        \
+    }                                                                                \
   } while (0)
 
+  const bool w8 = c.dtype == SV_BF16_W8;
   a.X = x; a.gain = (const float*)(packed + pl.g1); a.Wp = (const uint4*)(packed + pl.wqkv);
+  a.wscale = w8 ? (const float*)(packed + pl.sqkv) : nullptr;
   shape(3 * D, H);
   a.q_out = q; a.kc = (bf16_t*)kv.k; a.vc = (bf16_t*)kv.v; a.depth = tree.depth;
   a.prefix_len = kv.prefix_len; a.p_max = kv.prefix_len_max; a.cap = kv.capacity; a.T = T_;
@@ -245,17 +252,20 @@ static int verify_layer_bf16(const sv_model_cfg& c, const char* packed, float* x
       tree.anc_mask, tree.n_words, T_, c.n_heads, kv.capacity, attn);
   mark(3);
   a.X = attn; a.gain = nullptr; a.Wp = (const uint4*)(packed + pl.wo);
+  a.wscale = w8 ? (const float*)(packed + pl.so) : nullptr;
   shape(H, D);
   a.x_io = x;
   SV_LAUNCH_GEMM(PRO_PLAIN, EPI_RESID);
   mark(4);
   a.X = x; a.gain = (const float*)(packed + pl.g2); a.Wp = (const uint4*)(packed + pl.wgu);
+  a.wscale = w8 ? (const float*)(packed + pl.sgu) : nullptr;
   shape(2 * F, H);
   a.act = act;
   mark(5);
   SV_LAUNCH_GEMM(PRO_GAIN, EPI_SWIGLU);
   mark(6);
   a.X = act; a.gain = nullptr; a.Wp = (const uint4*)(packed + pl.wd);
+  a.wscale = w8 ? (const float*)(packed + pl.sd) : nullptr;
   shape(H, F);
   a.x_io = x;
   mark(7);
@@ -273,7 +283,7 @@ static bool stack_plan(const sv_model_cfg& c, int n_layers, const void* const* p
                        const sv_kv_view* kv, const sv_tree& tree, int B, float* x, char* ws,
                        StackArgs* a, StackBufs* d, StackArgs** a_dev) {
   const int T_ = tree.n_nodes, M = B * T_;
-  if (c.dtype != SV_BF16 || M > kMTile || n_layers < 1 || n_layers > kStackMaxLayers) return false;
+  if (c.dtype != SV_BF16 || M > kMTile || n_layers < 1 || n_layers > kStackMaxLayers) return false;   // (8-bit weights: per-layer launches only)
   int dev = 0, cus = 0;
   if (hipGetDevice(&dev) != hipSuccess ||
       hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
@@ -467,8 +477,48 @@ int sv_pack_layer(const sv_model_cfg* cfg, const sv_layer_weights* raw, void* pa
     return SV_ERR_NULL;
   if (packed_bytes < packed_layout(*cfg).total || ((uintptr_t)packed % kAlign))
     return SV_ERR_WORKSPACE;
+  if (cfg->dtype == SV_BF16_W8) return SV_ERR_DTYPE;      // sv_pack_layer_w8 takes the scales
   if (cfg->dtype == SV_F32) return pack_layer_t<float>(*cfg, *raw, (char*)packed, (hipStream_t)stream);
   return pack_layer_t<bf16_t>(*cfg, *raw, (char*)packed, (hipStream_t)stream);
+}
+
+int sv_pack_layer_w8(const sv_model_cfg* cfg, const sv_layer_weights* raw,
+                     const sv_layer_scales* sc, void* packed_v, size_t packed_bytes,
+                     void* stream) {
+  const int rc = check_cfg(cfg);
+  if (rc != SV_OK) return rc;
+  if (cfg->dtype != SV_BF16_W8) return SV_ERR_DTYPE;
+  if (!raw || !sc || !packed_v || !raw->g1 || !raw->wq || !raw->wk || !raw->wv || !raw->wo ||
+      !raw->g2 || !raw->wg || !raw->wu || !raw->wd || !sc->sq || !sc->sk || !sc->sv || !sc->so ||
+      !sc->sg || !sc->su || !sc->sd)
+    return SV_ERR_NULL;
+  const sv_model_cfg& c = *cfg;
+  const PackedLayout pl = packed_layout(c);
+  if (packed_bytes < pl.total || ((uintptr_t)packed_v % kAlign)) return SV_ERR_WORKSPACE;
+  char* packed = (char*)packed_v;
+  hipStream_t st = (hipStream_t)stream;
+  const int H = c.hidden, D = c.n_heads * c.head_dim, F = c.mlp_dim;
+  pack_gain<bf16_t><<<ceil_div(H, 256), 256, 0, st>>>((const bf16_t*)raw->g1, (float*)(packed + pl.g1), H);
+  pack_gain<bf16_t><<<ceil_div(H, 256), 256, 0, st>>>((const bf16_t*)raw->g2, (float*)(packed + pl.g2), H);
+  struct Piece {
+    const void* src; const float* scale; size_t dst, sdst; int rows, k, mode, off;
+  };
+  const Piece pieces[] = {
+      {raw->wq, sc->sq, pl.wqkv, pl.sqkv, D, H, PACK_PAIR16_HEAD, 0},
+      {raw->wk, sc->sk, pl.wqkv, pl.sqkv, D, H, PACK_PAIR16_HEAD, D},
+      {raw->wv, sc->sv, pl.wqkv, pl.sqkv, D, H, PACK_PAIR16_HEAD, 2 * D},
+      {raw->wo, sc->so, pl.wo, pl.so, H, D, PACK_PLAIN, 0},
+      {raw->wg, sc->sg, pl.wgu, pl.sgu, F, H, PACK_PAIR16_GU, 0},
+      {raw->wu, sc->su, pl.wgu, pl.sgu, F, H, PACK_PAIR16_GU, 16},
+      {raw->wd, sc->sd, pl.wd, pl.sd, H, F, PACK_PLAIN, 0}};
+  for (const Piece& p : pieces) {
+    const size_t n8 = (size_t)p.rows * (p.k / 8);
+    pack_rows_mfma_w8<<<(unsigned)((n8 + 255) / 256), 256, 0, st>>>(
+        (const uint2*)p.src, (uint2*)(packed + p.dst), p.rows, p.k, p.mode, p.off);
+    pack_row_scales<<<ceil_div(p.rows, 256), 256, 0, st>>>(p.scale, (float*)(packed + p.sdst), p.rows,
+                                                           p.mode, p.off);
+  }
+  return launch_status();
 }
 
 int sv_workspace_bytes(const sv_model_cfg* cfg, int B, int T, int n_scored, size_t* bytes) {

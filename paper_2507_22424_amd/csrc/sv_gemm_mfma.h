@@ -92,10 +92,39 @@ __global__ void pack_rows_mfma(const uint4* __restrict__ src, uint4* __restrict_
   dst[frag * 64 + (n % kFragRows) + 32 * (kc & 1)] = src[i];
 }
 
+// 8-bit weights (E4M3 codes, one float32 scale per row): the same tiles and row permutations,
+// but one 16-byte load of a lane now carries two k-steps - the lane's 8 codes of k-step 2j, then
+// its 8 codes of k-step 2j + 1 - so a tile is (K / 32) x 64 uint4 and a piece of 128 k-values is
+// four loads.  One thread moves 8 codes: piece (n, kc8) of a source row lands in the uint2 at
+// (((n/32) * (K/32) + kc8/4) * 64 + n%32 + 32 * (kc8%2)) * 2 + (kc8/2)%2.
+__device__ inline int packed_row(int n_src, int mode, int off) {
+  if (mode == PACK_PAIR16_HEAD) {
+    const int d = n_src % 128;
+    return off + (n_src - d) + 32 * ((d % 64) / 16) + 16 * (d / 64) + d % 16;
+  }
+  if (mode == PACK_PAIR16_GU) return 32 * (n_src / 16) + off + n_src % 16;
+  return off + n_src;
+}
+__global__ void pack_rows_mfma_w8(const uint2* __restrict__ src, uint2* __restrict__ dst, int rows,
+                                  int K, int mode, int off) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int per_row = K / 8;
+  if (i >= (size_t)rows * per_row) return;
+  const int n = packed_row((int)(i / per_row), mode, off), kc8 = (int)(i % per_row);
+  const size_t load = (size_t)(n / kFragRows) * (K / 32) + (kc8 >> 2);
+  dst[(load * 64 + (n % kFragRows) + 32 * (kc8 & 1)) * 2 + ((kc8 >> 1) & 1)] = src[i];
+}
+__global__ void pack_row_scales(const float* __restrict__ src, float* __restrict__ dst, int rows,
+                                int mode, int off) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < rows) dst[packed_row(i, mode, off)] = src[i];
+}
+
 struct GemmArgs {
   const float* X;        // [M, K] float32 activations
   const float* gain;     // [K] RMSNorm gain (PRO_GAIN) or unused
-  const uint4* Wp;       // packed weights, N rows
+  const uint4* Wp;       // packed weights, N rows (bf16 fragments, or E4M3 codes: see pack_rows_mfma_w8)
+  const float* wscale;   // 8-bit weights: [N] scale of each packed row; unused otherwise
   int M, N, K;
   int S;                 // K slices: 1 or even, at most 8
   int gpx;               // tile groups per XCD (units per XCD = gpx * S)
@@ -263,6 +292,26 @@ __device__ inline float silu_fast(float x) {
   return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x));
 }
 
+// One 16-byte load of E4M3 codes -> the two bf16 operand fragments it carries (exact: every
+// E4M3 value is a bf16 value).  Hardware conversion to float32 pairs, then the pack-convert.
+typedef float f32x2v_t __attribute__((ext_vector_type(2)));
+__device__ inline void w8_to_frags(const u32x4_t raw, bf16x8_t& f0, bf16x8_t& f1) {
+  u32x4_t a, b;
+#pragma unroll
+  for (int d = 0; d < 2; ++d) {
+    const f32x2v_t lo0 = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw[d], false);
+    const f32x2v_t hi0 = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw[d], true);
+    a[2 * d] = pack_bf16x2(lo0[0], lo0[1]);
+    a[2 * d + 1] = pack_bf16x2(hi0[0], hi0[1]);
+    const f32x2v_t lo1 = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw[2 + d], false);
+    const f32x2v_t hi1 = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw[2 + d], true);
+    b[2 * d] = pack_bf16x2(lo1[0], lo1[1]);
+    b[2 * d + 1] = pack_bf16x2(hi1[0], hi1[1]);
+  }
+  f0 = __builtin_bit_cast(bf16x8_t, a);
+  f1 = __builtin_bit_cast(bf16x8_t, b);
+}
+
 // XCD (accelerator complex die) this wave runs on: bits 3:0 of the XCC_ID hardware register.
 __device__ inline int xcd_actual(int n_xcd) {
   return (int)(__builtin_amdgcn_s_getreg((4 - 1) << 11 | 0 << 6 | 20) & 0xf) % n_xcd;
@@ -280,7 +329,7 @@ __device__ inline int frag_slot(int l, int s) { return ((l & 31) ^ (((s & 7) << 
 // loop, where spilled scalars cost stalls between the matrix instructions.
 typedef const __attribute__((address_space(4))) GemmArgs* gemm_args_ptr_t;
 typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
-template <int PRO, int EPI>
+template <int PRO, int EPI, bool W8>
 __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos, int* s_crow,
                                                   int tid, int lane, int wave) {
   GemmArgs a;                                // one batch of scalar loads; registers from here on
@@ -297,6 +346,7 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
   const auto part16 = SV_GLOBAL(const uint4, a.part16);
   const auto pscale = SV_GLOBAL(const float, a.pscale);
   const auto sumsq = SV_GLOBAL(const float, a.sumsq);
+  const auto wscale = SV_GLOBAL(const float, a.wscale);
   const auto status = SV_GLOBAL(int, a.status);
   const auto x_io = SV_GLOBAL(float, a.x_io);
   const auto act = SV_GLOBAL(float, a.act);
@@ -390,6 +440,7 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
       u32x2_t part[kRedBatch][8];
       float pinv[kRedBatch][8];
       float xres[kRedBatch][4];
+      float wsc[kRedBatch];                                           // 8-bit weights: scale of this lane's weight row
 #pragma unroll
       for (int bi = 0; bi < kRedBatch; ++bi) {                        // all loads of the batch first
         const int tl = tl0 + t_step * bi;
@@ -420,6 +471,7 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
           for (int j = 0; j < 4; ++j)
             xres[bi][j] = x_io[(size_t)min(m0 + row0 + j, a.M - 1) * a.N + tile * 32 + ln];
         }
+        if (W8) wsc[bi] = wscale[tile * 32 + ln];
       }
       // The phase is bound by the round trips of these loads, not by arithmetic: keep the whole
       // batch in flight together (left alone, the compiler sinks loads towards their uses).
@@ -486,6 +538,10 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
 #pragma unroll
           for (int j = 0; j < 4; ++j) v[j] *= rstd4[j];
         }
+        if (W8) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) v[j] *= wsc[bi];
+        }
         if (EPI == EPI_RESID) {
 #pragma unroll
           for (int j = 0; j < 4; ++j)
@@ -546,8 +602,11 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
 // to two pieces.
 // MULTI: a K slice may span several LDS chunks (the host knows from its plan); the single-chunk
 // form carries no re-staging code and nothing of it in registers through the main loop.
-template <int PRO, int EPI, bool MULTI>
+// W8: the weights are E4M3 codes (four loads per piece, converted to bf16 fragments in
+// registers; the row scales are applied in the reduction).
+template <int PRO, int EPI, bool MULTI, bool W8>
 __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
+  constexpr int kLoads = W8 ? kPieceFrags / 2 : kPieceFrags;   // 16-byte loads per piece and lane
   // X chunk: [32 k-steps][2 m-halves][hi, lo][64 slots] x 16 bytes = 128 KiB
   __shared__ uint4 xs[32 * 2 * 2 * 64];
   __shared__ int s_pos[kMTile];             // EPI_QKV: rotary position of each row of the m tile
@@ -575,27 +634,27 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
     const int n_chunks = (np + 3) >> 2;                  // LDS chunks of 4 pieces
     const int my_tiles = t_count > wave ? (t_count - wave + 3) / 4 : 0;   // tiles wave, wave+4, ..
     const size_t unit_id = ((size_t)mt * G + g) * S + sp;
-    const size_t tile_stride = (size_t)(K / kFragK) * 64;                 // uint4 per tile
+    const size_t tile_stride = (size_t)(K / (W8 ? 2 * kFragK : kFragK)) * 64;   // uint4 per tile
     typedef const __attribute__((address_space(1))) u32x4_t* wptr_t;
     const wptr_t wbase = (wptr_t)a.Wp + (size_t)(t_begin + wave) * tile_stride +
-                         (size_t)p_begin * (kPieceFrags * 64);
+                         (size_t)p_begin * (kLoads * 64);
 
     // Ring of weight pieces.  Every step of the main loop issues exactly kPieceFrags loads into
     // the slot it has just consumed - a cache-resident dummy address once nothing is left - so
     // the number of younger loads behind any slot is a compile-time constant and the wait
     // before each MFMA is exact (a conditional load would force a full drain instead).
-    u32x4_t ring[kRing][kPieceFrags];
+    u32x4_t ring[kRing][kLoads];
     // next piece to load: a running pointer (piece after piece, then a jump to this wave's next
     // tile), so that issuing costs a handful of scalar instructions
     wptr_t ip = my_tiles > 0 ? wbase : (wptr_t)a.Wp;
-    const size_t tile_jump = 4 * tile_stride - (size_t)np * (kPieceFrags * 64);
+    const size_t tile_jump = 4 * tile_stride - (size_t)np * (kLoads * 64);
     int ij = 0, it = 0;
     auto issue = [&](u32x4_t* buf) {
 #pragma unroll
-      for (int f = 0; f < kPieceFrags; ++f)   // streamed once: do not keep it in the caches
+      for (int f = 0; f < kLoads; ++f)        // streamed once: do not keep it in the caches
         buf[f] = __builtin_nontemporal_load(ip + ((unsigned)lane + f * 64u));
       if (it < my_tiles) {
-        ip += kPieceFrags * 64;
+        ip += kLoads * 64;
         if (++ij == np) {
           ij = 0;
           ip += tile_jump;
@@ -732,10 +791,18 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
           // low 3 bits are those of f.
           auto piece_block = [&](auto first_of_tile) {
             constexpr bool kFirst = decltype(first_of_tile)::value;
+            bf16x8_t wf[kPieceFrags];                    // the piece's eight weight fragments
+#pragma unroll
+            for (int l = 0; l < kLoads; ++l) {
+              if (W8)
+                w8_to_frags(buf[l], wf[2 * l], wf[2 * l + 1]);
+              else
+                wf[l] = __builtin_bit_cast(bf16x8_t, buf[l]);
+            }
 #pragma unroll
             for (int f = 0; f < kPieceFrags; ++f) {
               const uint4* xp = xf + (size_t)(f * 4) * 64 + frag_slot(lane, f);
-              const bf16x8_t w = __builtin_bit_cast(bf16x8_t, buf[f]);
+              const bf16x8_t w = wf[f];
               const bf16x8_t x0h = __builtin_bit_cast(bf16x8_t, xp[0]);
               const bf16x8_t x0l = __builtin_bit_cast(bf16x8_t, xp[64]);
               const bf16x8_t x1h = __builtin_bit_cast(bf16x8_t, xp[128]);
@@ -751,6 +818,7 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
               acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0l, w, acc0, 0, 0, 0);
               acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1l, w, acc1, 0, 0, 0);
             }
+            if (W8) __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);   // conversion of fragment 0
             __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);       // LDS reads of fragment 0
 #pragma unroll
             for (int f = 0; f < kPieceFrags - 1; ++f) {
@@ -758,6 +826,7 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
               for (int q = 0; q < 4; ++q) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA of fragment f
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read of fragment f + 1
+                if (W8) __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   // a quarter of fragment f + 1's conversion
               }
             }
             __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
@@ -875,7 +944,7 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
     // ---- second half: group barrier, reduction, epilogue (arguments read afresh) ----
     gemm_args_ptr_t ap = (gemm_args_ptr_t)__builtin_amdgcn_kernarg_segment_ptr();
     asm volatile("" : "+s"(ap));
-    gemm_reduce_phase<PRO, EPI>(ap, s_pos, s_crow, tid, lane, wave);
+    gemm_reduce_phase<PRO, EPI, W8>(ap, s_pos, s_crow, tid, lane, wave);
   }
 }
 

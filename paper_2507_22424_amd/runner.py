@@ -61,7 +61,10 @@ class VerifyPass:
         """Upload the nine tensors of a layer, pack them, drop the raw copies."""
         dev = {k: v.to(self.device).contiguous() for k, v in raw.items()}
         packed = torch.empty(self.packed_bytes, dtype=torch.uint8, device=self.device)
-        sv.sv_pack_layer(self.cfg, dev, packed)
+        if self.cfg.dtype == sv.SV_BF16_W8:
+            sv.sv_pack_layer_w8(self.cfg, dev, packed)
+        else:
+            sv.sv_pack_layer(self.cfg, dev, packed)
         torch.cuda.current_stream().synchronize()
         self.packed[layer] = packed
 

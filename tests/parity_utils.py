@@ -11,6 +11,7 @@ import time
 import numpy as np
 import torch
 
+from oracle import fp8_weights as f8
 from oracle import verify_oracle as vo
 from paper_2507_22424_amd import binding as sv
 from paper_2507_22424_amd import workload as wl
@@ -67,9 +68,16 @@ class SideBySide:
         self.attn_err, self.x_err = [], []
         t0 = time.time()
         for l in range(L):
-            w = wl.layer_weights(cfg, l)
-            self.gpu.load_layer(l, w)
-            w64 = {k: f64(v) for k, v in w.items()}
+            if cfg.dtype == "bf16_w8":       # 8-bit matrices: the oracle computes on the dequantised ones
+                w = wl.layer_weights_w8(cfg, l)
+                self.gpu.load_layer(l, w)
+                w64 = {k: (f64(v) if k.startswith("g") else
+                           f8.dequantise(v.numpy(), w[k + "_scale"].numpy()))
+                       for k, v in w.items() if not k.endswith("_scale")}
+            else:
+                w = wl.layer_weights(cfg, l)
+                self.gpu.load_layer(l, w)
+                w64 = {k: f64(v) for k, v in w.items()}
             del w
             ref_attn = []
             for b in range(B):

@@ -139,6 +139,26 @@ def test_bf16_small_model(T, B, P):
     check_accept_paths(s, (0, 4, 8))
 
 
+# ---- 8-bit weight storage (E4M3 codes + row scales), same bar as bf16 ------------------------
+
+@pytest.mark.parametrize("T,B,P", [(26, 2, 90), (60, 1, 280), (70, 2, 40)])
+def test_w8_small_model(T, B, P):
+    cfg = wl.C2.scaled(name=f"w8-small-T{T}-B{B}", index=50 + B, dtype="bf16_w8", n_layers=3,
+                       hidden=512, n_heads=4, head_dim=128, mlp_dim=1536, vocab=1024, n_bins=256,
+                       tree_nodes=T, n_episodes=B, prefix_lo=max(1, P - 50), prefix_hi=P,
+                       max_children=6, r_values=(0, 4))
+    s = SideBySide(cfg)
+    assert not s.persistent_checked                  # per-layer launches only
+    check_forward(s, TOL["bf16"])
+    check_accept_paths(s, (0, 4))
+
+
+def test_w8_one_7b_layer():
+    s = SideBySide(wl.C2.scaled(name="C2-w8", vocab=32000, dtype="bf16_w8"))
+    assert max(s.attn_err) <= TOL["bf16"] and max(s.x_err) <= TOL["bf16"]
+    say(f"[C2-w8] attn err {max(s.attn_err):.3e}, x err {max(s.x_err):.3e}")
+
+
 # ---- configuration 2: one 7B-shaped layer, bf16 ------------------------------------------
 
 def test_c2_one_7b_layer_bf16():
