@@ -93,6 +93,9 @@ def main():
     ap.add_argument("--r", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers (invalid as a result)")
+    ap.add_argument("--weights", choices=("bf16", "w8"), default="bf16",
+                    help="w8: the same workload with 8-bit (E4M3 + row scale) matrices, a variant "
+                         "of its own: half the weight bytes, not the headline configuration")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (calibrates rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters in the same profile)")
@@ -108,6 +111,10 @@ def main():
     from paper_2507_22424_amd.runner import VerifyPass
 
     cfg = wl.C3 if args.layers is None else wl.C3.scaled(n_layers=args.layers)
+    w8 = args.weights == "w8"
+    if w8:
+        cfg = cfg.scaled(dtype="bf16_w8")
+        args.no_cpu_baseline = True      # the baseline leg times the bf16 workload
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
     B, T, L = cfg.n_episodes, cfg.tree_nodes, cfg.n_layers
@@ -117,7 +124,7 @@ def main():
 
     t0 = time.time()
     with ThreadPoolExecutor(max_workers=8) as ex:
-        futs = [ex.submit(wl.layer_weights, cfg, l) for l in range(L)]
+        futs = [ex.submit(wl.layer_weights_w8 if w8 else wl.layer_weights, cfg, l) for l in range(L)]
         for l, f in enumerate(futs):
             vp.load_layer(l, f.result())
             futs[l] = None
@@ -169,7 +176,8 @@ def main():
                 acc_ms[k] += evs.elapsed_ms(l * n_ev + a, l * n_ev + b)
     per_step_ms = {k: v / prof_steps for k, v in acc_ms.items()}
     H, D, F = cfg.hidden, cfg.n_heads * cfg.head_dim, cfg.mlp_dim
-    gemm_bytes = {"qkv": 3 * D * H * 2, "o": H * D * 2, "gate_up": 2 * F * H * 2, "down": H * F * 2}
+    wb = 1 if w8 else 2                  # bytes per weight (the row scales of w8 are 0.1 % more)
+    gemm_bytes = {"qkv": 3 * D * H * wb, "o": H * D * wb, "gate_up": 2 * F * H * wb, "down": H * F * wb}
     gemm_ms = sum(per_step_ms[k] for k in gemm_bytes)
     gemm_gbs = sum(gemm_bytes.values()) * L / (gemm_ms * 1e-3) / 1e9
     kv_bytes = 2 * cfg.n_heads * (int(prefix_len[0]) + T) * cfg.head_dim * 2
@@ -180,11 +188,12 @@ def main():
         "metric": "verified tree tokens/sec + step latency (7B-shaped, tree 60); % HBM peak",
         "value": tokens_per_s, "unit": "verified tree tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 (8-bit E4M3 weights)" if w8 else "bf16",
         "data": "synthetic",
         "config": {"workload": f"C3: {L}-layer 7B-shaped verify pass + 256-bin action head + "
                                f"relaxed accept (r={args.r}), tree {T} nodes depth 7, prefix "
-                               f"{int(prefix_len[0])}, 1 episode",
+                               f"{int(prefix_len[0])}, 1 episode" + (", 8-bit weights" if w8 else ""),
                    "hidden": H, "layers": L, "tree_nodes": T, "prefix": int(prefix_len[0])},
         "step_hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "step_algorithmic_bytes": step_bytes,
@@ -192,7 +201,7 @@ def main():
         "kernel_ms_per_step": per_step_ms,
         "roofline": {"bound": "hbm", "kernel": "gemm_stream_bf16 (4 launches per layer: q/k/v, o, gate/up, down)",
                      "achieved": gemm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": gemm_gbs / HBM_PEAK_GBS, "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH,
+                     "frac": gemm_gbs / HBM_PEAK_GBS, "traffic": None if w8 else GEMM_TRAFFIC_BYTES_PER_LAUNCH,
                      "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/c3_step_hbm_traffic.txt",
                      "bytes_per_launch_avg": weights_total / (4 * L),
                      "avg_launch_us": gemm_ms * 1e3 / (4 * L)},

@@ -159,6 +159,14 @@ def test_w8_one_7b_layer():
     say(f"[C2-w8] attn err {max(s.attn_err):.3e}, x err {max(s.x_err):.3e}")
 
 
+def test_w8_full_pass_32_layers():
+    """The benchmark's workload with 8-bit matrices, all 32 layers deep."""
+    s = SideBySide(wl.C3.scaled(name="C3-w8", dtype="bf16_w8"), per_layer=False)
+    n_ties = check_forward(s, TOL["bf16"])
+    check_accept_paths(s, wl.C3.r_values)
+    say(f"[C3-w8] logit err {s.logit_err.max():.3e}, tolerated argmax near-ties: {n_ties} of {len(s.ref_token)} nodes")
+
+
 # ---- configuration 2: one 7B-shaped layer, bf16 ------------------------------------------
 
 def test_c2_one_7b_layer_bf16():

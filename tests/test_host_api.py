@@ -138,3 +138,29 @@ def test_stack_calls_check_their_arguments_before_any_launch():
                                           None, None, 0, None) == -2
     assert lib.sv_verify_stack_persistent(C.byref(c7), 2, ptrs, one, kvs, C.byref(tree), 2, one,
                                           big, None, None, 0, None) == -2
+
+
+def test_eight_bit_weight_packing_checks_its_arguments_before_any_launch():
+    """SV_BF16_W8: half the matrix bytes plus the row scales; the two pack calls each refuse the
+    other's dtype; nothing is launched on bad arguments."""
+    lib = sv.lib()
+    bf = sv.model_cfg("bf16", 512, 4, 128, 1536, 1024, 1e-5, 10000.0)
+    w8 = sv.model_cfg("bf16_w8", 512, 4, 128, 1536, 1024, 1e-5, 10000.0)
+    nb, n8 = sv.sv_packed_layer_bytes(bf), sv.sv_packed_layer_bytes(w8)
+    H, D, F = 512, 512, 1536
+    matrix_elems = 3 * D * H + H * D + 2 * F * H + H * F
+    assert nb - n8 >= matrix_elems - 4 * (3 * D + 2 * H + 2 * F) - 8 * 256      # 1 byte less per element, scales added
+    assert n8 >= matrix_elems + 4 * (3 * D + 2 * H + 2 * F)
+    one = C.c_void_p(256)
+    raw = sv.LayerWeights(*([256] * 9))
+    sc = sv.LayerScales(*([256] * 7))
+    assert lib.sv_pack_layer_w8(C.byref(bf), C.byref(raw), C.byref(sc), one, 1 << 30, None) == -6
+    assert lib.sv_pack_layer(C.byref(w8), C.byref(raw), one, 1 << 30, None) == -6
+    assert lib.sv_pack_layer_w8(C.byref(w8), None, C.byref(sc), one, 1 << 30, None) == -1
+    assert lib.sv_pack_layer_w8(C.byref(w8), C.byref(raw), None, one, 1 << 30, None) == -1
+    no_scale = sv.LayerScales(256, 256, 256, 256, 256, 256, None)
+    assert lib.sv_pack_layer_w8(C.byref(w8), C.byref(raw), C.byref(no_scale), one, 1 << 30, None) == -1
+    assert lib.sv_pack_layer_w8(C.byref(w8), C.byref(raw), C.byref(sc), one, n8 - 1, None) == -5
+    assert lib.sv_pack_layer_w8(C.byref(w8), C.byref(raw), C.byref(sc), C.c_void_p(260), n8, None) == -5
+    odd = sv.model_cfg("bf16_w8", 384, 4, 128, 1536, 1024, 1e-5, 10000.0)      # hidden not a multiple of 256
+    assert lib.sv_pack_layer_w8(C.byref(odd), C.byref(raw), C.byref(sc), one, 1 << 30, None) == -2
