@@ -19,16 +19,17 @@ from paper_2507_22424_amd.runner import VerifyPass
 
 
 _ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+_LOG_DIR = os.path.join(_ROOT, os.environ.get("SV_TEST_LOG_DIR", "gpurun_out"))
 
 
 def say(msg):
-    """Progress / result line: printed (visible with `pytest -s`) and appended to
-    gpurun_out/parity.log, so that a long GPU test shows signs of life and leaves its
-    measured errors behind even when pytest captures the output."""
+    """Progress / result line: printed (visible with `pytest -s`) and appended to a log file in
+    the run's output folder, so that a long GPU test shows signs of life and leaves its measured
+    errors behind even when pytest captures the output."""
     print(msg, flush=True)
     try:
-        os.makedirs(os.path.join(_ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(_ROOT, "gpurun_out", "parity.log"), "a") as f:
+        os.makedirs(_LOG_DIR, exist_ok=True)
+        with open(os.path.join(_LOG_DIR, "parity.log"), "a") as f:
             f.write(msg + "\n")
     except OSError:
         pass
