@@ -60,7 +60,7 @@ constexpr int kTileFloats = kMTile * kFragRows;   // one partial tile, [64][32] 
 constexpr int kTileVec4 = kTileFloats / 8;        // .. as stored: scaled int16 pairs, [4][64 lanes] uint4 = 4 KiB
 constexpr int kXcds = 8;
 constexpr int kCntStride = 32;     // 32-bit words per group's counters: a 128-byte line of its own
-constexpr int kRedBatch = 6;       // reduction work items whose loads are in flight together
+constexpr int kRedBatch = 3;       // reduction work items whose loads are in flight together
 
 enum { PRO_PLAIN = 0, PRO_GAIN = 1 };
 enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
