@@ -1,6 +1,6 @@
 """Benchmark of one Spec-VLA tree-verification step on one MI355X.
 
-step = sv_verify_stack (32 layers) -> sv_action_head_argmax -> sv_relaxed_accept for the full
+step = sv_verify_stack (32 layers) -> sv_action_head_argmax_packed -> sv_relaxed_accept for the full
 7B-shaped configuration (60-node tree, 280-token prefix, bf16 weights), all inputs resident
 in HBM.  Prints ONE JSON line: verified tree tokens/s, step latency, the HBM roofline of the
 dominant kernel (the weight-streaming GEMM, timed live with HIP events) and the CPU oracle

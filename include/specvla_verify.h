@@ -262,6 +262,25 @@ int sv_action_head_argmax(const sv_model_cfg *cfg, const void *g_final, const vo
                           int32_t *out_token, float *out_logits, void *workspace,
                           size_t ws_bytes, void *stream);
 
+/* The same head for bf16 models (SV_BF16, SV_BF16_W8) on the streaming matrix-core kernel of
+ * the layers: the head rows [vocab_lo, vocab_hi) are re-tiled once at load time, and every
+ * call then reads them once at streaming speed (final RMSNorm, Eq. 1; Sec. 4.3 for the
+ * action rows).  vocab_hi - vocab_lo must be a multiple of 32 and H a multiple of 256.
+ *   sv_packed_head_bytes: host-only, bytes of the packed form -> *bytes
+ *   sv_pack_head: g_final [device] [H] bf16, w_lm [device] [V, H] bf16 row-major;
+ *                 packed [device], 256-byte aligned, packed_bytes >= sv_packed_head_bytes
+ *   sv_action_head_argmax_packed: packed_head from sv_pack_head with the same cfg and range;
+ *                 x, out_token, out_logits as in sv_action_head_argmax; workspace sized and
+ *                 initialised with n_scored = vocab_hi - vocab_lo
+ * SV_ERR_DTYPE for SV_F32, SV_ERR_SHAPE for ranges or sizes outside the rules above. */
+int sv_packed_head_bytes(const sv_model_cfg *cfg, int vocab_lo, int vocab_hi, size_t *bytes);
+int sv_pack_head(const sv_model_cfg *cfg, const void *g_final, const void *w_lm, int vocab_lo,
+                 int vocab_hi, void *packed, size_t packed_bytes, void *stream);
+int sv_action_head_argmax_packed(const sv_model_cfg *cfg, const void *packed_head, const float *x,
+                                 int n_rows, int vocab_lo, int vocab_hi, int32_t *out_token,
+                                 float *out_logits, void *workspace, size_t ws_bytes,
+                                 void *stream);
+
 /* Relaxed acceptance (Eq. 5, Alg. 1) over B trees and the longest accepted path.  Integer
  * only.  bin(t) = t - action_lo.  Node c >= 1 passes when draft_token[c] and
  * target_token[parent[c]] are both action tokens and |bin difference| <= r; r = 0 is strict

@@ -26,7 +26,8 @@ EXPORTS = ("sv_version", "sv_strerror", "sv_tree_build_masks", "sv_packed_layer_
            "sv_pack_layer", "sv_pack_layer_w8", "sv_workspace_bytes", "sv_workspace_init", "sv_workspace_region",
            "sv_verify_layer",
            "sv_verify_layer_timed", "sv_verify_stack", "sv_verify_stack_persistent",
-           "sv_action_head_argmax", "sv_relaxed_accept",
+           "sv_action_head_argmax", "sv_packed_head_bytes", "sv_pack_head",
+           "sv_action_head_argmax_packed", "sv_relaxed_accept",
            "sv_commit_path", "sv_advance_prefix", "sv_tree_build_device")
 SV_N_TIMING_EVENTS = 9
 SV_TIMELINE_SLOTS = 16
@@ -100,6 +101,12 @@ def lib() -> C.CDLL:
         l.sv_action_head_argmax.argtypes = [C.POINTER(ModelCfg), C.c_void_p, C.c_void_p, C.c_void_p,
                                             C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                             C.c_void_p, C.c_size_t, C.c_void_p]
+        l.sv_packed_head_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int, C.c_int, C.POINTER(C.c_size_t)]
+        l.sv_pack_head.argtypes = [C.POINTER(ModelCfg), C.c_void_p, C.c_void_p, C.c_int, C.c_int,
+                                   C.c_void_p, C.c_size_t, C.c_void_p]
+        l.sv_action_head_argmax_packed.argtypes = [C.POINTER(ModelCfg), C.c_void_p, C.c_void_p, C.c_int,
+                                                   C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                   C.c_size_t, C.c_void_p]
         l.sv_relaxed_accept.argtypes = [C.POINTER(Tree), C.c_void_p, C.c_void_p, C.c_int, C.c_int,
                                         C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -285,6 +292,39 @@ def sv_action_head_argmax(cfg: ModelCfg, g_final: torch.Tensor, w_lm: torch.Tens
         _dev(out_token, torch.int32, "out_token"), _dev(out_logits, torch.float32, "out_logits"),
         _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)),
         "sv_action_head_argmax")
+
+
+def sv_packed_head_bytes(cfg: ModelCfg, vocab_lo: int, vocab_hi: int) -> int:
+    out = C.c_size_t(0)
+    _check(lib().sv_packed_head_bytes(C.byref(cfg), vocab_lo, vocab_hi, C.byref(out)),
+           "sv_packed_head_bytes")
+    return out.value
+
+
+def sv_pack_head(cfg: ModelCfg, g_final: torch.Tensor, w_lm: torch.Tensor, vocab_lo: int,
+                 vocab_hi: int, packed: torch.Tensor, stream=None) -> None:
+    if w_lm.numel() != cfg.vocab * cfg.hidden or g_final.numel() != cfg.hidden:
+        raise ValueError("w_lm must be [vocab, hidden] and g_final [hidden]")
+    _check(lib().sv_pack_head(
+        C.byref(cfg), _dev(g_final, torch.bfloat16, "g_final"), _dev(w_lm, torch.bfloat16, "w_lm"),
+        vocab_lo, vocab_hi, _dev(packed, torch.uint8, "packed"), packed.numel(), _stream(stream)),
+        "sv_pack_head")
+
+
+def sv_action_head_argmax_packed(cfg: ModelCfg, packed_head: torch.Tensor, x: torch.Tensor,
+                                 n_rows: int, vocab_lo: int, vocab_hi: int,
+                                 out_token: torch.Tensor, out_logits: Optional[torch.Tensor],
+                                 workspace: torch.Tensor, stream=None) -> None:
+    if x.numel() < n_rows * cfg.hidden:
+        raise ValueError("x must be [n_rows, hidden]")
+    if out_token.numel() < n_rows or (out_logits is not None and
+                                      out_logits.numel() < n_rows * (vocab_hi - vocab_lo)):
+        raise ValueError("output tensors too small")
+    _check(lib().sv_action_head_argmax_packed(
+        C.byref(cfg), _dev(packed_head, torch.uint8, "packed_head"), _dev(x, torch.float32, "x"),
+        n_rows, vocab_lo, vocab_hi, _dev(out_token, torch.int32, "out_token"),
+        _dev(out_logits, torch.float32, "out_logits"), _dev(workspace, torch.uint8, "workspace"),
+        workspace.numel(), _stream(stream)), "sv_action_head_argmax_packed")
 
 
 def sv_relaxed_accept(tree: Tree, draft_token: torch.Tensor, target_token: torch.Tensor,

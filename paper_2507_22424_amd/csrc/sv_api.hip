@@ -113,8 +113,39 @@ static WorkspaceLayout workspace_layout(const sv_model_cfg& c, int m_rows, int n
   L.act = o;         o = align_up(o + mp * F * 4, kAlign);
   L.head_z = o;      o = align_up(o + mp * H * 4, kAlign);
   L.head_logits = o; o = align_up(o + mp * (size_t)(n_scored > 0 ? n_scored : 0) * 4 * 16, kAlign);   // up to 16 K-slice planes
+  // (the regions above do not move with n_scored: a layer call finds them without knowing it)
+  L.head_cnt = L.head_cnt_bytes = L.head_sumsq = L.head_part = L.head_part_bytes = 0;
+  if (c.dtype != SV_F32 && n_scored > 0 && n_scored % kFragRows == 0) {
+    const size_t tiles = n_scored / kFragRows, s_max = 8;
+    L.head_cnt_bytes = align_up(mt * (tiles + kXcds) * kCntStride * sizeof(int), kAlign);
+    L.head_cnt = o;   o += L.head_cnt_bytes;
+    L.head_sumsq = o; o = align_up(o + mt * (tiles + kXcds) * s_max * kMTile * 4, kAlign);
+    L.head_part_bytes = align_up(mt * tiles * s_max * kTileFloats * 4, 2 * kAlign);
+    L.head_part = o;  o += L.head_part_bytes;
+  }
   L.total = o;
   return L;
+}
+
+// Packed head: float32 gain, then the scored rows in fragment order.
+struct HeadLayout {
+  size_t gain, w, total;
+};
+static HeadLayout head_layout(const sv_model_cfg& c, int n) {
+  HeadLayout L;
+  L.gain = 0;
+  L.w = align_up((size_t)c.hidden * 4, kAlign);
+  L.total = L.w + align_up((size_t)n * c.hidden * 2, kAlign);
+  return L;
+}
+static int check_packed_head(const sv_model_cfg* cfg, int vocab_lo, int vocab_hi) {
+  const int rc = check_cfg(cfg);
+  if (rc != SV_OK) return rc;
+  if (cfg->dtype == SV_F32) return SV_ERR_DTYPE;
+  if (vocab_lo < 0 || vocab_lo >= vocab_hi || vocab_hi > cfg->vocab ||
+      (vocab_hi - vocab_lo) % kFragRows)
+    return SV_ERR_SHAPE;
+  return SV_OK;
 }
 
 // K slices of the LM-head GEMM (it has few output tiles, so the reduction is spread out).
@@ -412,6 +443,39 @@ static int head_t(const sv_model_cfg& c, const T* g_final, const T* w_lm, const 
   return launch_status();
 }
 
+// Head on the streaming kernel: RMSNorm gain in the staging pass, 1 / rms after the reduction,
+// logits to the workspace, then the row argmax.
+static int head_packed(const sv_model_cfg& c, const char* packed, const float* x, int n_rows,
+                       int lo, int hi, int32_t* out_token, float* out_logits, char* ws,
+                       hipStream_t st) {
+  const int n = hi - lo, H = c.hidden;
+  const WorkspaceLayout wl = workspace_layout(c, n_rows, n);
+  const HeadLayout hl = head_layout(c, n);
+  const int n_xcd = device_xcds();
+  const GemmPlan p = plan_gemm(n, H, n_xcd);
+  float* logits = (float*)(ws + wl.head_logits);
+  GemmArgs a;
+  memset(&a, 0, sizeof(a));
+  a.X = x; a.gain = (const float*)(packed + hl.gain); a.Wp = (const uint4*)(packed + hl.w);
+  a.M = n_rows; a.N = n; a.K = H; a.S = p.S; a.gpx = p.gpx; a.n_xcd = n_xcd;
+  const int n_tiles = n / kFragRows, G = n_xcd * p.gpx, npieces = H / kBlkK;
+  a.tq = n_tiles / G; a.trem = n_tiles % G;
+  a.pq = npieces / p.S; a.prem = npieces % p.S;
+  a.inv_S = (65536u + p.S - 1) / p.S;
+  a.part16 = (uint4*)(ws + wl.head_part);
+  a.pscale = (float*)(ws + wl.head_part + wl.head_part_bytes / 2);
+  a.sumsq = (float*)(ws + wl.head_sumsq);
+  a.group_cnt = (unsigned*)(ws + wl.head_cnt);
+  a.status = (int*)(ws + wl.counters + wl.counter_bytes) - 1;   // the layers' status word
+  a.eps = c.rms_eps;
+  a.x_io = logits;
+  const dim3 grid(n_xcd, p.gpx * p.S, wl.m_tiles);
+  if (p.multi) gemm_stream_bf16<PRO_GAIN, EPI_OUT, true, false><<<grid, 256, 0, st>>>(a);
+  else gemm_stream_bf16<PRO_GAIN, EPI_OUT, false, false><<<grid, 256, 0, st>>>(a);
+  argmax_rows_wide<<<n_rows, 256, 0, st>>>(logits, out_logits, n, lo, out_token);
+  return launch_status();
+}
+
 }  // namespace sv
 
 using namespace sv;
@@ -544,6 +608,10 @@ int sv_workspace_init(const sv_model_cfg* cfg, int B, int T, int n_scored, void*
   if (n > 0)
     zero_ints<<<(unsigned)((n + 255) / 256), 256, 0, (hipStream_t)stream>>>(
         (int*)((char*)workspace + wl.counters), n);
+  const size_t nh = wl.head_cnt_bytes / sizeof(int);
+  if (nh > 0)
+    zero_ints<<<(unsigned)((nh + 255) / 256), 256, 0, (hipStream_t)stream>>>(
+        (int*)((char*)workspace + wl.head_cnt), nh);
   return launch_status();
 }
 
@@ -686,6 +754,47 @@ int sv_action_head_argmax(const sv_model_cfg* cfg, const void* g_final, const vo
                          vocab_hi, out_token, out_logits, (char*)workspace, (hipStream_t)stream);
   return head_t<bf16_t>(*cfg, (const bf16_t*)g_final, (const bf16_t*)w_lm, x, n_rows, vocab_lo,
                         vocab_hi, out_token, out_logits, (char*)workspace, (hipStream_t)stream);
+}
+
+int sv_packed_head_bytes(const sv_model_cfg* cfg, int vocab_lo, int vocab_hi, size_t* bytes) {
+  if (!bytes) return SV_ERR_NULL;
+  const int rc = check_packed_head(cfg, vocab_lo, vocab_hi);
+  if (rc != SV_OK) return rc;
+  *bytes = head_layout(*cfg, vocab_hi - vocab_lo).total;
+  return SV_OK;
+}
+
+int sv_pack_head(const sv_model_cfg* cfg, const void* g_final, const void* w_lm, int vocab_lo,
+                 int vocab_hi, void* packed_v, size_t packed_bytes, void* stream) {
+  const int rc = check_packed_head(cfg, vocab_lo, vocab_hi);
+  if (rc != SV_OK) return rc;
+  if (!g_final || !w_lm || !packed_v) return SV_ERR_NULL;
+  const int n = vocab_hi - vocab_lo, H = cfg->hidden;
+  const HeadLayout hl = head_layout(*cfg, n);
+  if (packed_bytes < hl.total || ((uintptr_t)packed_v % kAlign)) return SV_ERR_WORKSPACE;
+  char* packed = (char*)packed_v;
+  hipStream_t st = (hipStream_t)stream;
+  pack_gain<bf16_t><<<ceil_div(H, 256), 256, 0, st>>>((const bf16_t*)g_final, (float*)(packed + hl.gain), H);
+  const size_t n8 = (size_t)n * (H / 8);
+  pack_rows_mfma<<<(unsigned)((n8 + 255) / 256), 256, 0, st>>>(
+      (const uint4*)((const bf16_t*)w_lm + (size_t)vocab_lo * H), (uint4*)(packed + hl.w), n, H,
+      PACK_PLAIN, 0);
+  return launch_status();
+}
+
+int sv_action_head_argmax_packed(const sv_model_cfg* cfg, const void* packed_head, const float* x,
+                                 int n_rows, int vocab_lo, int vocab_hi, int32_t* out_token,
+                                 float* out_logits, void* workspace, size_t ws_bytes,
+                                 void* stream) {
+  const int rc = check_packed_head(cfg, vocab_lo, vocab_hi);
+  if (rc != SV_OK) return rc;
+  if (!packed_head || !x || !out_token || !workspace) return SV_ERR_NULL;
+  if (n_rows < 1 || n_rows > (1 << 15)) return SV_ERR_SHAPE;
+  if (((uintptr_t)workspace % kAlign) || ((uintptr_t)packed_head % kAlign) ||
+      ws_bytes < workspace_layout(*cfg, n_rows, vocab_hi - vocab_lo).total)
+    return SV_ERR_WORKSPACE;
+  return head_packed(*cfg, (const char*)packed_head, x, n_rows, vocab_lo, vocab_hi, out_token,
+                     out_logits, (char*)workspace, (hipStream_t)stream);
 }
 
 int sv_relaxed_accept(const sv_tree* tree, const int32_t* draft_token,

@@ -63,7 +63,7 @@ constexpr int kCntStride = 32;     // 32-bit words per group's counters: a 128-b
 constexpr int kRedBatch = 3;       // reduction work items whose loads are in flight together
 
 enum { PRO_PLAIN = 0, PRO_GAIN = 1 };
-enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
+enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_OUT = 3 };
 enum { PACK_PLAIN = 0, PACK_PAIR16_HEAD = 1, PACK_PAIR16_GU = 2 };
 
 // Packer: src [rows, K] bf16 row-major -> fragment order, with a row permutation:
@@ -140,7 +140,7 @@ struct GemmArgs {
   unsigned* group_cnt;   // [m_tiles][groups][kCntStride]: arrival (4 bits per XCD) and departure counters in the first two words, zero between launches
   int* status;           // sticky: != 0 once slices of one tile were seen on different XCDs
   float eps;
-  float* x_io;           // EPI_RESID: x_io [M, N] += Y
+  float* x_io;           // EPI_RESID: x_io [M, N] += Y;  EPI_OUT: x_io [M, N] = Y
   float* act;            // EPI_SWIGLU: act [M, N/2] = silu(gate) * up
   float* q_out;          // EPI_QKV: [M, nh*128] float32, rotated
   bf16_t* kc;            // EPI_QKV: caches [B][nh][cap][128]
@@ -547,6 +547,12 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
           for (int j = 0; j < 4; ++j)
             if (m0 + row0 + j < a.M)
               x_io[(size_t)(m0 + row0 + j) * a.N + tile * 32 + ln] = xres[bi][j] + v[j];
+        }
+        if (EPI == EPI_OUT) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            if (m0 + row0 + j < a.M)
+              x_io[(size_t)(m0 + row0 + j) * a.N + tile * 32 + ln] = v[j];
         }
         if (EPI == EPI_SWIGLU) {             // lanes 0..15 gate, 16..31 up of the same column
           const int F = a.N / 2;

@@ -104,6 +104,8 @@ struct WorkspaceLayout {
   size_t counter_bytes, part_bytes;
   // persistent stack kernel (bf16, one m tile): barrier words, per-XCD row sums and partial tiles
   size_t stack_ctl, stack_ctl_bytes, stack_sumsq, stack_part, stack_part_bytes;
+  // packed head (bf16, scored rows a multiple of 32): its own counters, row sums, partial tiles
+  size_t head_cnt, head_cnt_bytes, head_sumsq, head_part, head_part_bytes;
   int m_pad, m_tiles;
 };
 

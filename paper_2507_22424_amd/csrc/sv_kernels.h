@@ -308,6 +308,56 @@ __global__ __launch_bounds__(64) void argmax_rows(const float* __restrict__ part
   if (threadIdx.x == 0) out[row] = token_lo + (bi == 0x7fffffff ? 0 : bi);
 }
 
+// The same decision over finished logits (one plane, e.g. of the streaming head): 256 threads
+// per row, four loads in flight per thread; the lowest index wins exact ties.
+__global__ __launch_bounds__(256) void argmax_rows_wide(const float* __restrict__ logits,
+                                                        float* __restrict__ logits_out, int n,
+                                                        int token_lo, int32_t* __restrict__ out) {
+  __shared__ float s_best[4];
+  __shared__ int s_bi[4];
+  const size_t row = blockIdx.x;
+  const float* src = logits + row * n;
+  float best = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int i0 = threadIdx.x; i0 < n; i0 += 4 * 256) {
+    float v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = i0 + 256 * u < n ? src[i0 + 256 * u] : -INFINITY;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = i0 + 256 * u;
+      if (i >= n) continue;
+      if (logits_out) logits_out[row * n + i] = v[u];
+      if (v[u] > best || (v[u] == best && i < bi)) {
+        best = v[u];
+        bi = i;
+      }
+    }
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const float ov = __shfl_xor(best, off, kWave);
+    const int oi = __shfl_xor(bi, off, kWave);
+    if (ov > best || (ov == best && oi < bi)) {
+      best = ov;
+      bi = oi;
+    }
+  }
+  if ((threadIdx.x & 63) == 0) {
+    s_best[threadIdx.x >> 6] = best;
+    s_bi[threadIdx.x >> 6] = bi;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w)
+      if (s_best[w] > best || (s_best[w] == best && s_bi[w] < bi)) {
+        best = s_best[w];
+        bi = s_bi[w];
+      }
+    out[row] = token_lo + (bi == 0x7fffffff ? 0 : bi);
+  }
+}
+
 // ---------------------------------------------------------------------------------------
 // Packers (load time).  pack_gain widens a gain vector to float32; pack_rows_plain copies
 // a [rows, K] matrix behind `row_off` rows of the destination.

@@ -45,6 +45,9 @@ class VerifyPass:
         dt = sv.storage_dtype(self.cfg)
         self.g_final = torch.ones(wc.hidden, dtype=dt, device=device)
         self.w_lm = torch.zeros(wc.vocab, wc.hidden, dtype=dt, device=device)
+        # bf16 models score the head on the streaming kernel, from a packed copy of its rows
+        self.packed_head: Optional[torch.Tensor] = None
+        self.head_packable = self.cfg.dtype != sv.SV_F32 and self.n_scored % 32 == 0
         self.x0 = torch.zeros(self.M, wc.hidden, dtype=torch.float32, device=device)
         self.x = torch.zeros_like(self.x0)
         self.draft = torch.zeros(self.M, dtype=torch.int32, device=device)
@@ -75,6 +78,12 @@ class VerifyPass:
             self.w_lm.copy_(w_rows)
         else:
             self.w_lm[self.wc.action_lo:].copy_(w_rows)
+        if self.head_packable:
+            nb = sv.sv_packed_head_bytes(self.cfg, self.vocab_lo, self.vocab_hi)
+            self.packed_head = torch.empty(nb, dtype=torch.uint8, device=self.device)
+            sv.sv_pack_head(self.cfg, self.g_final, self.w_lm, self.vocab_lo, self.vocab_hi,
+                            self.packed_head)
+            torch.cuda.current_stream().synchronize()
 
     def load_prefix(self, layer: int, episode: int, k: torch.Tensor, v: torch.Tensor) -> None:
         P = k.shape[1]
@@ -90,9 +99,11 @@ class VerifyPass:
 
     # ---- one step ------------------------------------------------------------------
     def forward(self, n_layers: Optional[int] = None, want_logits: bool = True,
-                route: str = "stack") -> None:
+                route: str = "stack", head: str = "auto") -> None:
         """All layers, then the head.  route: "stack" (one sv_verify_stack call), "layers" (one
-        sv_verify_layer call per layer) or "persistent" (sv_verify_stack_persistent)."""
+        sv_verify_layer call per layer) or "persistent" (sv_verify_stack_persistent).  head:
+        "packed" (sv_action_head_argmax_packed), "plain" (sv_action_head_argmax on the raw
+        rows) or "auto" (packed where a packed head has been loaded)."""
         self.x.copy_(self.x0)
         n = self.wc.n_layers if n_layers is None else n_layers
         views = [kv.struct for kv in self.kv[:n]]
@@ -106,9 +117,18 @@ class VerifyPass:
         else:
             sv.sv_verify_stack(self.cfg, self.packed[:n], self.x, views, self.tree.struct, self.B,
                                self.workspace)
-        sv.sv_action_head_argmax(self.cfg, self.g_final, self.w_lm, self.x, self.M, self.vocab_lo,
-                                 self.vocab_hi, self.token, self.logits if want_logits else None,
-                                 self.workspace)
+        if head == "auto":
+            head = "packed" if self.packed_head is not None else "plain"
+        if head == "packed":
+            if self.packed_head is None:
+                raise RuntimeError("no packed head loaded (bf16 model, scored rows a multiple of 32)")
+            sv.sv_action_head_argmax_packed(self.cfg, self.packed_head, self.x, self.M,
+                                            self.vocab_lo, self.vocab_hi, self.token,
+                                            self.logits if want_logits else None, self.workspace)
+        else:
+            sv.sv_action_head_argmax(self.cfg, self.g_final, self.w_lm, self.x, self.M,
+                                     self.vocab_lo, self.vocab_hi, self.token,
+                                     self.logits if want_logits else None, self.workspace)
 
     def accept(self, r: int, target: Optional[torch.Tensor] = None) -> None:
         sv.sv_relaxed_accept(self.tree.struct, self.draft, self.token if target is None else target,
@@ -116,8 +136,8 @@ class VerifyPass:
                              self.accept_mask, self.accepted_len, self.best_node, self.path,
                              self.out_tokens)
 
-    def step(self, r: int, want_logits: bool = False) -> None:
-        self.forward(want_logits=want_logits)
+    def step(self, r: int, want_logits: bool = False, head: str = "auto") -> None:
+        self.forward(want_logits=want_logits, head=head)
         self.accept(r)
 
     def set_tree(self, parent: np.ndarray) -> None:

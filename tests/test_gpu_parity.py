@@ -313,6 +313,65 @@ def test_full_vocabulary_head_variant():
         assert_accept_equal(g, refs, cfg.max_depth)
 
 
+def _head_both_ways(H, V, M, ranges, seed, rows_scale=None):
+    """Packed head and plain head on random rows against the oracle's head, range by range."""
+    cfg = sv.model_cfg("bf16", H, H // 128, 128, 3 * H, V, 1e-5, 10000.0)
+    gen = torch.Generator().manual_seed(seed)
+    x = torch.randn(M, H, generator=gen, dtype=torch.float32)
+    if rows_scale is not None:
+        x *= rows_scale.reshape(-1, 1)
+    g = (1.0 + 0.1 * torch.randn(H, generator=gen)).to(torch.bfloat16)
+    w = (0.02 * torch.randn(V, H, generator=gen)).to(torch.bfloat16)
+    xd, gd, wd = x.cuda(), g.cuda(), w.cuda()
+    x64, g64, w64 = x.double().numpy(), g.double().numpy(), w.double().numpy()
+    for lo, hi in ranges:
+        n = hi - lo
+        say(f"[head H={H} V={V} M={M}] rows {lo}..{hi}")
+        B, T = (1, M) if M <= 128 else (M // 64, 64)     # the workspace is sized by B * T rows
+        ws = torch.empty(sv.sv_workspace_bytes(cfg, B, T, n), dtype=torch.uint8, device="cuda")
+        sv.sv_workspace_init(cfg, B, T, n, ws)
+        packed = torch.empty(sv.sv_packed_head_bytes(cfg, lo, hi), dtype=torch.uint8, device="cuda")
+        sv.sv_pack_head(cfg, gd, wd, lo, hi, packed)
+        tok = {k: torch.full((M,), -1, dtype=torch.int32, device="cuda") for k in ("packed", "plain")}
+        lg = {k: torch.zeros(M, n, dtype=torch.float32, device="cuda") for k in ("packed", "plain")}
+        for rep in range(2):                 # twice: the counters must be back at zero
+            sv.sv_action_head_argmax_packed(cfg, packed, xd, M, lo, hi, tok["packed"], lg["packed"], ws)
+        sv.sv_action_head_argmax(cfg, gd, wd, xd, M, lo, hi, tok["plain"], lg["plain"], ws)
+        tok_only = torch.full((M,), -1, dtype=torch.int32, device="cuda")
+        sv.sv_action_head_argmax_packed(cfg, packed, xd, M, lo, hi, tok_only, None, ws)
+        torch.cuda.synchronize()
+        ref_logits, ref_tok = vo.action_head(x64, g64, w64[lo:hi], lo, 1e-5)
+        scale = np.max(np.abs(ref_logits), axis=1, keepdims=True)
+        for k in ("packed", "plain"):
+            got = lg[k].cpu().numpy()
+            err = np.max(np.abs(got - ref_logits) / scale)
+            say(f"   {k}: logit err {err:.2e}")
+            assert err <= 2e-3               # far inside the 2e-2 bar: one product, no depth
+            t = tok[k].cpu().numpy()
+            assert np.array_equal(t, lo + np.argmax(got, axis=1))      # the integer decision
+            for i in np.flatnonzero(t != ref_tok):                       # only near-ties may differ
+                gap = ref_logits[i, ref_tok[i] - lo] - ref_logits[i, t[i] - lo]
+                assert gap <= 2 * 2e-3 * scale[i, 0]
+        assert np.array_equal(tok_only.cpu().numpy(), tok["packed"].cpu().numpy())
+        off, nb = sv.sv_workspace_region(cfg, B, T, n, sv.SV_WS_STATUS)
+        assert int(ws[off:off + 4].view(torch.int32).item()) == 0
+
+
+def test_packed_head_small_shapes_and_ranges():
+    """The head on the streaming kernel (Eq. 1; Sec. 4.3 for the action rows): one tile, fewer
+    tiles than tile groups, the action rows, the full vocabulary; one row, a ragged row tile,
+    several row tiles."""
+    _head_both_ways(512, 1024, 1, [(992, 1024), (768, 1024)], seed=11)
+    _head_both_ways(512, 1024, 60, [(512, 608), (768, 1024), (0, 1024)], seed=12)
+    _head_both_ways(1024, 2048, 192, [(1792, 2048), (0, 2048)], seed=13)
+
+
+def test_packed_head_7b_shape_action_rows_and_full_vocabulary():
+    """H = 4096, V = 32000, 60 rows of very different size (the row scales of the partial tiles)."""
+    scale = torch.tensor([10.0 ** ((i % 7) - 3) for i in range(60)])
+    _head_both_ways(4096, 32000, 60, [(32000 - 256, 32000), (0, 32000)], seed=14, rows_scale=scale)
+
+
 def test_multi_step_loop_with_kv_commit_reproduces_greedy_decoding():
     """The outer loop of Alg. 1 on the GPU with strict acceptance (r = 0): verify a (mock-)drafted
     tree, take the accepted tokens plus the verifier's own token, commit the path's K/V rows,

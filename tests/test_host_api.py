@@ -164,3 +164,44 @@ def test_eight_bit_weight_packing_checks_its_arguments_before_any_launch():
     assert lib.sv_pack_layer_w8(C.byref(w8), C.byref(raw), C.byref(sc), C.c_void_p(260), n8, None) == -5
     odd = sv.model_cfg("bf16_w8", 384, 4, 128, 1536, 1024, 1e-5, 10000.0)      # hidden not a multiple of 256
     assert lib.sv_pack_layer_w8(C.byref(odd), C.byref(raw), C.byref(sc), one, 1 << 30, None) == -2
+
+
+def test_packed_head_checks_its_arguments_before_any_launch():
+    """Packed head: gain + rows in bytes; bf16 only; scored range a multiple of 32 inside the
+    vocabulary; buffers aligned and large enough; workspace grows with the scored rows."""
+    lib = sv.lib()
+    bf = sv.model_cfg("bf16", 512, 4, 128, 1536, 1024, 1e-5, 10000.0)
+    f32 = sv.model_cfg("f32", 512, 4, 128, 1536, 1024, 1e-5, 10000.0)
+    nb = sv.sv_packed_head_bytes(bf, 768, 1024)
+    assert 256 * 512 * 2 + 512 * 4 <= nb <= 256 * 512 * 2 + 512 * 4 + 512
+    assert sv.sv_packed_head_bytes(bf, 0, 1024) >= 1024 * 512 * 2 + 512 * 4
+    out = C.c_size_t(0)
+    one = C.c_void_p(256)
+    assert lib.sv_packed_head_bytes(C.byref(f32), 768, 1024, C.byref(out)) == -6
+    assert lib.sv_packed_head_bytes(C.byref(bf), 768, 1024, None) == -1
+    for lo, hi in ((768, 1000), (-32, 0), (1024, 1024), (1000, 1056), (512, 480)):
+        assert lib.sv_packed_head_bytes(C.byref(bf), lo, hi, C.byref(out)) == -2, (lo, hi)
+        assert lib.sv_pack_head(C.byref(bf), one, one, lo, hi, one, 1 << 30, None) == -2
+        assert lib.sv_action_head_argmax_packed(C.byref(bf), one, one, 4, lo, hi, one, None, one,
+                                                1 << 40, None) == -2
+    assert lib.sv_pack_head(C.byref(f32), one, one, 768, 1024, one, 1 << 30, None) == -6
+    assert lib.sv_pack_head(C.byref(bf), None, one, 768, 1024, one, 1 << 30, None) == -1
+    assert lib.sv_pack_head(C.byref(bf), one, None, 768, 1024, one, 1 << 30, None) == -1
+    assert lib.sv_pack_head(C.byref(bf), one, one, 768, 1024, None, 1 << 30, None) == -1
+    assert lib.sv_pack_head(C.byref(bf), one, one, 768, 1024, one, nb - 1, None) == -5
+    assert lib.sv_pack_head(C.byref(bf), one, one, 768, 1024, C.c_void_p(264), nb, None) == -5
+    ws = sv.sv_workspace_bytes(bf, 1, 8, 256)
+    assert ws > sv.sv_workspace_bytes(bf, 1, 8, 0)
+    assert sv.sv_workspace_bytes(bf, 1, 8, 1024) > ws
+    args = (C.byref(bf), one, one, 8, 768, 1024, one, None, one)
+    assert lib.sv_action_head_argmax_packed(*args, ws - 1, None) == -5
+    assert lib.sv_action_head_argmax_packed(C.byref(bf), one, one, 8, 768, 1024, one, None,
+                                            C.c_void_p(264), ws, None) == -5
+    assert lib.sv_action_head_argmax_packed(C.byref(bf), C.c_void_p(264), one, 8, 768, 1024, one,
+                                            None, one, ws, None) == -5
+    assert lib.sv_action_head_argmax_packed(C.byref(bf), None, one, 8, 768, 1024, one, None, one,
+                                            ws, None) == -1
+    assert lib.sv_action_head_argmax_packed(C.byref(bf), one, one, 0, 768, 1024, one, None, one,
+                                            ws, None) == -2
+    assert lib.sv_action_head_argmax_packed(C.byref(f32), one, one, 8, 768, 1024, one, None, one,
+                                            ws, None) == -6
