@@ -226,7 +226,7 @@ int sv_verify_stack(const sv_model_cfg *cfg, int n_layers, const void *const *pa
                     const sv_kv_view *kv, const sv_tree *tree, int B, void *workspace,
                     size_t ws_bytes, void *stream);
 
-/* Experimental single-launch form of sv_verify_stack, bit-identical results: up to 32 layers
+/* Experimental single-launch form of sv_verify_stack, same arithmetic: up to 32 layers
  * run as ONE persistent launch (one workgroup per compute unit, split into waves that only
  * stream weights and waves that stage, reduce, attend and synchronise), so that weight loads
  * of the next phase are already in flight while a phase boundary is worked on.  Measured

@@ -618,6 +618,9 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
   __shared__ int s_pos[kMTile];             // EPI_QKV: rotary position of each row of the m tile
   __shared__ int s_crow[kMTile];            // EPI_QKV: cache row (b * nh * cap + P + t) of each row
   __shared__ float s_rowscale[kMTile];      // 2^-h of each row for this slice's partial tiles
+  // single-chunk form: accumulators of a tile that two waves share (see the runs below), handed
+  // from the wave that holds the tile's last pieces to the one that holds its first
+  __shared__ uint4 s_head[MULTI ? 1 : 3 * 8 * 64];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: bookkeeping stays in scalar registers
   const int mt = blockIdx.z, m0 = mt * kMTile;
@@ -638,12 +641,33 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
     const int p_begin = sp * pq + min(sp, prem);         // first piece (128 k-values) of the slice
     const int np = pq + (sp < prem ? 1 : 0);             // pieces in the slice
     const int n_chunks = (np + 3) >> 2;                  // LDS chunks of 4 pieces
-    const int my_tiles = t_count > wave ? (t_count - wave + 3) / 4 : 0;   // tiles wave, wave+4, ..
+    // Which pieces a wave multiplies.  MULTI: whole tiles wave, wave+4, .. (at most one, see the
+    // host's plan).  Single-chunk form: the group's t_count * np pieces, tile after tile, are cut
+    // into four equal consecutive runs, one per wave - with 21 or 22 tiles in a group whole
+    // tiles would give waves of 5 and of 6 tiles, and the launch waits for the longest.  A tile
+    // that straddles a cut is summed from the two waves' accumulators at the end (fewer than
+    // four tiles: whole tiles, so that no tile is shared by more than two waves).
+    const int my_tiles = t_count > wave ? (t_count - wave + 3) / 4 : 0;
+    int b0 = 0, b1 = 0;                                  // this wave's run of pieces [b0, b1)
+    if (!MULTI) {
+      const int P = t_count * np;
+      if (t_count >= 4) {
+        b0 = (wave * P) >> 2;
+        b1 = ((wave + 1) * P) >> 2;
+      } else {
+        b0 = min(wave, t_count) * np;
+        b1 = min(wave + 1, t_count) * np;
+      }
+    }
+    // first tile and first piece of the run (np <= 4 here; no division)
+    const int ft = MULTI ? wave : (np == 4 ? b0 >> 2 : np == 3 ? (b0 * 21846) >> 16 : np == 2 ? b0 >> 1 : b0);
+    const int cj0 = MULTI ? 0 : b0 - ft * np;
+    const int n_run = MULTI ? my_tiles * np : b1 - b0;
     const size_t unit_id = ((size_t)mt * G + g) * S + sp;
     const size_t tile_stride = (size_t)(K / (W8 ? 2 * kFragK : kFragK)) * 64;   // uint4 per tile
     typedef const __attribute__((address_space(1))) u32x4_t* wptr_t;
-    const wptr_t wbase = (wptr_t)a.Wp + (size_t)(t_begin + wave) * tile_stride +
-                         (size_t)p_begin * (kLoads * 64);
+    const wptr_t wbase = (wptr_t)a.Wp + (size_t)(t_begin + ft) * tile_stride +
+                         (size_t)(p_begin + cj0) * (kLoads * 64);
 
     // Ring of weight pieces.  Every step of the main loop issues exactly kPieceFrags loads into
     // the slot it has just consumed - a cache-resident dummy address once nothing is left - so
@@ -652,20 +676,20 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
     u32x4_t ring[kRing][kLoads];
     // next piece to load: a running pointer (piece after piece, then a jump to this wave's next
     // tile), so that issuing costs a handful of scalar instructions
-    wptr_t ip = my_tiles > 0 ? wbase : (wptr_t)a.Wp;
-    const size_t tile_jump = 4 * tile_stride - (size_t)np * (kLoads * 64);
-    int ij = 0, it = 0;
+    wptr_t ip = n_run > 0 ? wbase : (wptr_t)a.Wp;
+    const size_t tile_jump = (MULTI ? 4 : 1) * tile_stride - (size_t)np * (kLoads * 64);
+    int ij = cj0, to_issue = n_run;
     auto issue = [&](u32x4_t* buf) {
 #pragma unroll
       for (int f = 0; f < kLoads; ++f)        // streamed once: do not keep it in the caches
         buf[f] = __builtin_nontemporal_load(ip + ((unsigned)lane + f * 64u));
-      if (it < my_tiles) {
+      if (to_issue > 0) {
         ip += kLoads * 64;
         if (++ij == np) {
           ij = 0;
           ip += tile_jump;
-          if (++it == my_tiles) ip = (wptr_t)a.Wp;
         }
+        if (--to_issue == 0) ip = (wptr_t)a.Wp;
       }
     };
 
@@ -772,12 +796,89 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
         rsb[i] = *reinterpret_cast<const float4*>(&s_rowscale[32 + 8 * i + rbase]);
       }
     }
-    int ct = 0, cj = 0;                                  // piece being consumed: tile count, piece
-    int steps_left = my_tiles * np;                      // single-chunk form: every wave walks its own tiles
+    int ct = 0, cj = cj0;                                // piece being consumed: tile count, piece
+    int steps_left = n_run;                              // single-chunk form: every wave walks its own run
+    bool fresh = true;                                   // the accumulators hold nothing of the current tile yet
+    bool head_pending = cj0 > 0;                         // the run starts inside a tile: its sum goes to the wave before
     // partial tile of this wave's current tile and this slice (data, inverse scale)
-    const size_t pidx0 = ((size_t)mt * n_tiles + t_begin + wave) * S + sp;
+    const size_t pidx0 = ((size_t)mt * n_tiles + t_begin + ft) * S + sp;
     const uint4* pt = a.part16 + pidx0 * kTileVec4 + lane;
     const float* ps = a.pscale + pidx0;
+
+    // A finished tile goes out (called at the tile's last piece, or after the loop for a tile
+    // shared with the next wave).
+    auto finish_tile = [&]() {
+      // Tile finished.  The partial tile goes out in register order as scaled int16 pairs
+      // (each store instruction writes 1 KiB contiguous); the reducer reads it back with
+      // the same lane -> register mapping.  Register r of lane l is row
+      // 8*(r/4) + 4*(l/32) + r%4 (+32 for acc1), column l % 32 of the [64][32] tile.
+      // The stores are issued from inline assembly on purpose: the compiler's wait-count
+      // bookkeeping then sees loads only and keeps its waits exact; a store it knew of would
+      // turn every later wait into a drain of the whole ring.  Unseen stores can only make
+      // its waits longer, never too short; their own completion is awaited explicitly
+      // before the arrival below.
+      float t0[16], t1[16];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float4 ra = make_float4(1.f, 1.f, 1.f, 1.f), rb = ra;
+        if (PRO == PRO_GAIN) {                     // rows brought to a common size
+          ra = MULTI ? *reinterpret_cast<const float4*>(&s_rowscale[8 * i + rbase]) : rsa[i];
+          rb = MULTI ? *reinterpret_cast<const float4*>(&s_rowscale[32 + 8 * i + rbase]) : rsb[i];
+        }
+        t0[4 * i] = acc0[4 * i] * ra.x;         t1[4 * i] = acc1[4 * i] * rb.x;
+        t0[4 * i + 1] = acc0[4 * i + 1] * ra.y; t1[4 * i + 1] = acc1[4 * i + 1] * rb.y;
+        t0[4 * i + 2] = acc0[4 * i + 2] * ra.z; t1[4 * i + 2] = acc1[4 * i + 2] * rb.z;
+        t0[4 * i + 3] = acc0[4 * i + 3] * ra.w; t1[4 * i + 3] = acc1[4 * i + 3] * rb.w;
+      }
+      unsigned tmax = 0u;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const unsigned m0_ = mag_bits(t0[r]), m1_ = mag_bits(t1[r]);
+        const unsigned mm = m0_ > m1_ ? m0_ : m1_;
+        tmax = tmax > mm ? tmax : mm;
+      }
+      unsigned wmax = wave_max_u32(tmax);
+      const bool clean = wmax < kInfBits;
+      if (!clean) {                                // rare: the maximum of the finite elements
+        tmax = 0u;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const unsigned m0_ = finite_mag_bits(t0[r]), m1_ = finite_mag_bits(t1[r]);
+          const unsigned mm = m0_ > m1_ ? m0_ : m1_;
+          tmax = tmax > mm ? tmax : mm;
+        }
+        wmax = wave_max_u32(tmax);
+      }
+      float psc, pinv;
+      partial_tile_scale(wmax, psc, pinv);
+      u32x4_t dq[4];
+      if (clean) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int r = 8 * (q & 1) + 2 * e;     // register inside acc0 (q < 2) or acc1
+            dq[q][e] = q < 2 ? pack_q16x2(t0[r], t0[r + 1], psc) : pack_q16x2(t1[r], t1[r + 1], psc);
+          }
+      } else {
+        pinv = -pinv;                              // tells the reader to look for the code
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int r = 8 * (q & 1) + 2 * e;
+            dq[q][e] = q < 2 ? pack_q16x2_coded(t0[r], t0[r + 1], psc) : pack_q16x2_coded(t1[r], t1[r + 1], psc);
+          }
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const u32x4_t d = dq[q];
+        // s_nop: a store of more than 64 bits reads its data registers a few cycles after
+        // issue; the compiler cannot see that this is a store, so the wait states are explicit
+        asm volatile("global_store_dwordx4 %0, %1, off\n\ts_nop 3" ::"v"(pt + q * 64), "v"(d) : "memory");
+      }
+      if (lane == 0) asm volatile("global_store_dword %0, %1, off" ::"v"(ps), "v"(pinv) : "memory");
+    };
 
     // One step: the piece in `buf` (piece cj of this wave's current tile) is multiplied and the
     // slot is refilled.  The loop is compute bound at one wave per SIMD, so the bookkeeping
@@ -788,7 +889,7 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
       if (MULTI || steps_left > 0) {
         --steps_left;
         const int jq = cj & 3;
-        if (ct < my_tiles) {
+        if (!MULTI || ct < my_tiles) {
           const uint4* xf = xs + (size_t)(jq * kPieceFrags * 4) * 64;
           // One basic block per piece: 32 LDS reads and 32 MFMAs.  The schedule is pinned so
           // that the four X operands of fragment f + 1 are read while the MFMAs of fragment f
@@ -837,80 +938,27 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
             }
             __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
           };
-          if (cj == 0) piece_block(std::true_type{}); else piece_block(std::false_type{});
+          if (MULTI ? cj == 0 : fresh) piece_block(std::true_type{}); else piece_block(std::false_type{});
+          fresh = false;
           if (cj == np - 1) {
-            // Tile finished.  The partial tile goes out in register order as scaled int16 pairs
-            // (each store instruction writes 1 KiB contiguous); the reducer reads it back with
-            // the same lane -> register mapping.  Register r of lane l is row
-            // 8*(r/4) + 4*(l/32) + r%4 (+32 for acc1), column l % 32 of the [64][32] tile.
-            // The stores are issued from inline assembly on purpose: the compiler's wait-count
-            // bookkeeping then sees loads only and keeps its waits exact; a store it knew of would
-            // turn every later wait into a drain of the whole ring.  Unseen stores can only make
-            // its waits longer, never too short; their own completion is awaited explicitly
-            // before the arrival below.
-            float t0[16], t1[16];
+            if (!MULTI && head_pending) {
+              // the tile's first pieces belong to the wave before this one: it adds these sums
+              // to its own after the loop and stores the tile
+              head_pending = false;
+              uint4* h = s_head + (size_t)(wave - 1) * 8 * 64 + lane;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              float4 ra = make_float4(1.f, 1.f, 1.f, 1.f), rb = ra;
-              if (PRO == PRO_GAIN) {                     // rows brought to a common size
-                ra = MULTI ? *reinterpret_cast<const float4*>(&s_rowscale[8 * i + rbase]) : rsa[i];
-                rb = MULTI ? *reinterpret_cast<const float4*>(&s_rowscale[32 + 8 * i + rbase]) : rsb[i];
+              for (int q = 0; q < 4; ++q) {
+                const f32x4_t lo4 = {acc0[4 * q], acc0[4 * q + 1], acc0[4 * q + 2], acc0[4 * q + 3]};
+                const f32x4_t hi4 = {acc1[4 * q], acc1[4 * q + 1], acc1[4 * q + 2], acc1[4 * q + 3]};
+                h[q * 64] = __builtin_bit_cast(uint4, lo4);
+                h[(4 + q) * 64] = __builtin_bit_cast(uint4, hi4);
               }
-              t0[4 * i] = acc0[4 * i] * ra.x;         t1[4 * i] = acc1[4 * i] * rb.x;
-              t0[4 * i + 1] = acc0[4 * i + 1] * ra.y; t1[4 * i + 1] = acc1[4 * i + 1] * rb.y;
-              t0[4 * i + 2] = acc0[4 * i + 2] * ra.z; t1[4 * i + 2] = acc1[4 * i + 2] * rb.z;
-              t0[4 * i + 3] = acc0[4 * i + 3] * ra.w; t1[4 * i + 3] = acc1[4 * i + 3] * rb.w;
-            }
-            unsigned tmax = 0u;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const unsigned m0_ = mag_bits(t0[r]), m1_ = mag_bits(t1[r]);
-              const unsigned mm = m0_ > m1_ ? m0_ : m1_;
-              tmax = tmax > mm ? tmax : mm;
-            }
-            unsigned wmax = wave_max_u32(tmax);
-            const bool clean = wmax < kInfBits;
-            if (!clean) {                                // rare: the maximum of the finite elements
-              tmax = 0u;
-#pragma unroll
-              for (int r = 0; r < 16; ++r) {
-                const unsigned m0_ = finite_mag_bits(t0[r]), m1_ = finite_mag_bits(t1[r]);
-                const unsigned mm = m0_ > m1_ ? m0_ : m1_;
-                tmax = tmax > mm ? tmax : mm;
-              }
-              wmax = wave_max_u32(tmax);
-            }
-            float psc, pinv;
-            partial_tile_scale(wmax, psc, pinv);
-            u32x4_t dq[4];
-            if (clean) {
-#pragma unroll
-              for (int q = 0; q < 4; ++q)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                  const int r = 8 * (q & 1) + 2 * e;     // register inside acc0 (q < 2) or acc1
-                  dq[q][e] = q < 2 ? pack_q16x2(t0[r], t0[r + 1], psc) : pack_q16x2(t1[r], t1[r + 1], psc);
-                }
             } else {
-              pinv = -pinv;                              // tells the reader to look for the code
-#pragma unroll
-              for (int q = 0; q < 4; ++q)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                  const int r = 8 * (q & 1) + 2 * e;
-                  dq[q][e] = q < 2 ? pack_q16x2_coded(t0[r], t0[r + 1], psc) : pack_q16x2_coded(t1[r], t1[r + 1], psc);
-                }
+              finish_tile();
             }
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              const u32x4_t d = dq[q];
-              // s_nop: a store of more than 64 bits reads its data registers a few cycles after
-              // issue; the compiler cannot see that this is a store, so the wait states are explicit
-              asm volatile("global_store_dwordx4 %0, %1, off\n\ts_nop 3" ::"v"(pt + q * 64), "v"(d) : "memory");
-            }
-            if (lane == 0) asm volatile("global_store_dword %0, %1, off" ::"v"(ps), "v"(pinv) : "memory");
-            ps += 4 * S;
-            pt += (size_t)4 * S * kTileVec4;             // this wave's next tile
+            fresh = true;
+            ps += (MULTI ? 4 : 1) * S;
+            pt += (size_t)(MULTI ? 4 : 1) * S * kTileVec4;   // this wave's next tile
           }
         }
         if (++cj == np) {
@@ -944,6 +992,23 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
       while (steps_left > 0) {
 #pragma unroll
         for (int sl = 0; sl < kRing; ++sl) step(ring[sl]);
+      }
+      // tiles shared by two waves: every wave has left the loop, the sums of the later pieces
+      // are in LDS
+      asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+      if (cj != 0) {                                     // the run ended inside a tile
+        const uint4* h = s_head + (size_t)wave * 8 * 64 + lane;   // written by wave + 1
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const f32x4_t lo4 = __builtin_bit_cast(f32x4_t, h[q * 64]);
+          const f32x4_t hi4 = __builtin_bit_cast(f32x4_t, h[(4 + q) * 64]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            acc0[4 * q + e] += lo4[e];
+            acc1[4 * q + e] += hi4[e];
+          }
+        }
+        finish_tile();
       }
     }
 

@@ -46,6 +46,15 @@ def row_rel_err(gpu, ref):
     return num / den
 
 
+def same_up_to_rounding(a, b, tol=1e-3):
+    """NaNs in the same places, and every row within tol of the other's (max |diff| / max |b|)."""
+    if not np.array_equal(np.isnan(a), np.isnan(b)):
+        return False
+    a0, b0 = np.nan_to_num(a), np.nan_to_num(b)
+    scale = np.maximum(np.max(np.abs(b0), axis=-1, keepdims=True), 1e-30)
+    return bool(np.all(np.abs(a0 - b0) <= tol * scale))
+
+
 class SideBySide:
     """Outputs of one configuration from both sides."""
 
@@ -114,8 +123,8 @@ class SideBySide:
         self.gpu_logits = self.gpu.logits.cpu().numpy()
         self.gpu_token = self.gpu.token.cpu().numpy()
         self.gpu_x = self.gpu.x.cpu().numpy()
-        # the three routes do the same arithmetic in the same order: sv_verify_layer calls,
-        # sv_verify_stack, and (where it applies) the single persistent launch
+        # sv_verify_layer calls and sv_verify_stack issue the same kernels (bit-identical);
+        # the single persistent launch (where it applies) does the same arithmetic
         if x_layer_calls is not None:
             assert np.array_equal(self.gpu_x, x_layer_calls.cpu().numpy(), equal_nan=True), \
                 "stack and per-layer routes differ"
@@ -124,9 +133,16 @@ class SideBySide:
             try:
                 self.gpu.forward(want_logits=True, route="persistent")
                 torch.cuda.synchronize()
-                assert np.array_equal(self.gpu.x.cpu().numpy(), self.gpu_x, equal_nan=True), \
-                    "persistent route differs"
-                assert np.array_equal(self.gpu.logits.cpu().numpy(), self.gpu_logits, equal_nan=True)
+                # (the single launch adds the K pieces of a tile in one run, the layer kernels
+                # may split a tile's pieces between two waves: float32 rounding and a step of
+                # the 16-bit partial tiles apart per product, which grows with depth like any
+                # rounding difference - so this route is held to the oracle, as the other is,
+                # in check_forward; here only a coarse guard against a wrong result)
+                px, pl = self.gpu.x.cpu().numpy(), self.gpu.logits.cpu().numpy()
+                assert same_up_to_rounding(px, self.gpu_x, tol=2e-2), "persistent route differs"
+                assert same_up_to_rounding(pl, self.gpu_logits, tol=2e-2)
+                self.persistent_x_err = np.nanmax(row_rel_err(px, self.ref_x))
+                self.persistent_logit_err = np.nanmax(row_rel_err(pl, self.ref_logits))
                 self.persistent_checked = True
             except sv.SvError as e:
                 if e.status != sv.SV_ERR_SHAPE:

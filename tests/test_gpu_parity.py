@@ -32,6 +32,9 @@ def check_forward(s, tol, tie_frac_cap=0.25, attn_tol=None):
         assert max(s.attn_err) <= (tol if attn_tol is None else attn_tol)
         assert max(s.x_err) <= tol
     assert s.logit_err.max() <= tol
+    if s.persistent_checked:                 # the single-launch route against the oracle
+        say(f"[{name}] persistent route: x err {s.persistent_x_err:.3e}, logit err {s.persistent_logit_err:.3e}")
+        assert s.persistent_x_err <= tol and s.persistent_logit_err <= tol
     s.check_gpu_argmax_of_own_logits()
     ok, bad = s.tolerated_ties(tol)
     say(f"[{name}] tokens differing from the oracle: {ok} tolerated near-ties, {bad} others, "
