@@ -270,8 +270,15 @@ __global__ __launch_bounds__(64 * NW) void tree_attention_mfma(
   // per wave: transposed V tile [128 d][32 keys] with padded rows; reused for the merge
   __shared__ __attribute__((aligned(16))) unsigned char lds_raw[NW * 128 * kVtPitch];
   __shared__ float s_m[NW][kAttQ], s_l[NW][kAttQ];
+  // Workgroups are dealt to the XCDs in turn (linear index modulo 8), and each XCD has its own
+  // L2: the tasks are renumbered so that an XCD gets a contiguous run of (head, query tile)
+  // pairs - the query tiles of one head then read that head's K/V through one L2 instead of
+  // fetching it from HBM once per XCD.
+  const unsigned total = gridDim.x * gridDim.y, lin = blockIdx.x + gridDim.x * blockIdx.y;
+  const unsigned task = (total & 7u) ? lin : (lin & 7u) * (total >> 3) + (lin >> 3);
+  const unsigned head = task / gridDim.x;
   tree_attention_body<NW, false>(q, kc, vc, prefix_len, p_max, anc, n_words, T, nh, cap, out,
-                                 (int)blockIdx.x, (int)blockIdx.y, lds_raw, s_m, s_l,
+                                 (int)(task - head * gridDim.x), (int)head, lds_raw, s_m, s_l,
                                  (int)threadIdx.x, [] { __syncthreads(); });
 }
 
