@@ -25,7 +25,10 @@ namespace sv {
 
 constexpr int kAttQ = 16;        // queries per workgroup
 constexpr int kAttKeys = 32;     // keys per tile
-constexpr int kVtPitch = 72;     // bytes per row of the transposed V tile (64 + pad, 8-byte aligned)
+constexpr int kVtPitch = 72;     // LDS per wave = 128 * kVtPitch bytes (V tile in the loop, merge buffer after it)
+constexpr int kVPitch = 272;     // bytes per key row of the V tile in LDS (128 bf16 + 16 bytes so that rows spread over the banks)
+static_assert(kAttKeys * kVPitch <= 128 * kVtPitch, "V tile must fit the wave's LDS share");
+typedef short i16x4_t __attribute__((ext_vector_type(4)));
 constexpr float kNegBig = -1.0e30f;
 
 // 16-byte load from global memory (also when the compiler cannot tell where the pointer points)
@@ -102,7 +105,9 @@ __device__ inline void tree_attention_body(
     const int key0 = t * kAttKeys;
 #pragma unroll
     for (int st = 0; st < 2; ++st) {
-      const int key = min(key0 + 16 * st + c, nkeys - 1);
+      // row c of sub-tile st is key 8 * (c / 4) + 4 * st + c % 4 of the tile: a lane then holds
+      // the scores of keys 8g .. 8g+7, the order in which the second product takes them
+      const int key = min(key0 + 8 * (c >> 2) + 4 * st + (c & 3), nkeys - 1);
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks)
         kreg[st * 4 + ks] = ld_global_u4(kbase + (size_t)key * 128 + 32 * ks + 8 * g);
@@ -133,31 +138,10 @@ __device__ inline void tree_attention_body(
       s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, ql[ks], s0, 0, 0, 0);
       s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, ql[ks], s1, 0, 0, 0);
     }
-    // ---- V tile -> LDS, transposed, two keys per 32-bit store ----
-    // The lane holds V[key 4i+g][8c .. 8c+7]; the lane 16 further (group g^1) holds the
-    // neighbouring key.  After one exchange each of the two has both rows; the even group
-    // writes elements 0..3, the odd group elements 4..7, as (even key | odd key << 16).
+    // ---- V tile -> LDS as loaded: row = key, the lane's 8 elements of key 4i + g ----
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      // the gfx950 row swap of a value with itself returns what the even lane groups hold and
-      // what the odd ones hold - the two rows, in both lanes of the pair, without a trip through LDS
-      const uint4 mine = vreg[i];
-      const auto sx = __builtin_amdgcn_permlane16_swap(mine.x, mine.x, false, false);
-      const auto sy = __builtin_amdgcn_permlane16_swap(mine.y, mine.y, false, false);
-      const auto sz = __builtin_amdgcn_permlane16_swap(mine.z, mine.z, false, false);
-      const auto sw = __builtin_amdgcn_permlane16_swap(mine.w, mine.w, false, false);
-      const bool odd = g & 1;
-      const uint4 ev = make_uint4(sx[0], sy[0], sz[0], sw[0]);   // row of key 4i + (g & ~1)
-      const uint4 od = make_uint4(sx[1], sy[1], sz[1], sw[1]);   // row of key 4i + (g | 1)
-      // the two 32-bit words (= 4 elements) this lane transposes
-      const unsigned e_w0 = odd ? ev.z : ev.x, e_w1 = odd ? ev.w : ev.y;
-      const unsigned o_w0 = odd ? od.z : od.x, o_w1 = odd ? od.w : od.y;
-      unsigned char* dst = vt + (8 * c + (odd ? 4 : 0)) * kVtPitch + (4 * i + (g & ~1)) * 2;
-      *reinterpret_cast<unsigned*>(dst) = (e_w0 & 0xffffu) | (o_w0 << 16);
-      *reinterpret_cast<unsigned*>(dst + kVtPitch) = (e_w0 >> 16) | (o_w0 & 0xffff0000u);
-      *reinterpret_cast<unsigned*>(dst + 2 * kVtPitch) = (e_w1 & 0xffffu) | (o_w1 << 16);
-      *reinterpret_cast<unsigned*>(dst + 3 * kVtPitch) = (e_w1 >> 16) | (o_w1 & 0xffff0000u);
-    }
+    for (int i = 0; i < 8; ++i)
+      *reinterpret_cast<uint4*>(vt + (4 * i + g) * kVPitch + 16 * c) = vreg[i];
     // prefetch the next tile of this wave while the rest of this one is computed
     const int tn = t + NW;
     const int key0 = t * kAttKeys;
@@ -175,7 +159,7 @@ __device__ inline void tree_attention_body(
     } else {
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const int kidx = key0 + 16 * (e >> 2) + 4 * g + (e & 3);
+        const int kidx = key0 + 8 * g + e;
         const int tn_ = kidx - P;
         bool vis = kidx < P;
         if (tn_ >= 0 && tn_ < T) vis = ((tn_ < 64 ? mask0 >> tn_ : mask1 >> (tn_ - 64)) & 1ull) != 0;
@@ -202,20 +186,25 @@ __device__ inline void tree_attention_body(
     split8(p, ph, pl);
 
     // ---- O^T = O^T * corr + V^T P^T ----
-    __builtin_amdgcn_s_waitcnt(0xc07f);      // lgkmcnt(0): this wave's V^T stores have landed
+    // V^T operand by the LDS transpose read of gfx950: the 16 lanes of a group address 4 key
+    // rows x 16 d columns (lane s: row s / 4, columns 4 * (s % 4) ..+3) and lane s receives
+    // column s of the four rows.  Two reads give the lane V[keys 8g .. 8g+7][d = 16 dt + c].
+    __builtin_amdgcn_s_waitcnt(0xc07f);      // lgkmcnt(0): this wave's V stores have landed
+    typedef __attribute__((address_space(3))) i16x4_t* lds_v4_t;
+    const unsigned char* vrow = vt + (8 * g + (c >> 2)) * kVPitch + 8 * (c & 3);
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) {
-      const unsigned char* row = vt + (16 * dt + c) * kVtPitch;
-      const uint2 va = *reinterpret_cast<const uint2*>(row + 8 * g);
-      const uint2 vb = *reinterpret_cast<const uint2*>(row + 32 + 8 * g);
-      const bf16x8_t v8 = __builtin_bit_cast(bf16x8_t, make_uint4(va.x, va.y, vb.x, vb.y));
+      const i16x4_t va = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4_t)(vrow + 32 * dt));
+      const i16x4_t vb = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4_t)(vrow + 32 * dt + 4 * kVPitch));
+      const uint2 va2 = __builtin_bit_cast(uint2, va), vb2 = __builtin_bit_cast(uint2, vb);
+      const bf16x8_t v8 = __builtin_bit_cast(bf16x8_t, make_uint4(va2.x, va2.y, vb2.x, vb2.y));
       f32x4_t acc = o[dt];
       acc[0] *= corr; acc[1] *= corr; acc[2] *= corr; acc[3] *= corr;
       acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v8, ph, acc, 0, 0, 0);
       acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v8, pl, acc, 0, 0, 0);
       o[dt] = acc;
     }
-    __builtin_amdgcn_s_waitcnt(0xc07f);      // V^T reads done before the next tile overwrites them
+    __builtin_amdgcn_s_waitcnt(0xc07f);      // V reads done before the next tile overwrites them
   }
 
   // ---- merge the waves ----
