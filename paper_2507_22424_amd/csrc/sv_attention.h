@@ -11,8 +11,10 @@
 //   * a K tile is a matrix-core operand as it sits in the cache (16 B per lane, no staging),
 //   * a lane owns one query column: the online-softmax state and the rescale are per lane,
 //   * the probabilities come out of the first product in exactly the register layout the
-//     second one wants (k-slot (g, e) of lane group g = key 4g+e of the first 16-key
-//     sub-tile for e < 4, of the second for e >= 4); only V is transposed through LDS.
+//     second one wants (the rows of the two 16-key sub-tiles are ordered so that k-slot
+//     (g, e) of lane group g is key 8g + e of the tile);
+//   * only V passes through LDS: stored as loaded (row = key), read back as the V^T operand
+//     with the transposing LDS read of gfx950 (ds_read_b64_tr_b16) - no register shuffles.
 // Queries and probabilities are split into hi + lo bf16 parts so that, with the exact bf16
 // keys and values, the result carries float32-level rounding only.
 #ifndef SV_ATTENTION_H
