@@ -22,7 +22,7 @@ HBM_PEAK_GBS = 8000.0
 # layer), from the two rocprofv3 --pmc runs summarised in profiles/c3_step_hbm_traffic.txt:
 # fetched (FETCH_SIZE x 2, calibrated with a 1 GiB copy) + written (WRITE_SIZE x 1):
 # gate/up 211.7 + 25.3, q/k/v 122.0 + 14.6, down 117.0 + 5.2, output 47.1 + 5.2 (MB).
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = (211.57 + 25.29 + 121.95 + 14.64 + 117.04 + 5.20 + 47.09 + 5.20) / 4 * 1e6
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = (211.68 + 25.30 + 121.97 + 14.64 + 117.04 + 5.20 + 47.08 + 5.20) / 4 * 1e6
 
 
 def log(msg):
