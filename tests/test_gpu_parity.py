@@ -369,6 +369,13 @@ def test_packed_head_small_shapes_and_ranges():
     _head_both_ways(1024, 2048, 192, [(1792, 2048), (0, 2048)], seed=13)
 
 
+def test_packed_head_tiles_shared_between_waves_with_short_k_slices():
+    """Many tiles per group and K slices of 2 and of 4 pieces: the waves' runs of pieces cut
+    through tiles (5 or 6 tiles per group over four waves), so tiles are summed from two waves."""
+    _head_both_ways(256, 44800, 20, [(0, 44800)], seed=15)
+    _head_both_ways(512, 45056, 70, [(0, 45056)], seed=16)
+
+
 def test_packed_head_7b_shape_action_rows_and_full_vocabulary():
     """H = 4096, V = 32000, 60 rows of very different size (the row scales of the partial tiles)."""
     scale = torch.tensor([10.0 ** ((i % 7) - 3) for i in range(60)])
