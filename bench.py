@@ -213,6 +213,11 @@ def main():
                      "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/c3_step_hbm_traffic.txt",
                      "bytes_per_launch_avg": weights_total / (4 * L),
                      "avg_launch_us": gemm_ms * 1e3 / (4 * L)},
+        # the K/V stream of the tree attention (prefix + tree rows of every head, once per layer)
+        "kv_stream": {"bound": "hbm", "kernel": "tree_attention_mfma", "bytes_per_launch": kv_bytes,
+                      "avg_launch_us": per_step_ms["attn"] * 1e3 / L,
+                      "achieved": kv_bytes * L / (per_step_ms["attn"] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                      "unit": "GB/s", "frac": kv_bytes * L / (per_step_ms["attn"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }
     if args.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
