@@ -157,6 +157,16 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
+    # spread of single steps (torch events on the same stream; one more pass of `steps` steps)
+    se = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(args.steps)]
+    for e0, e1 in se:
+        e0.record()
+        one_step()
+        e1.record()
+    torch.cuda.synchronize()
+    step_ms = sorted(e0.elapsed_time(e1) for e0, e1 in se)
+    pct = lambda q: step_ms[min(len(step_ms) - 1, int(q * len(step_ms)))]
     tokens_per_s = B * T / (dt / args.steps)
     accepted = vp.accepted_len.cpu().tolist()
     accepted_by_r = {}
@@ -219,6 +229,22 @@ def main():
                       "achieved": kv_bytes * L / (per_step_ms["attn"] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                       "unit": "GB/s", "frac": kv_bytes * L / (per_step_ms["attn"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }
+    # what a plain streaming read reaches on this GPU (sv_stream_read over 2 GiB, best of 5)
+    probe = torch.empty(1 << 31, dtype=torch.uint8, device="cuda").fill_(1)
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    best = float("inf")
+    for _ in range(6):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        sv.sv_stream_read(probe, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        best = min(best, e0.elapsed_time(e1))
+    ceiling = probe.numel() / (best * 1e-3) / 1e9
+    del probe
+    out["step_ms_p10_p50_p90"] = [pct(0.1), pct(0.5), pct(0.9)]
+    out["roofline"]["stream_read_measured"] = ceiling
+    out["roofline"]["frac_of_stream_read"] = gemm_gbs / ceiling
     if args.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)

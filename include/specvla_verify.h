@@ -281,6 +281,15 @@ int sv_action_head_argmax_packed(const sv_model_cfg *cfg, const void *packed_hea
                                  float *out_logits, void *workspace, size_t ws_bytes,
                                  void *stream);
 
+/* Measurement aid, no part of the verification path: reads `bytes` of device memory once with
+ * the access pattern of the weight stream (16-byte non-temporal loads, 1 KiB per wave and
+ * instruction, 8 KiB per wave in flight) and discards the data.  bench.py times it to report
+ * the streaming-read rate the GPU reaches next to its data-sheet HBM peak.
+ *   ptr: [device], 16-byte aligned, bytes a multiple of 16;  sink: [device] 16 bytes, 16-byte
+ *   aligned (written only for one data pattern in 2^96)
+ * SV_ERR_SHAPE for sizes or alignments outside that. */
+int sv_stream_read(const void *ptr, size_t bytes, void *sink, void *stream);
+
 /* Relaxed acceptance (Eq. 5, Alg. 1) over B trees and the longest accepted path.  Integer
  * only.  bin(t) = t - action_lo.  Node c >= 1 passes when draft_token[c] and
  * target_token[parent[c]] are both action tokens and |bin difference| <= r; r = 0 is strict

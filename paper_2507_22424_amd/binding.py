@@ -27,7 +27,7 @@ EXPORTS = ("sv_version", "sv_strerror", "sv_tree_build_masks", "sv_packed_layer_
            "sv_verify_layer",
            "sv_verify_layer_timed", "sv_verify_stack", "sv_verify_stack_persistent",
            "sv_action_head_argmax", "sv_packed_head_bytes", "sv_pack_head",
-           "sv_action_head_argmax_packed", "sv_relaxed_accept",
+           "sv_action_head_argmax_packed", "sv_stream_read", "sv_relaxed_accept",
            "sv_commit_path", "sv_advance_prefix", "sv_tree_build_device")
 SV_N_TIMING_EVENTS = 9
 SV_TIMELINE_SLOTS = 16
@@ -107,6 +107,7 @@ def lib() -> C.CDLL:
         l.sv_action_head_argmax_packed.argtypes = [C.POINTER(ModelCfg), C.c_void_p, C.c_void_p, C.c_int,
                                                    C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                                                    C.c_size_t, C.c_void_p]
+        l.sv_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         l.sv_relaxed_accept.argtypes = [C.POINTER(Tree), C.c_void_p, C.c_void_p, C.c_int, C.c_int,
                                         C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -325,6 +326,14 @@ def sv_action_head_argmax_packed(cfg: ModelCfg, packed_head: torch.Tensor, x: to
         n_rows, vocab_lo, vocab_hi, _dev(out_token, torch.int32, "out_token"),
         _dev(out_logits, torch.float32, "out_logits"), _dev(workspace, torch.uint8, "workspace"),
         workspace.numel(), _stream(stream)), "sv_action_head_argmax_packed")
+
+
+def sv_stream_read(buf: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    """Measurement aid: one streaming read of `buf` (any dtype, contiguous, on the device)."""
+    if not buf.is_cuda or not buf.is_contiguous():
+        raise ValueError("buf must be a contiguous device tensor")
+    _check(lib().sv_stream_read(buf.data_ptr(), buf.numel() * buf.element_size(),
+                                _dev(sink, torch.uint8, "sink"), _stream(stream)), "sv_stream_read")
 
 
 def sv_relaxed_accept(tree: Tree, draft_token: torch.Tensor, target_token: torch.Tensor,

@@ -797,6 +797,17 @@ int sv_action_head_argmax_packed(const sv_model_cfg* cfg, const void* packed_hea
                      out_logits, (char*)workspace, (hipStream_t)stream);
 }
 
+int sv_stream_read(const void* ptr, size_t bytes, void* sink, void* stream) {
+  if (!ptr || !sink) return SV_ERR_NULL;
+  if (bytes < 16 || (bytes % 16) || ((uintptr_t)ptr % 16) || ((uintptr_t)sink % 16)) return SV_ERR_SHAPE;
+  const size_t n_vec = bytes / 16;
+  size_t blocks = (n_vec + 2047) / 2048;               // 8 KiB per wave and round
+  if (blocks > 2048) blocks = 2048;                    // 8 workgroups per CU walk the buffer
+  stream_read_kernel<<<(unsigned)blocks, 256, 0, (hipStream_t)stream>>>((const u32x4_t*)ptr, n_vec,
+                                                                       (u32x4_t*)sink);
+  return launch_status();
+}
+
 int sv_relaxed_accept(const sv_tree* tree, const int32_t* draft_token,
                       const int32_t* target_token, int action_lo, int n_bins, int r, int B,
                       int d_cap, uint8_t* accept_mask, int32_t* accepted_len,

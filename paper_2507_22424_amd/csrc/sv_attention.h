@@ -28,8 +28,13 @@ namespace sv {
 constexpr int kAttQ = 16;        // queries per workgroup
 constexpr int kAttKeys = 32;     // keys per tile
 constexpr int kVtPitch = 72;     // LDS per wave = 128 * kVtPitch bytes (V tile in the loop, merge buffer after it)
-constexpr int kVPitch = 272;     // bytes per key row of the V tile in LDS (128 bf16 + 16 bytes so that rows spread over the banks)
-static_assert(kAttKeys * kVPitch <= 128 * kVtPitch, "V tile must fit the wave's LDS share");
+// V tile in LDS: 288 bytes per key row (a row starts 8 banks after the one before), and rows
+// 8..15 of every 16 hold their two 128-byte halves swapped: the 32 lanes that read together
+// (keys 8g .. 8g+3 or +4 .. +7 of two lane groups, 32 bytes each) then hit 64 different banks.
+constexpr int kVPitch = 288;
+constexpr int kMergePitch = kAttQ + 1;   // floats per d row of the merge buffer (odd: the readers' rows fall on different banks)
+static_assert(kAttKeys * kVPitch <= 128 * kVtPitch && 128 * kMergePitch * 4 <= 128 * kVtPitch,
+              "V tile and merge rows must fit the wave's LDS share");
 typedef short i16x4_t __attribute__((ext_vector_type(4)));
 constexpr float kNegBig = -1.0e30f;
 
@@ -143,7 +148,7 @@ __device__ inline void tree_attention_body(
     // ---- V tile -> LDS as loaded: row = key, the lane's 8 elements of key 4i + g ----
 #pragma unroll
     for (int i = 0; i < 8; ++i)
-      *reinterpret_cast<uint4*>(vt + (4 * i + g) * kVPitch + 16 * c) = vreg[i];
+      *reinterpret_cast<uint4*>(vt + (4 * i + g) * kVPitch + ((16 * c) ^ (((4 * i + g) & 8) << 4))) = vreg[i];
     // prefetch the next tile of this wave while the rest of this one is computed
     const int tn = t + NW;
     const int key0 = t * kAttKeys;
@@ -194,10 +199,12 @@ __device__ inline void tree_attention_body(
     __builtin_amdgcn_s_waitcnt(0xc07f);      // lgkmcnt(0): this wave's V stores have landed
     typedef __attribute__((address_space(3))) i16x4_t* lds_v4_t;
     const unsigned char* vrow = vt + (8 * g + (c >> 2)) * kVPitch + 8 * (c & 3);
+    const int half_swap = 128 * (g & 1);     // rows 8 .. 15 of each 16: halves swapped
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) {
-      const i16x4_t va = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4_t)(vrow + 32 * dt));
-      const i16x4_t vb = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4_t)(vrow + 32 * dt + 4 * kVPitch));
+      const unsigned char* vcol = vrow + 32 * dt + (dt < 4 ? half_swap : -half_swap);
+      const i16x4_t va = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4_t)vcol);
+      const i16x4_t vb = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4_t)(vcol + 4 * kVPitch));
       const uint2 va2 = __builtin_bit_cast(uint2, va), vb2 = __builtin_bit_cast(uint2, vb);
       const bf16x8_t v8 = __builtin_bit_cast(bf16x8_t, make_uint4(va2.x, va2.y, vb2.x, vb2.y));
       f32x4_t acc = o[dt];
@@ -211,7 +218,7 @@ __device__ inline void tree_attention_body(
 
   // ---- merge the waves ----
   sync();
-  float* om = reinterpret_cast<float*>(lds_raw);          // [NW waves][128 d][16 q] float32
+  float* om = reinterpret_cast<float*>(lds_raw);          // [NW waves][128 d][kMergePitch] float32 (16 q used)
   if (g == 0) {
     s_m[wave][c] = m_run;
     s_l[wave][c] = l_run;
@@ -219,7 +226,7 @@ __device__ inline void tree_attention_body(
 #pragma unroll
   for (int dt = 0; dt < 8; ++dt)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) om[(wave * 128 + 16 * dt + 4 * g + r) * kAttQ + c] = o[dt][r];
+    for (int r = 0; r < 4; ++r) om[(wave * 128 + 16 * dt + 4 * g + r) * kMergePitch + c] = o[dt][r];
   sync();
   // the first four waves finish d rows 32w .. 32w+31: lane -> (d = 32w + lane % 32, queries
   // (lane / 32) * 8 .. + 7)
@@ -235,7 +242,7 @@ __device__ inline void tree_attention_body(
 #pragma unroll
       for (int w = 0; w < NW; ++w) {
         const float sc = __expf(s_m[w][qq] - m_all);
-        num += sc * om[(w * 128 + d) * kAttQ + qq];
+        num += sc * om[(w * 128 + d) * kMergePitch + qq];
         den += sc * s_l[w][qq];
       }
       const int tnode = qb * kAttQ + qq;

@@ -359,6 +359,31 @@ __global__ __launch_bounds__(256) void argmax_rows_wide(const float* __restrict_
 }
 
 // ---------------------------------------------------------------------------------------
+// Measurement aid: reads a buffer once the way the GEMM streams weights (non-temporal 16-byte
+// loads, 1 KiB per wave and instruction, 8 KiB per wave in flight) and discards the data.
+// grid = any, block = 256.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4_t* __restrict__ p, size_t n_vec,
+                                                          u32x4_t* __restrict__ sink) {
+  typedef const __attribute__((address_space(1))) u32x4_t* gptr_t;
+  const gptr_t g = (gptr_t)p;
+  const size_t lane = threadIdx.x & 63;
+  const size_t n_waves = (size_t)gridDim.x * 4;
+  u32x4_t acc = {0u, 0u, 0u, 0u};
+  for (size_t blk = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6); blk * 512 < n_vec; blk += n_waves) {
+    u32x4_t v[8];
+#pragma unroll
+    for (int f = 0; f < 8; ++f) {
+      const size_t i = blk * 512 + f * 64 + lane;
+      v[f] = __builtin_nontemporal_load(g + (i < n_vec ? i : n_vec - 1));
+    }
+#pragma unroll
+    for (int f = 0; f < 8; ++f) acc ^= v[f];
+  }
+  if (acc[0] == 0x9e3779b9u && acc[1] == 0x7f4a7c15u && acc[2] == 0xf39cc060u) *sink = acc;   // keeps the loads
+}
+
+// ---------------------------------------------------------------------------------------
 // Packers (load time).  pack_gain widens a gain vector to float32; pack_rows_plain copies
 // a [rows, K] matrix behind `row_off` rows of the destination.
 // ---------------------------------------------------------------------------------------

@@ -382,6 +382,18 @@ def test_packed_head_7b_shape_action_rows_and_full_vocabulary():
     _head_both_ways(4096, 32000, 60, [(32000 - 256, 32000), (0, 32000)], seed=14, rows_scale=scale)
 
 
+def test_stream_read_aid_runs_on_ragged_sizes_and_leaves_memory_alone():
+    """The measurement aid reads and discards: sizes that are not a multiple of its 8 KiB rounds,
+    a buffer smaller than one round, and the buffer and sink unchanged afterwards."""
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    for n in (16, 8192 - 16, 8192 * 5 + 48, (1 << 24) + 16):
+        buf = torch.arange(n, dtype=torch.int64, device="cuda").to(torch.uint8)
+        keep = buf.clone()
+        sv.sv_stream_read(buf, sink)
+        torch.cuda.synchronize()
+        assert torch.equal(buf, keep) and int(sink.sum()) == 0
+
+
 def test_graph_replays_match_host_launched_steps():
     """One step recorded into a HIP graph and replayed: every replay - with new hidden rows and
     draft tokens written between replays, host-launched steps and synchronisations in between -

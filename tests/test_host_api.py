@@ -205,3 +205,14 @@ def test_packed_head_checks_its_arguments_before_any_launch():
                                             ws, None) == -2
     assert lib.sv_action_head_argmax_packed(C.byref(f32), one, one, 8, 768, 1024, one, None, one,
                                             ws, None) == -6
+
+
+def test_stream_read_checks_its_arguments_before_any_launch():
+    lib = sv.lib()
+    a = C.c_void_p(4096)
+    assert lib.sv_stream_read(None, 4096, a, None) == -1
+    assert lib.sv_stream_read(a, 4096, None, None) == -1
+    assert lib.sv_stream_read(a, 0, a, None) == -2
+    assert lib.sv_stream_read(a, 4100, a, None) == -2
+    assert lib.sv_stream_read(C.c_void_p(4100), 4096, a, None) == -2
+    assert lib.sv_stream_read(a, 4096, C.c_void_p(4104), None) == -2
