@@ -93,6 +93,10 @@ def main():
     ap.add_argument("--r", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers (invalid as a result)")
+    ap.add_argument("--config", choices=("C3", "C4", "C5"), default="C3",
+                    help="C3 is the benchmark workload; C4 (16 episodes) and C5 (prefix 2048, 128 "
+                         "nodes) are parity configurations that can be timed and profiled the "
+                         "same way (no CPU baseline, no stored traffic figure)")
     ap.add_argument("--weights", choices=("bf16", "w8"), default="bf16",
                     help="w8: the same workload with 8-bit (E4M3 + row scale) matrices, a variant "
                          "of its own: half the weight bytes, not the headline configuration")
@@ -113,17 +117,20 @@ def main():
     from paper_2507_22424_amd import workload as wl
     from paper_2507_22424_amd.runner import VerifyPass
 
-    cfg = wl.C3 if args.layers is None else wl.C3.scaled(n_layers=args.layers)
+    base = {"C3": wl.C3, "C4": wl.C4, "C5": wl.C5}[args.config]
+    cfg = base if args.layers is None else base.scaled(n_layers=args.layers)
     w8 = args.weights == "w8"
     if w8:
         cfg = cfg.scaled(dtype="bf16_w8")
-        args.no_cpu_baseline = True      # the baseline leg times the bf16 workload
+    if w8 or args.config != "C3":
+        args.no_cpu_baseline = True      # the baseline leg times the bf16 benchmark workload
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
     B, T, L = cfg.n_episodes, cfg.tree_nodes, cfg.n_layers
     prefix_len = wl.prefix_lengths(cfg)
-    parent = wl.episode_tree(cfg, 0)
-    vp = VerifyPass(cfg, prefix_len, parent)
+    parents = [wl.episode_tree(cfg, b) for b in range(B)]
+    parent = parents[0]
+    vp = VerifyPass(cfg, prefix_len, np.concatenate(parents))
 
     t0 = time.time()
     with ThreadPoolExecutor(max_workers=8) as ex:
@@ -131,18 +138,21 @@ def main():
         for l, f in enumerate(futs):
             vp.load_layer(l, f.result())
             futs[l] = None
-            k, v = wl.prefix_kv(cfg, 0, l, int(prefix_len[0]))
-            vp.load_prefix(l, 0, k, v)
+            for b in range(B):
+                k, v = wl.prefix_kv(cfg, b, l, int(prefix_len[b]))
+                vp.load_prefix(l, b, k, v)
             if l % 8 == 7:
                 log(f"bench: {l + 1}/{L} layers resident ({time.time() - t0:.0f}s)")
     head = wl.head_weights(cfg)
     vp.load_head(head["g_final"], head["w_lm"])
-    vp.set_hidden(wl.hidden_rows(cfg, 0))
+    vp.set_hidden(torch.cat([wl.hidden_rows(cfg, b) for b in range(B)]))
 
     # draft ids within +-8 bins of the verifier's own choice (two-phase: one untimed forward)
     vp.forward(want_logits=False)
     torch.cuda.synchronize()
-    vp.set_draft(wl.noisy_draft_tokens(cfg, 0, parent, vp.token.cpu().numpy()))
+    tok = vp.token.cpu().numpy()
+    vp.set_draft(np.concatenate([wl.noisy_draft_tokens(cfg, b, parents[b], tok[b * T:(b + 1) * T])
+                                 for b in range(B)]))
 
     # --launch graph: the step recorded once into a HIP graph and replayed (the same launches in
     # the same order)
@@ -197,9 +207,9 @@ def main():
     gemm_bytes = {"qkv": 3 * D * H * wb, "o": H * D * wb, "gate_up": 2 * F * H * wb, "down": H * F * wb}
     gemm_ms = sum(per_step_ms[k] for k in gemm_bytes)
     gemm_gbs = sum(gemm_bytes.values()) * L / (gemm_ms * 1e-3) / 1e9
-    kv_bytes = 2 * cfg.n_heads * (int(prefix_len[0]) + T) * cfg.head_dim * 2
+    kv_bytes = sum(2 * cfg.n_heads * (int(p) + T) * cfg.head_dim * 2 for p in prefix_len)   # all episodes, one layer
     weights_total = sum(gemm_bytes.values()) * L
-    step_bytes = weights_total + kv_bytes * L + cfg.n_bins * H * 2 + 2 * cfg.n_heads * T * cfg.head_dim * 2 * L
+    step_bytes = weights_total + kv_bytes * L + cfg.n_bins * H * 2 + 2 * cfg.n_heads * B * T * cfg.head_dim * 2 * L
 
     out = {
         "metric": "verified tree tokens/sec + step latency (7B-shaped, tree 60); % HBM peak",
@@ -208,10 +218,12 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16 (8-bit E4M3 weights)" if w8 else "bf16",
         "data": "synthetic",
-        "config": {"workload": f"C3: {L}-layer 7B-shaped verify pass + 256-bin action head + "
+        "config": {"workload": f"{args.config}: {L}-layer 7B-shaped verify pass + 256-bin action head + "
                                f"relaxed accept (r={args.r}), tree {T} nodes depth 7, prefix "
-                               f"{int(prefix_len[0])}, 1 episode" + (", 8-bit weights" if w8 else ""),
+                               f"{int(prefix_len.min())}" + (f"..{int(prefix_len.max())}" if B > 1 else "") +
+                               f", {B} episode" + ("s" if B > 1 else "") + (", 8-bit weights" if w8 else ""),
                    "hidden": H, "layers": L, "tree_nodes": T, "prefix": int(prefix_len[0]),
+                   "episodes": B,
                    "launch": "HIP graph replay" if graph is not None else "host launches"},
         "step_hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "step_algorithmic_bytes": step_bytes,
@@ -219,7 +231,8 @@ def main():
         "kernel_ms_per_step": per_step_ms,
         "roofline": {"bound": "hbm", "kernel": "gemm_stream_bf16 (4 launches per layer: q/k/v, o, gate/up, down)",
                      "achieved": gemm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": gemm_gbs / HBM_PEAK_GBS, "traffic": None if w8 else GEMM_TRAFFIC_BYTES_PER_LAUNCH,
+                     "frac": gemm_gbs / HBM_PEAK_GBS,
+                     "traffic": None if (w8 or args.config != "C3") else GEMM_TRAFFIC_BYTES_PER_LAUNCH,
                      "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/c3_step_hbm_traffic.txt",
                      "bytes_per_launch_avg": weights_total / (4 * L),
                      "avg_launch_us": gemm_ms * 1e3 / (4 * L)},
