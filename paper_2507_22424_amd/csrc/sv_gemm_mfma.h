@@ -452,8 +452,8 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
 #pragma unroll
         for (int s2 = 0; s2 < 8; ++s2) part[bi][s2] = pb[(size_t)min(s2, S - 1) * (kTileVec4 * 2)];
         if (S == 8) {
-          // the eight scales of the tile in two loads (the load queue holds 63 requests: a batch
-          // of six items must not need more, or its loads go out in two rounds)
+          // the eight scales of the tile in two loads instead of eight (the load queue holds 63
+          // requests; batches of three items measured fastest, larger ones slower)
           typedef float f32x4a_t __attribute__((ext_vector_type(4)));
           const auto pv = (const __attribute__((address_space(1))) f32x4a_t*)(pscale + pidx);
           const f32x4a_t p0 = pv[0], p1 = pv[1];
