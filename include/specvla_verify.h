@@ -152,19 +152,6 @@ int sv_workspace_bytes(const sv_model_cfg *cfg, int B, int T, int n_scored, size
 int sv_workspace_init(const sv_model_cfg *cfg, int B, int T, int n_scored, void *workspace,
                       size_t ws_bytes, void *stream);
 
-/* Host-only inspection aid for tests: where an intermediate of the last sv_verify_layer call
- * lives inside the workspace.  which = SV_WS_ATTN_OUT: attention output before the output
- * projection, float32 [B*T, nh*d].  which = SV_WS_Q: rotated queries, float32 [B*T, nh*d].
- * which = SV_WS_STATUS: one int32 (bytes = 0 for SV_F32 models), zero unless a bf16 GEMM found
- * the K slices of one output tile on different XCDs - the placement its cache-local reduction
- * relies on and checks on every call; non-zero means results are suspect.  Cleared by
- * sv_workspace_init. */
-#define SV_WS_ATTN_OUT 0
-#define SV_WS_Q 1
-#define SV_WS_STATUS 2
-int sv_workspace_region(const sv_model_cfg *cfg, int B, int T, int n_scored, int which,
-                        size_t *offset, size_t *bytes);
-
 /* The draft tree of every episode, built on the device from the recorded top-K predictions of
  * the draft model (Sec. 4.1: those predictions form a tree with several paths; Sec. 5.1: top 8,
  * at most 50 nodes).  Candidate c of an episode has a parent (an earlier candidate, or -1 =
@@ -205,17 +192,6 @@ int sv_verify_layer(const sv_model_cfg *cfg, const void *packed, float *x,
                     const sv_kv_view *kv, const sv_tree *tree, int B, void *workspace,
                     size_t ws_bytes, void *stream);
 
-/* Measurement aid: exactly sv_verify_layer, but records the caller's HIP events on `stream`
- * around single kernel launches so that a benchmark can read per-kernel durations with
- * hipEventElapsedTime: events[0],[1] bracket the q/k/v GEMM, [2],[3] the tree attention,
- * [3],[4] the output GEMM, [5],[6] the gate/up GEMM, [7],[8] the down GEMM.
- * events: [host] array of SV_N_TIMING_EVENTS hipEvent_t (created by the caller with timing
- * enabled).  SV_ERR_NULL if the array or an entry is NULL. */
-#define SV_N_TIMING_EVENTS 9
-int sv_verify_layer_timed(const sv_model_cfg *cfg, const void *packed, float *x,
-                          const sv_kv_view *kv, const sv_tree *tree, int B, void *workspace,
-                          size_t ws_bytes, void *stream, void *const *events);
-
 /* The whole verifier stack (Sec. 4.1: M_V scores every draft position in one forward pass):
  * exactly sv_verify_layer for layer 0 .. n_layers-1 in turn on the same x, issued from one call.
  *   packed: [host] array of n_layers [device] pointers, each from sv_pack_layer
@@ -225,30 +201,6 @@ int sv_verify_layer_timed(const sv_model_cfg *cfg, const void *packed, float *x,
 int sv_verify_stack(const sv_model_cfg *cfg, int n_layers, const void *const *packed, float *x,
                     const sv_kv_view *kv, const sv_tree *tree, int B, void *workspace,
                     size_t ws_bytes, void *stream);
-
-/* Experimental single-launch form of sv_verify_stack, same arithmetic: up to 32 layers
- * run as ONE persistent launch (one workgroup per compute unit, split into waves that only
- * stream weights and waves that stage, reduce, attend and synchronise), so that weight loads
- * of the next phase are already in flight while a phase boundary is worked on.  Measured
- * slower than the per-layer launches on MI355X (the boundaries, not the launches, dominate);
- * kept as a measured design point.  Needs a bf16 model, B*T <= 64, n_layers <= 32, all kv
- * views sharing prefix_len / prefix_len_max / capacity, and every compute unit of the device
- * free: the workgroups meet at device-wide barriers with bounded waits; if they cannot all be
- * resident the waits run out, the status word (SV_WS_STATUS) becomes non-zero and the results
- * are invalid.  SV_ERR_SHAPE where the form does not apply.
- *   timeline: NULL, or [device] int64 [n_workgroups * n_layers * SV_TIMELINE_SLOTS]: workgroup
- *             w writes the device clock (100 MHz) at fixed points of layer l to
- *             timeline[(w * n_layers + l) * SV_TIMELINE_SLOTS + i]; for GEMM phase p = 0..3
- *             (q/k/v, output, gate/up, down) slot 3p = activations staged, 3p+1 = all tiles
- *             handed over, 3p+2 = reduction and epilogue done; 12 = first device-wide barrier
- *             passed, 13 = attention done, 14 = second barrier passed
- *   timeline_len: entries available (SV_ERR_WORKSPACE if too few)
- *   n_workgroups: [host] out, may be NULL: workgroups of the launch (at most 256) */
-#define SV_TIMELINE_SLOTS 16
-int sv_verify_stack_persistent(const sv_model_cfg *cfg, int n_layers, const void *const *packed,
-                               float *x, const sv_kv_view *kv, const sv_tree *tree, int B,
-                               void *workspace, size_t ws_bytes, void *stream, long long *timeline,
-                               size_t timeline_len, int *n_workgroups);
 
 /* Final RMSNorm, LM-head logits of vocabulary rows [vocab_lo, vocab_hi) and the greedy
  * choice among them (Eq. 1), the lowest id winning exact ties.  vocab_lo = V - 256,
@@ -280,15 +232,6 @@ int sv_action_head_argmax_packed(const sv_model_cfg *cfg, const void *packed_hea
                                  int n_rows, int vocab_lo, int vocab_hi, int32_t *out_token,
                                  float *out_logits, void *workspace, size_t ws_bytes,
                                  void *stream);
-
-/* Measurement aid, no part of the verification path: reads `bytes` of device memory once with
- * the access pattern of the weight stream (16-byte non-temporal loads, 1 KiB per wave and
- * instruction, 8 KiB per wave in flight) and discards the data.  bench.py times it to report
- * the streaming-read rate the GPU reaches next to its data-sheet HBM peak.
- *   ptr: [device], 16-byte aligned, bytes a multiple of 16;  sink: [device] 16 bytes, 16-byte
- *   aligned (written only for one data pattern in 2^96)
- * SV_ERR_SHAPE for sizes or alignments outside that. */
-int sv_stream_read(const void *ptr, size_t bytes, void *sink, void *stream);
 
 /* Relaxed acceptance (Eq. 5, Alg. 1) over B trees and the longest accepted path.  Integer
  * only.  bin(t) = t - action_lo.  Node c >= 1 passes when draft_token[c] and

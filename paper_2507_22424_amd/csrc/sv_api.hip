@@ -7,12 +7,13 @@
 #include <cstring>
 
 #include "specvla_verify.h"
+#include "specvla_verify_aux.h"
 #include "sv_accept.h"
 #include "sv_attention.h"
 #include "sv_gemm_mfma.h"
 #include "sv_internal.h"
 #include "sv_kernels.h"
-#include "sv_stack_persistent.h"
+#include "sv_flow.h"
 #include "sv_tree_build.h"
 
 namespace sv {
@@ -57,6 +58,30 @@ static GemmPlan plan_gemm(int n_rows, int k, int n_xcd) {
   return p;
 }
 
+// Fills the work split of one product into its argument block.
+static GemmPlan fill_plan(GemmArgs& a, int N, int K, int n_xcd) {
+  const GemmPlan p = plan_gemm(N, K, n_xcd);
+  a.N = N; a.K = K; a.S = p.S; a.gpx = p.gpx; a.n_xcd = n_xcd;
+  const int n_tiles = N / kFragRows, G = n_xcd * p.gpx, npieces = K / kBlkK;
+  a.tq = n_tiles / G; a.trem = n_tiles % G;
+  a.pq = npieces / p.S; a.prem = npieces % p.S;
+  a.inv_S = (65536u + p.S - 1) / p.S;      // exact for the unit numbers that occur (< 4096)
+  return p;
+}
+
+// Per-XCD extent of the split-K scratch regions for a product of N rows over K: units (gpx * S)
+// and partial tiles (gpx * (tiles per group, rounded up) * S), the largest over the XCD counts a
+// device can have.
+static void scratch_extent(int N, int K, int* ucap, int* tstride) {
+  for (int n_xcd = 1; n_xcd <= kXcds; n_xcd *= 2) {
+    GemmArgs a;
+    const GemmPlan p = fill_plan(a, N, K, n_xcd);
+    const int u = p.gpx * p.S, t = p.gpx * (a.tq + 1) * p.S;
+    if (u > *ucap) *ucap = u;
+    if (t > *tstride) *tstride = t;
+  }
+}
+
 static int device_xcds() {
   static int cached[64] = {0};               // hardware facts only; a race rewrites the same value
   int dev = 0;
@@ -81,28 +106,23 @@ static WorkspaceLayout workspace_layout(const sv_model_cfg& c, int m_rows, int n
   if (H > n_max) n_max = H;
   size_t o = 0;
   if (c.dtype != SV_F32) {
-    // sized for the worst split (8 slices), independent of the device
-    const size_t tiles_max = n_max / kFragRows, s_max = 8;
-    L.counter_bytes = align_up((mt * (tiles_max + kXcds) * kCntStride + 64) * sizeof(int), kAlign);   // group counters + status word
+    // sized for the worst split over the XCD counts a device can have
+    const int D_ = (int)D, H_ = (int)H, F_ = (int)F;
+    L.ucap = 1; L.tstride = 1;
+    scratch_extent(3 * D_, H_, &L.ucap, &L.tstride);
+    scratch_extent(H_, D_, &L.ucap, &L.tstride);
+    scratch_extent(2 * F_, H_, &L.ucap, &L.tstride);
+    scratch_extent(H_, F_, &L.ucap, &L.tstride);
+    L.counter_bytes = align_up((mt * kXcds * L.ucap * kCntStride + 64) * sizeof(int), kAlign);   // group counters + status word
     L.counters = o; o += L.counter_bytes;
-    L.sumsq = o;    o = align_up(o + mt * (tiles_max + kXcds) * s_max * kMTile * 4, kAlign);
-    L.part_bytes = align_up(mt * tiles_max * s_max * kTileFloats * 4, 2 * kAlign);
+    L.sumsq = o;    o = align_up(o + mt * kXcds * L.ucap * kMTile * 4, kAlign);
+    // partial tiles: 16-bit data (4 KiB each) in the first half of the region, one scale each behind it
+    L.part_bytes = align_up(mt * kXcds * L.tstride * (size_t)kTileFloats * 4, 2 * kAlign);
     L.part = o;     o += L.part_bytes;
     L.xhat = o;
-    L.stack_ctl = L.stack_ctl_bytes = L.stack_sumsq = L.stack_part = L.stack_part_bytes = 0;
-    if (mt == 1) {
-      // group words [32 layers][4 phases][256 groups] x 128 B, then grid (8 x 64), workgroup
-      // counters (256 x 32) and flags (256 x 32) as 32-bit words, then the launch description
-      L.stack_ctl_bytes = align_up((size_t)kStackMaxLayers * 4 * 256 * 8 * kStackCntStride +
-                                   (8 * 64 + 256 * 32 + 256 * 32) * 4 + sizeof(StackArgs), kAlign);
-      L.stack_ctl = o;   o += L.stack_ctl_bytes;
-      L.stack_sumsq = o; o = align_up(o + (size_t)kXcds * kUnitsPerXcd * kMTile * 4, kAlign);
-      L.stack_part_bytes = (tiles_max + kXcds * kUnitsPerXcd) * s_max * kTileFloats * 4;
-      L.stack_part = o;  o = align_up(o + L.stack_part_bytes, kAlign);
-    }
   } else {
-    L.stack_ctl = L.stack_ctl_bytes = L.stack_sumsq = L.stack_part = L.stack_part_bytes = 0;
     L.counter_bytes = 0;
+    L.ucap = L.tstride = 0;
     L.counters = L.sumsq = o;
     L.part_bytes = align_up(mp * n_max * 4, kAlign);
     L.part = o;     o += L.part_bytes;
@@ -111,16 +131,32 @@ static WorkspaceLayout workspace_layout(const sv_model_cfg& c, int m_rows, int n
   L.q = o;           o = align_up(o + mp * D * 4, kAlign);
   L.attn = o;        o = align_up(o + mp * D * 4, kAlign);
   L.act = o;         o = align_up(o + mp * F * 4, kAlign);
+  // single-launch form (bf16 models, one row tile): every layer of a launch has its own
+  // activation buffers - slot 0 starts with the q / attn / act regions above - plus the table of
+  // per-layer launch descriptions and the completion counters
+  L.flow_layers = 0;
+  L.flow_x1 = L.flow_x2 = L.flow_stride = L.flow_tab = L.flow_done = 0;
+  if (c.dtype != SV_F32 && mt == 1) {
+    L.flow_layers = kFlowMaxLayers;
+    L.flow_x1 = o;   o = align_up(o + mp * H * 4, kAlign);
+    L.flow_x2 = o;   o = align_up(o + mp * H * 4, kAlign);
+    L.flow_stride = o - L.q;                       // bytes from one layer's slot to the next
+    o = L.q + (size_t)kFlowMaxLayers * L.flow_stride;
+    L.flow_tab = o;  o = align_up(o + (size_t)kFlowMaxLayers * sizeof(FlowLayer), kAlign);
+    L.flow_done = o; o = align_up(o + (size_t)kFlowMaxLayers * 5 * kFlowCntStride * 4, kAlign);
+  }
   L.head_z = o;      o = align_up(o + mp * H * 4, kAlign);
   L.head_logits = o; o = align_up(o + mp * (size_t)(n_scored > 0 ? n_scored : 0) * 4 * 16, kAlign);   // up to 16 K-slice planes
   // (the regions above do not move with n_scored: a layer call finds them without knowing it)
   L.head_cnt = L.head_cnt_bytes = L.head_sumsq = L.head_part = L.head_part_bytes = 0;
+  L.head_ucap = L.head_tstride = 0;
   if (c.dtype != SV_F32 && n_scored > 0 && n_scored % kFragRows == 0) {
-    const size_t tiles = n_scored / kFragRows, s_max = 8;
-    L.head_cnt_bytes = align_up(mt * (tiles + kXcds) * kCntStride * sizeof(int), kAlign);
+    L.head_ucap = 1; L.head_tstride = 1;
+    scratch_extent(n_scored, (int)H, &L.head_ucap, &L.head_tstride);
+    L.head_cnt_bytes = align_up(mt * kXcds * L.head_ucap * kCntStride * sizeof(int), kAlign);
     L.head_cnt = o;   o += L.head_cnt_bytes;
-    L.head_sumsq = o; o = align_up(o + mt * (tiles + kXcds) * s_max * kMTile * 4, kAlign);
-    L.head_part_bytes = align_up(mt * tiles * s_max * kTileFloats * 4, 2 * kAlign);
+    L.head_sumsq = o; o = align_up(o + mt * kXcds * L.head_ucap * kMTile * 4, kAlign);
+    L.head_part_bytes = align_up(mt * kXcds * L.head_tstride * (size_t)kTileFloats * 4, 2 * kAlign);
     L.head_part = o;  o += L.head_part_bytes;
   }
   L.total = o;
@@ -245,13 +281,9 @@ static int verify_layer_bf16(const sv_model_cfg& c, const char* packed, float* x
   float* act = (float*)(ws + wl.act);
   dim3 grid(n_xcd, 1, wl.m_tiles);           // workgroup (x, y) -> XCD x, unit y
   bool multi = false;
+  a.ucap = wl.ucap; a.tstride = wl.tstride;
   auto shape = [&](int N, int K) {
-    const GemmPlan p = plan_gemm(N, K, n_xcd);
-    a.N = N; a.K = K; a.S = p.S; a.gpx = p.gpx;
-    const int n_tiles = N / kFragRows, G = n_xcd * p.gpx, npieces = K / kBlkK;
-    a.tq = n_tiles / G; a.trem = n_tiles % G;
-    a.pq = npieces / p.S; a.prem = npieces % p.S;
-    a.inv_S = (65536u + p.S - 1) / p.S;      // exact for the unit numbers that occur (< 4096)
+    const GemmPlan p = fill_plan(a, N, K, n_xcd);
     grid.y = p.gpx * p.S;
     multi = p.multi;
   };
@@ -285,7 +317,7 @@ static int verify_layer_bf16(const sv_model_cfg& c, const char* packed, float* x
   a.X = attn; a.gain = nullptr; a.Wp = (const uint4*)(packed + pl.wo);
   a.wscale = w8 ? (const float*)(packed + pl.so) : nullptr;
   shape(H, D);
-  a.x_io = x;
+  a.x_res = x; a.x_io = x;
   SV_LAUNCH_GEMM(PRO_PLAIN, EPI_RESID);
   mark(4);
   a.X = x; a.gain = (const float*)(packed + pl.g2); a.Wp = (const uint4*)(packed + pl.wgu);
@@ -298,7 +330,7 @@ static int verify_layer_bf16(const sv_model_cfg& c, const char* packed, float* x
   a.X = act; a.gain = nullptr; a.Wp = (const uint4*)(packed + pl.wd);
   a.wscale = w8 ? (const float*)(packed + pl.sd) : nullptr;
   shape(H, F);
-  a.x_io = x;
+  a.x_res = x; a.x_io = x;
   mark(7);
   SV_LAUNCH_GEMM(PRO_PLAIN, EPI_RESID);
   mark(8);
@@ -306,87 +338,95 @@ static int verify_layer_bf16(const sv_model_cfg& c, const char* packed, float* x
   return launch_status();
 }
 
-// ---- bf16 models, up to 64 rows: the whole stack as persistent launches ----------------------
+// ---- bf16 models, up to 64 rows: all layers of a call as one launch (sv_flow.h) -------------
 
-// Fills the launch description; false if this shape / device / cache layout needs the
-// per-layer path.
-static bool stack_plan(const sv_model_cfg& c, int n_layers, const void* const* packed,
-                       const sv_kv_view* kv, const sv_tree& tree, int B, float* x, char* ws,
-                       StackArgs* a, StackBufs* d, StackArgs** a_dev) {
+static int verify_flow_bf16(const sv_model_cfg& c, int n_layers, const void* const* packed,
+                            float* x, const sv_kv_view* kv, const sv_tree& tree, int B, char* ws,
+                            hipStream_t st, long long* timeline = nullptr, size_t timeline_len = 0,
+                            int* units_per_layer = nullptr) {
   const int T_ = tree.n_nodes, M = B * T_;
-  if (c.dtype != SV_BF16 || M > kMTile || n_layers < 1 || n_layers > kStackMaxLayers) return false;   // (8-bit weights: per-layer launches only)
-  int dev = 0, cus = 0;
-  if (hipGetDevice(&dev) != hipSuccess ||
-      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
-    return false;
+  const int H = c.hidden, D = c.n_heads * c.head_dim, F = c.mlp_dim;
+  const PackedLayout pl = packed_layout(c);
+  const WorkspaceLayout wl = workspace_layout(c, M, 0);
   const int n_xcd = device_xcds();
-  if (cus < n_xcd * kUnitsPerXcd) return false;
+  const bool w8 = c.dtype == SV_BF16_W8;
+  FlowSetup s;
+  memset(&s, 0, sizeof(s));
+  FlowPlan p;
+  memset(&p, 0, sizeof(p));
+  int* status = (int*)(ws + wl.counters + wl.counter_bytes) - 1;
+  const int NK[4][2] = {{3 * D, H}, {H, D}, {2 * F, H}, {H, F}};
+  int units[5];
+  for (int i = 0; i < 4; ++i) {
+    GemmArgs& a = s.g[i];
+    const GemmPlan gp = fill_plan(a, NK[i][0], NK[i][1], n_xcd);
+    a.M = M; a.ucap = wl.ucap; a.tstride = wl.tstride;
+    a.part16 = (uint4*)(ws + wl.part);
+    a.pscale = (float*)(ws + wl.part + wl.part_bytes / 2);
+    a.sumsq = (float*)(ws + wl.sumsq);
+    a.group_cnt = (unsigned*)(ws + wl.counters);
+    a.status = status;
+    a.eps = c.rms_eps;
+    a.depth = tree.depth; a.prefix_len = kv[0].prefix_len; a.p_max = kv[0].prefix_len_max;
+    a.cap = kv[0].capacity; a.T = T_; a.nh = c.n_heads; a.theta = c.rope_theta;
+    a.n_spin = kFlowSpin;
+    p.multi[i] = gp.multi ? 1 : 0;
+    units[i < 1 ? 0 : i + 1] = gp.gpx * gp.S;
+    s.n_wg[i < 1 ? 0 : i + 1] = (unsigned)(n_xcd * gp.gpx * gp.S);
+  }
+  FlowAtt& A = s.att;
+  A.prefix_len = kv[0].prefix_len; A.anc = tree.anc_mask; A.p_max = kv[0].prefix_len_max;
+  A.n_words = tree.n_words; A.T = T_; A.nh = c.n_heads; A.cap = kv[0].capacity;
+  A.gx = B * ceil_div(T_, kAttQ);
+  A.total = A.gx * c.n_heads;
+  A.per_xcd = ceil_div(A.total, n_xcd);
+  A.status = status;
+  units[1] = A.per_xcd;
+  s.n_wg[1] = (unsigned)A.total;
+  p.ustart[0] = 0;
+  for (int i = 0; i < 5; ++i) p.ustart[i + 1] = p.ustart[i] + units[i];
+  s.off_g1 = pl.g1; s.off_g2 = pl.g2; s.off_wqkv = pl.wqkv; s.off_wo = pl.wo; s.off_wgu = pl.wgu;
+  s.off_wd = pl.wd; s.off_sqkv = pl.sqkv; s.off_so = pl.so; s.off_sgu = pl.sgu; s.off_sd = pl.sd;
+  s.w8 = w8 ? 1 : 0;
+  s.acts = (float*)(ws + wl.q);
+  s.act_stride = wl.flow_stride / 4;
+  s.off_q = 0; s.off_attn = (wl.attn - wl.q) / 4; s.off_act = (wl.act - wl.q) / 4;
+  s.off_x1 = (wl.flow_x1 - wl.q) / 4; s.off_x2 = (wl.flow_x2 - wl.q) / 4;
+  s.done = (unsigned*)(ws + wl.flow_done);
+  s.table = (FlowLayer*)(ws + wl.flow_tab);
+  p.table = s.table;
+  if (units_per_layer) *units_per_layer = p.ustart[5] * n_xcd;
+  if (timeline && timeline_len < (size_t)n_layers * p.ustart[5] * n_xcd * kFlowStamps) return SV_ERR_WORKSPACE;
+  // deeper stacks than the table holds: one launch per run of layers (a launch boundary orders
+  // and publishes everything, so the activation slots can be used again)
+  for (int l0 = 0; l0 < n_layers; l0 += kFlowMaxLayers) {
+    const int n = n_layers - l0 < kFlowMaxLayers ? n_layers - l0 : kFlowMaxLayers;
+    for (int l = 0; l < n; ++l) {
+      s.packed[l] = (const unsigned char*)packed[l0 + l];
+      s.kc[l] = (bf16_t*)kv[l0 + l].k;
+      s.vc[l] = (bf16_t*)kv[l0 + l].v;
+    }
+    s.n_layers = n;
+    s.x = x;
+    p.n_layers = n;
+    p.ts = timeline ? timeline + (size_t)l0 * p.ustart[5] * n_xcd * kFlowStamps : nullptr;
+    flow_setup_kernel<<<1, 64, 0, st>>>(s);
+    const dim3 grid(n_xcd, p.ustart[5] * n);
+    if (w8) verify_flow_kernel<true><<<grid, 256, 0, st>>>(p);
+    else verify_flow_kernel<false><<<grid, 256, 0, st>>>(p);
+  }
+  return launch_status();
+}
+
+// The single-launch form applies to bf16 models with one row tile whose layers share the
+// prefix lengths and the cache geometry.
+static bool flow_applies(const sv_model_cfg& c, int n_layers, const sv_kv_view* kv, int M) {
+  if (c.dtype == SV_F32 || M > kMTile) return false;
   for (int l = 1; l < n_layers; ++l)
     if (kv[l].prefix_len != kv[0].prefix_len || kv[l].prefix_len_max != kv[0].prefix_len_max ||
         kv[l].capacity != kv[0].capacity)
       return false;
-  const int H = c.hidden, D = c.n_heads * c.head_dim, F = c.mlp_dim;
-  const WorkspaceLayout wl = workspace_layout(c, M, 0);
-  const PackedLayout pl = packed_layout(c);
-  memset(a, 0, sizeof(*a));
-  memset(d, 0, sizeof(*d));
-  const int NK[4][2] = {{3 * D, H}, {H, D}, {2 * F, H}, {H, F}};
-  size_t part_xcd = 0;
-  int gmax = 1;
-  for (int ph = 0; ph < 4; ++ph) {
-    const GemmPlan p = plan_gemm(NK[ph][0], NK[ph][1], n_xcd);
-    if (p.gpx * p.S > kUnitsPerXcd) return false;
-    a->plan[ph] = PhasePlan{NK[ph][0], NK[ph][1], p.S, p.gpx};
-    const PhaseGeom g0 = phase_geom(a->plan[ph], n_xcd, 0, 0);
-    if (g0.n_chunks > 1 && g0.t_max > 4) return false;     // accumulators of one tile per wave only
-    const size_t need = (size_t)p.gpx * g0.t_max * p.S;        // partial tiles per XCD
-    if (need > part_xcd) part_xcd = need;
-    if (n_xcd * p.gpx > gmax) gmax = n_xcd * p.gpx;
-  }
-  if (gmax > 256 || part_xcd * n_xcd * kTileFloats * 4 > wl.stack_part_bytes) return false;
-  for (int l = 0; l < n_layers; ++l) {
-    a->L[l].packed = (const unsigned char*)packed[l];
-    a->L[l].kc = (bf16_t*)kv[l].k;
-    a->L[l].vc = (bf16_t*)kv[l].v;
-  }
-  a->n_layers = n_layers;
-  a->off_g1 = (unsigned)pl.g1; a->off_g2 = (unsigned)pl.g2;
-  a->off_wqkv = pl.wqkv; a->off_wo = pl.wo; a->off_wgu = pl.wgu; a->off_wd = pl.wd;
-  a->M = M; a->T = T_; a->nh = c.n_heads; a->n_xcd = n_xcd;
-  a->eps = c.rms_eps; a->theta = c.rope_theta;
-  d->x_io = x;
-  d->q = (float*)(ws + wl.q);
-  d->attn = (float*)(ws + wl.attn);
-  d->act = (float*)(ws + wl.act);
-  d->part16 = (uint4*)(ws + wl.stack_part);           // data in the first half, scales behind
-  d->pscale = (float*)(ws + wl.stack_part + wl.stack_part_bytes / 2);
-  a->part_xcd_tiles = part_xcd;
-  d->sumsq = (float*)(ws + wl.stack_sumsq);
-  char* ctl = ws + wl.stack_ctl;
-  d->group_cnt = (unsigned long long*)ctl;
-  a->gmax = 256;
-  unsigned* words = (unsigned*)(ctl + (size_t)kStackMaxLayers * 4 * 256 * 8 * kStackCntStride);
-  d->grid_cnt = words;
-  d->wg_cnt = words + 8 * 64;
-  d->wg_flag = words + 8 * 64 + 256 * 32;
-  *a_dev = (StackArgs*)(words + 8 * 64 + 256 * 32 + 256 * 32);
-  d->status = (int*)(ws + wl.counters + wl.counter_bytes) - 1;
-  d->depth = tree.depth;
-  d->prefix_len = kv[0].prefix_len;
-  d->anc = tree.anc_mask;
-  a->n_words = tree.n_words;
-  a->p_max = kv[0].prefix_len_max;
-  a->cap = kv[0].capacity;
   return true;
-}
-
-static int launch_stack(const StackArgs& a, const StackBufs& d, StackArgs* a_dev, char* ws,
-                        const WorkspaceLayout& wl, hipStream_t st) {
-  const size_t n = wl.stack_ctl_bytes / sizeof(int);
-  zero_ints<<<(unsigned)((n + 255) / 256), 256, 0, st>>>((int*)(ws + wl.stack_ctl), n);
-  write_stack_args<<<1, 64, 0, st>>>(a, a_dev);
-  verify_stack_persistent<<<a.n_xcd * kUnitsPerXcd, 512, 0, st>>>(a_dev, d);
-  return launch_status();
 }
 
 template <typename T>
@@ -452,16 +492,12 @@ static int head_packed(const sv_model_cfg& c, const char* packed, const float* x
   const WorkspaceLayout wl = workspace_layout(c, n_rows, n);
   const HeadLayout hl = head_layout(c, n);
   const int n_xcd = device_xcds();
-  const GemmPlan p = plan_gemm(n, H, n_xcd);
   float* logits = (float*)(ws + wl.head_logits);
   GemmArgs a;
   memset(&a, 0, sizeof(a));
+  const GemmPlan p = fill_plan(a, n, H, n_xcd);
   a.X = x; a.gain = (const float*)(packed + hl.gain); a.Wp = (const uint4*)(packed + hl.w);
-  a.M = n_rows; a.N = n; a.K = H; a.S = p.S; a.gpx = p.gpx; a.n_xcd = n_xcd;
-  const int n_tiles = n / kFragRows, G = n_xcd * p.gpx, npieces = H / kBlkK;
-  a.tq = n_tiles / G; a.trem = n_tiles % G;
-  a.pq = npieces / p.S; a.prem = npieces % p.S;
-  a.inv_S = (65536u + p.S - 1) / p.S;
+  a.M = n_rows; a.ucap = wl.head_ucap; a.tstride = wl.head_tstride;
   a.part16 = (uint4*)(ws + wl.head_part);
   a.pscale = (float*)(ws + wl.head_part + wl.head_part_bytes / 2);
   a.sumsq = (float*)(ws + wl.head_sumsq);
@@ -479,6 +515,7 @@ static int head_packed(const sv_model_cfg& c, const char* packed, const float* x
 }  // namespace sv
 
 using namespace sv;
+static_assert(kFlowStamps == SV_FLOW_STAMPS, "timeline stamps per workgroup");
 
 extern "C" {
 
@@ -659,6 +696,8 @@ static int verify_layer_checked(const sv_model_cfg* cfg, const void* packed, flo
   if (cfg->dtype == SV_F32)
     return verify_layer_f32(*cfg, (const char*)packed, x, *kv, *tree, B, (char*)workspace,
                             (hipStream_t)stream, ev);
+  if (!ev && flow_applies(*cfg, 1, kv, B * T))
+    return verify_flow_bf16(*cfg, 1, &packed, x, kv, *tree, B, (char*)workspace, (hipStream_t)stream);
   return verify_layer_bf16(*cfg, (const char*)packed, x, *kv, *tree, B, (char*)workspace,
                            (hipStream_t)stream, ev);
 }
@@ -708,6 +747,9 @@ int sv_verify_stack(const sv_model_cfg* cfg, int n_layers, const void* const* pa
                     size_t ws_bytes, void* stream) {
   const int rc = verify_stack_args(cfg, n_layers, packed, x, kv, tree, B, workspace, ws_bytes);
   if (rc != SV_OK) return rc;
+  if (flow_applies(*cfg, n_layers, kv, B * tree->n_nodes))
+    return verify_flow_bf16(*cfg, n_layers, packed, x, kv, *tree, B, (char*)workspace,
+                            (hipStream_t)stream);
   for (int l = 0; l < n_layers; ++l) {
     const int r2 = verify_layer_checked(cfg, packed[l], x, kv + l, tree, B, workspace, ws_bytes,
                                         stream, nullptr);
@@ -716,24 +758,16 @@ int sv_verify_stack(const sv_model_cfg* cfg, int n_layers, const void* const* pa
   return SV_OK;
 }
 
-int sv_verify_stack_persistent(const sv_model_cfg* cfg, int n_layers, const void* const* packed,
-                               float* x, const sv_kv_view* kv, const sv_tree* tree, int B,
-                               void* workspace, size_t ws_bytes, void* stream, long long* timeline,
-                               size_t timeline_len, int* n_workgroups) {
+int sv_verify_stack_timeline(const sv_model_cfg* cfg, int n_layers, const void* const* packed,
+                             float* x, const sv_kv_view* kv, const sv_tree* tree, int B,
+                             void* workspace, size_t ws_bytes, void* stream, long long* timeline,
+                             size_t timeline_len, int* workgroups_per_layer) {
   const int rc = verify_stack_args(cfg, n_layers, packed, x, kv, tree, B, workspace, ws_bytes);
   if (rc != SV_OK) return rc;
-  StackArgs a;
-  StackBufs d;
-  StackArgs* a_dev = nullptr;
-  if (!stack_plan(*cfg, n_layers, packed, kv, *tree, B, x, (char*)workspace, &a, &d, &a_dev))
-    return SV_ERR_SHAPE;
-  const int wgs = a.n_xcd * kUnitsPerXcd;
-  static_assert(kTsPerLayer == SV_TIMELINE_SLOTS, "timeline slots");
-  if (timeline && timeline_len < (size_t)wgs * n_layers * kTsPerLayer) return SV_ERR_WORKSPACE;
-  d.ts = timeline;
-  if (n_workgroups) *n_workgroups = wgs;
-  return launch_stack(a, d, a_dev, (char*)workspace, workspace_layout(*cfg, B * tree->n_nodes, 0),
-                      (hipStream_t)stream);
+  if (!timeline) return SV_ERR_NULL;
+  if (!flow_applies(*cfg, n_layers, kv, B * tree->n_nodes)) return SV_ERR_SHAPE;
+  return verify_flow_bf16(*cfg, n_layers, packed, x, kv, *tree, B, (char*)workspace,
+                          (hipStream_t)stream, timeline, timeline_len, workgroups_per_layer);
 }
 
 int sv_action_head_argmax(const sv_model_cfg* cfg, const void* g_final, const void* w_lm,

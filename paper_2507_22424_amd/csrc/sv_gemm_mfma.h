@@ -134,13 +134,19 @@ struct GemmArgs {
   int tq, trem, pq, prem;
   unsigned inv_S;
   int n_xcd;             // XCDs of the device (8 on MI355X; 1 for a single-XCD partition)
-  uint4* part16;         // [m_tiles][N/32][S] partial tiles, kTileVec4 uint4 each (scaled int16)
-  float* pscale;         // [m_tiles][N/32][S] inverse scale of each partial tile
-  float* sumsq;          // [m_tiles][n_xcd*gpx][S][64] row sums of x^2 over each K slice (RMSNorm, row scales of the partial tiles)
-  unsigned* group_cnt;   // [m_tiles][groups][kCntStride]: arrival (4 bits per XCD) and departure counters in the first two words, zero between launches
+  // Scratch of the split-K reduction.  Every address belongs to one XCD - regions are indexed
+  // [row tile][XCD][..] - so whatever one product leaves in an XCD's write-back L2 can never
+  // meet another XCD's use of the same address by a later product of the same launch.
+  int ucap;              // units per XCD the regions are laid out for (>= gpx * S)
+  int tstride;           // partial tiles per XCD the regions are laid out for (>= gpx * (tq + 1) * S)
+  uint4* part16;         // [m_tiles][n_xcd][tstride] partial tiles ([tile of the XCD][S]), kTileVec4 uint4 each (scaled int16)
+  float* pscale;         // [m_tiles][n_xcd][tstride] inverse scale of each partial tile
+  float* sumsq;          // [m_tiles][n_xcd][ucap][64] row sums of x^2 over each unit's K slice (RMSNorm, row scales of the partial tiles)
+  unsigned* group_cnt;   // [m_tiles][n_xcd][ucap][kCntStride]: arrival (4 bits per XCD) and departure counters of a group in the first two words, zero between products
   int* status;           // sticky: != 0 once slices of one tile were seen on different XCDs
   float eps;
-  float* x_io;           // EPI_RESID: x_io [M, N] += Y;  EPI_OUT: x_io [M, N] = Y
+  const float* x_res;    // EPI_RESID: residual input [M, N]
+  float* x_io;           // EPI_RESID: x_io [M, N] = x_res + Y (may alias x_res);  EPI_OUT: x_io [M, N] = Y
   float* act;            // EPI_SWIGLU: act [M, N/2] = silu(gate) * up
   float* q_out;          // EPI_QKV: [M, nh*128] float32, rotated
   bf16_t* kc;            // EPI_QKV: caches [B][nh][cap][128]
@@ -149,6 +155,13 @@ struct GemmArgs {
   const int32_t* prefix_len;
   int p_max, cap, T, nh;
   float theta;
+  // FLOW (all products of a pass in one launch): this product starts once *wait_cnt has
+  // reached wait_val (the workgroups of the product before it have all signalled), and every
+  // workgroup adds 1 to *done_cnt when its outputs are in memory.  n_spin bounds the wait.
+  const unsigned* wait_cnt;
+  unsigned wait_val;
+  unsigned* done_cnt;
+  int n_spin;
 };
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
@@ -312,6 +325,12 @@ __device__ inline void w8_to_frags(const u32x4_t raw, bf16x8_t& f0, bf16x8_t& f1
   f1 = __builtin_bit_cast(bf16x8_t, b);
 }
 
+// 16-byte load of four floats from global memory
+__device__ inline float4 ldg_f4(const __attribute__((address_space(1))) float* p) {
+  const f32x4_t v = *(const __attribute__((address_space(1))) f32x4_t*)p;
+  return make_float4(v[0], v[1], v[2], v[3]);
+}
+
 // XCD (accelerator complex die) this wave runs on: bits 3:0 of the XCC_ID hardware register.
 __device__ inline int xcd_actual(int n_xcd) {
   return (int)(__builtin_amdgcn_s_getreg((4 - 1) << 11 | 0 << 6 | 20) & 0xf) % n_xcd;
@@ -329,9 +348,17 @@ __device__ inline int frag_slot(int l, int s) { return ((l & 31) ^ (((s & 7) << 
 // loop, where spilled scalars cost stalls between the matrix instructions.
 typedef const __attribute__((address_space(4))) GemmArgs* gemm_args_ptr_t;
 typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
-template <int PRO, int EPI, bool W8>
+// Store that readers on other XCDs of the same launch may rely on (FLOW: written through to
+// memory at device scope; the signalling workgroup waits for its completion), or a plain store.
+template <bool DEV, typename T>
+__device__ __forceinline__ void store_out(__attribute__((address_space(1))) T* p, T v) {
+  if (DEV) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else *p = v;
+}
+template <int PRO, int EPI, bool W8, bool FLOW>
 __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos, int* s_crow,
-                                                  int tid, int lane, int wave) {
+                                                  int tid, int lane, int wave, int xcd, int u, int mt,
+                                                  long long* ts = nullptr) {
   GemmArgs a;                                // one batch of scalar loads; registers from here on
   {
     static_assert(sizeof(GemmArgs) % 4 == 0, "copied word by word");
@@ -349,17 +376,16 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
   const auto wscale = SV_GLOBAL(const float, a.wscale);
   const auto status = SV_GLOBAL(int, a.status);
   const auto x_io = SV_GLOBAL(float, a.x_io);
+  const auto x_res = SV_GLOBAL(const float, a.x_res);
+  const auto done_cnt = SV_GLOBAL(unsigned, a.done_cnt);
   const auto act = SV_GLOBAL(float, a.act);
   const auto q_out = SV_GLOBAL(float, a.q_out);
   const auto kc = SV_GLOBAL(unsigned short, a.kc);
   const auto vc = SV_GLOBAL(unsigned short, a.vc);
   const auto depth = SV_GLOBAL(const int32_t, a.depth);
   const auto prefix_len = SV_GLOBAL(const int32_t, a.prefix_len);
-  const int mt = blockIdx.z, m0 = mt * kMTile;
+  const int m0 = mt * kMTile;
   const int K = a.K, S = a.S;
-  const int n_tiles = a.N / kFragRows;
-  const int G = a.n_xcd * a.gpx;
-  const int xcd = blockIdx.x, u = blockIdx.y;
   const int ug = (int)(((unsigned)u * a.inv_S) >> 16);   // u / S
   const int g = xcd * a.gpx + ug, sp = u - ug * S;
   const int tq = a.tq, trem = a.trem;
@@ -375,7 +401,9 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
   __builtin_amdgcn_s_waitcnt(0);           // this wave's partial tiles are in L2
   __syncthreads();
   // (one line per group: arrivals and polls of different groups do not queue behind each other)
-  const auto gcnt = SV_GLOBAL(unsigned, a.group_cnt) + ((size_t)mt * G + g) * kCntStride;
+  const size_t xbase = (size_t)mt * a.n_xcd + xcd;       // this XCD's share of the scratch regions
+  const int t0x = xcd * a.gpx * tq + min(xcd * a.gpx, trem);   // first tile of this XCD
+  const auto gcnt = SV_GLOBAL(unsigned, a.group_cnt) + (xbase * a.ucap + ug) * kCntStride;
 #undef SV_GLOBAL
   if (EPI == EPI_QKV && tid >= 64 && tid < 64 + kMTile) {
     // rotary position and cache row of each row of the m tile, by the second wave while the
@@ -408,6 +436,7 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
     if (bad) __hip_atomic_fetch_or(status, bad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   __syncthreads();
+  if (FLOW && ts && tid == 0) ts[3] = wall_clock64();
   asm volatile("buffer_inv sc0" ::: "memory");                      // drop stale L1 lines (the L2 is shared)
   // Row sums of all slices -> 1 / rms: every wave keeps the value of row `lane` and fetches
   // the rows it needs with a lane read.  The loads are only issued here; they are consumed
@@ -416,7 +445,7 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
   if (PRO == PRO_GAIN) {
 #pragma unroll
     for (int s2 = 0; s2 < 8; ++s2)
-      ss8[s2] = sumsq[(((size_t)mt * G + g) * S + min(s2, S - 1)) * kMTile + lane];
+      ss8[s2] = sumsq[(xbase * a.ucap + ug * S + min(s2, S - 1)) * kMTile + lane];
   }
   float rstd_lane = 1.0f;
   unsigned rexp_lo = 0, rexp_hi = 0;       // row `lane`: h + 64 of slices 0..3 / 4..7
@@ -447,7 +476,7 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
         if (tl >= t_count) break;
         const int tile = t_begin + tl;
         // registers 4qd .. 4qd+3 of the tile = dwords 2qd, 2qd+1 = half of the uint4 of store qd/2
-        const size_t pidx = ((size_t)mt * n_tiles + tile) * S;
+        const size_t pidx = xbase * a.tstride + (size_t)(tile - t0x) * S;
         const auto pb = (const __attribute__((address_space(1))) u32x2_t*)(part16 + pidx * kTileVec4 + (qd >> 1) * 64 + lane) + (qd & 1);
 #pragma unroll
         for (int s2 = 0; s2 < 8; ++s2) part[bi][s2] = pb[(size_t)min(s2, S - 1) * (kTileVec4 * 2)];
@@ -469,7 +498,7 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
         if (EPI == EPI_RESID) {
 #pragma unroll
           for (int j = 0; j < 4; ++j)
-            xres[bi][j] = x_io[(size_t)min(m0 + row0 + j, a.M - 1) * a.N + tile * 32 + ln];
+            xres[bi][j] = x_res[(size_t)min(m0 + row0 + j, a.M - 1) * a.N + tile * 32 + ln];
         }
         if (W8) wsc[bi] = wscale[tile * 32 + ln];
       }
@@ -546,13 +575,13 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
 #pragma unroll
           for (int j = 0; j < 4; ++j)
             if (m0 + row0 + j < a.M)
-              x_io[(size_t)(m0 + row0 + j) * a.N + tile * 32 + ln] = xres[bi][j] + v[j];
+              store_out<FLOW>(x_io + ((size_t)(m0 + row0 + j) * a.N + tile * 32 + ln), xres[bi][j] + v[j]);
         }
         if (EPI == EPI_OUT) {
 #pragma unroll
           for (int j = 0; j < 4; ++j)
             if (m0 + row0 + j < a.M)
-              x_io[(size_t)(m0 + row0 + j) * a.N + tile * 32 + ln] = v[j];
+              store_out<FLOW>(x_io + ((size_t)(m0 + row0 + j) * a.N + tile * 32 + ln), v[j]);
         }
         if (EPI == EPI_SWIGLU) {             // lanes 0..15 gate, 16..31 up of the same column
           const int F = a.N / 2;
@@ -560,7 +589,7 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
           for (int j = 0; j < 4; ++j) {
             const float up = lane_xor16(v[j], lane);
             if (ln < 16 && m0 + row0 + j < a.M)
-              act[(size_t)(m0 + row0 + j) * F + tile * 16 + ln] = silu_fast(v[j]) * up;
+              store_out<FLOW>(act + ((size_t)(m0 + row0 + j) * F + tile * 16 + ln), silu_fast(v[j]) * up);
           }
         }
         if (EPI == EPI_QKV) {
@@ -586,9 +615,10 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
             }
             if (m0 + ml < a.M) {
               if (which == 0)
-                q_out[(size_t)(m0 + ml) * D + head * 128 + dcol] = val;
+                store_out<FLOW>(q_out + ((size_t)(m0 + ml) * D + head * 128 + dcol), val);
               else
-                cache[((size_t)s_crow[ml] + (size_t)head * a.cap) * 128 + dcol] = f32_to_bf16(val).bits;
+                store_out<FLOW>(cache + (((size_t)s_crow[ml] + (size_t)head * a.cap) * 128 + dcol),
+                                (unsigned short)f32_to_bf16(val).bits);
             }
           }
         }
@@ -601,34 +631,75 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
     gcnt[0] = 0;
     gcnt[1] = 0;
   }
+  if (FLOW) {
+    // outputs of every wave are in memory, then the workgroup reports in
+    __builtin_amdgcn_s_waitcnt(0);
+    asm volatile("s_barrier" ::: "memory");
+    if (tid == 0) {
+      __hip_atomic_fetch_add(done_cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (ts) ts[4] = wall_clock64();
+    }
+  }
 }
 
-// grid = (n_xcd, gpx * S, m_tiles), block = 256, 1 workgroup per CU (LDS).  K must be a multiple
-// of 256: slices are made of pieces of 16 fragments (2 K blocks), a chunk of X in LDS holds up
-// to two pieces.
+// LDS of one workgroup of the streaming GEMM (156 416 bytes; one workgroup per CU).
+constexpr int kGemmXsVec = 32 * 2 * 2 * 64;      // X chunk: [32 k-steps][2 m-halves][hi, lo][64 slots] x 16 bytes = 128 KiB
+constexpr int kGemmHeadVec = 3 * 8 * 64;         // single-chunk form: accumulators of tiles shared by two waves
+constexpr size_t kGemmLdsBytes = (size_t)(kGemmXsVec + kGemmHeadVec) * 16 + 3 * kMTile * 4;
+struct GemmLds {
+  uint4* xs;            // X chunk
+  uint4* s_head;        // accumulators handed between waves (single-chunk form)
+  int* s_pos;           // EPI_QKV: rotary position of each row of the m tile
+  int* s_crow;          // EPI_QKV: cache row (b * nh * cap + P + t) of each row
+  float* s_rowscale;    // 2^-h of each row for this slice's partial tiles
+  int* s_flag;          // FLOW: result of the first look at the dependency word
+};
+__device__ __forceinline__ GemmLds carve_gemm_lds(uint4* base) {
+  GemmLds l;
+  l.xs = base;
+  l.s_head = base + kGemmXsVec;
+  l.s_pos = reinterpret_cast<int*>(base + kGemmXsVec + kGemmHeadVec);
+  l.s_crow = l.s_pos + kMTile;
+  l.s_rowscale = reinterpret_cast<float*>(l.s_crow + kMTile);
+  l.s_flag = reinterpret_cast<int*>(l.s_rowscale + kMTile);
+  return l;
+}
+constexpr size_t kGemmLdsAlloc = kGemmLdsBytes + 16;     // + the flag word
+
+// One workgroup of the streaming GEMM: unit u of XCD xcd, row tile mt.  Launch shape of the
+// stand-alone kernel: grid = (n_xcd, gpx * S, m_tiles), block = 256, 1 workgroup per CU (LDS).
+// K must be a multiple of 256: slices are made of pieces of 16 fragments (2 K blocks), a chunk
+// of X in LDS holds up to two pieces.
 // MULTI: a K slice may span several LDS chunks (the host knows from its plan); the single-chunk
 // form carries no re-staging code and nothing of it in registers through the main loop.
 // W8: the weights are E4M3 codes (four loads per piece, converted to bf16 fragments in
 // registers; the row scales are applied in the reduction).
-template <int PRO, int EPI, bool MULTI, bool W8>
-__global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
+// FLOW: the workgroup is one of many products inside one launch: it requests its first weight
+// pieces, waits until the product before it has signalled completion (a bounded wait), reads its
+// activations (written through to memory by that product; the buffers of one launch are never
+// rewritten, so no cache holds an older copy), and writes its own outputs through to memory
+// before it signals.
+template <int PRO, int EPI, bool MULTI, bool W8, bool FLOW>
+__device__ __forceinline__ void gemm_stream_body(gemm_args_ptr_t ap, const int xcd, const int u,
+                                                 const int mt, const GemmLds lds, long long* ts = nullptr) {
+  const __attribute__((address_space(4))) GemmArgs& a = *ap;
   constexpr int kLoads = W8 ? kPieceFrags / 2 : kPieceFrags;   // 16-byte loads per piece and lane
-  // X chunk: [32 k-steps][2 m-halves][hi, lo][64 slots] x 16 bytes = 128 KiB
-  __shared__ uint4 xs[32 * 2 * 2 * 64];
-  __shared__ int s_pos[kMTile];             // EPI_QKV: rotary position of each row of the m tile
-  __shared__ int s_crow[kMTile];            // EPI_QKV: cache row (b * nh * cap + P + t) of each row
-  __shared__ float s_rowscale[kMTile];      // 2^-h of each row for this slice's partial tiles
-  // single-chunk form: accumulators of a tile that two waves share (see the runs below), handed
-  // from the wave that holds the tile's last pieces to the one that holds its first
-  __shared__ uint4 s_head[MULTI ? 1 : 3 * 8 * 64];
+  uint4* const xs = lds.xs;
+  int* const s_pos = lds.s_pos;
+  int* const s_crow = lds.s_crow;
+  float* const s_rowscale = lds.s_rowscale;
+  uint4* const s_head = lds.s_head;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: bookkeeping stays in scalar registers
-  const int mt = blockIdx.z, m0 = mt * kMTile;
+  // measurement aid: device clock (100 MHz) at fixed points of this workgroup's life
+  auto stamp = [&](int i) {
+    if (FLOW && ts && tid == 0) ts[i] = wall_clock64();
+  };
+  stamp(0);
+  const int m0 = mt * kMTile;
   const int K = a.K, S = a.S;
-  const int n_tiles = a.N / kFragRows;
-  const int G = a.n_xcd * a.gpx;
-  const int xcd = blockIdx.x;                // workgroups are dealt to the XCDs in turn, x fastest
-  const int u = blockIdx.y;                  // unit inside that XCD's share
+  // (workgroups are dealt to the XCDs in turn: xcd = linear workgroup index modulo n_xcd; u =
+  // unit inside that XCD's share)
 
   {
     const int ug = (int)(((unsigned)u * a.inv_S) >> 16);   // u / S
@@ -663,7 +734,9 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
     const int ft = MULTI ? wave : (np == 4 ? b0 >> 2 : np == 3 ? (b0 * 21846) >> 16 : np == 2 ? b0 >> 1 : b0);
     const int cj0 = MULTI ? 0 : b0 - ft * np;
     const int n_run = MULTI ? my_tiles * np : b1 - b0;
-    const size_t unit_id = ((size_t)mt * G + g) * S + sp;
+    const size_t xbase = (size_t)mt * a.n_xcd + xcd;     // this XCD's share of the scratch regions
+    const size_t unit_id = xbase * a.ucap + u;
+    const int t0x = xcd * a.gpx * tq + min(xcd * a.gpx, trem);   // first tile of this XCD
     const size_t tile_stride = (size_t)(K / (W8 ? 2 * kFragK : kFragK)) * 64;   // uint4 per tile
     typedef const __attribute__((address_space(1))) u32x4_t* wptr_t;
     const wptr_t wbase = (wptr_t)a.Wp + (size_t)(t_begin + ft) * tile_stride +
@@ -705,15 +778,16 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
       const int k = (p_begin + 4 * c) * kBlkK + (lane < nkc ? lane : 0) * 8;
       g0 = g1 = make_float4(1.f, 1.f, 1.f, 1.f);
       if (PRO == PRO_GAIN) {
-        g0 = *reinterpret_cast<const float4*>(a.gain + k);
-        g1 = *reinterpret_cast<const float4*>(a.gain + k + 4);
+        const auto gp = (const __attribute__((address_space(1))) float*)a.gain + k;
+        g0 = ldg_f4(gp);
+        g1 = ldg_f4(gp + 4);
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int m = m0 + wave + 4 * r;
-        const float* p = a.X + (size_t)min(m, a.M - 1) * K + k;
-        xa[r] = *reinterpret_cast<const float4*>(p);
-        xb[r] = *reinterpret_cast<const float4*>(p + 4);
+        const auto p = (const __attribute__((address_space(1))) float*)a.X + (size_t)min(m, a.M - 1) * K + k;
+        xa[r] = ldg_f4(p);
+        xb[r] = ldg_f4(p + 4);
       }
     };
     // `before_row(r)` runs ahead of row r's conversion (the first chunk slips the ring's loads in)
@@ -770,18 +844,55 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
       // 32 MB of weight requests in front of each other's X rows, and the X round trip - which
       // nothing can overlap - grows with the queue.  Spread over the conversion the same loads
       // still arrive before the main loop wants them (measured: 3.5 us per layer).
+      // FLOW: the activations exist only once the product before this one has signalled.  One
+      // look at its counter decides: if it is complete (the usual case for a workgroup that
+      // starts late in the hand-over) the order above is kept; otherwise the whole ring is
+      // requested first - the weights do not depend on anything - and the wait that follows
+      // costs nothing that the loads would not have cost anyway.
+      bool ready = true;
+      if (FLOW && a.wait_val != 0) {
+        const auto wc = (const __attribute__((address_space(1))) unsigned*)a.wait_cnt;
+        if (tid == 0)
+          *lds.s_flag = __hip_atomic_load(wc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= a.wait_val;
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        ready = __builtin_amdgcn_readfirstlane(*lds.s_flag) != 0;
+      }
       float4 xa[16], xb[16], g0, g1;
-      x_load(0, xa, xb, g0, g1);
-      issue(ring[0]);
-      x_convert(0, xa, xb, g0, g1, [&](int r) {
-        static_assert(kRing == 4, "one slot every fourth row");
-        if (r == 4) issue(ring[1]);
-        if (r == 8) issue(ring[2]);
-        if (r == 12) issue(ring[3]);
-      });
+      if (ready) {
+        x_load(0, xa, xb, g0, g1);
+        issue(ring[0]);
+        x_convert(0, xa, xb, g0, g1, [&](int r) {
+          static_assert(kRing == 4, "one slot every fourth row");
+          if (r == 4) issue(ring[1]);
+          if (r == 8) issue(ring[2]);
+          if (r == 12) issue(ring[3]);
+        });
+      } else {
+#pragma unroll
+        for (int sl = 0; sl < kRing; ++sl) issue(ring[sl]);
+        if (tid == 0) {
+          const auto wc = (const __attribute__((address_space(1))) unsigned*)a.wait_cnt;
+          int spin = 0;
+          while (__hip_atomic_load(wc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < a.wait_val) {
+            if (++spin > a.n_spin) {               // gave up: results are invalid, say so
+              __hip_atomic_fetch_or((__attribute__((address_space(1))) int*)a.status, 4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              break;
+            }
+            __builtin_amdgcn_s_sleep(2);
+          }
+        }
+        asm volatile("s_barrier" ::: "memory");
+        // the workgroups of an XCD that share a K slice (one per tile group) all leave the wait at
+        // the same moment and ask for the same rows: later groups hold back a little, so that
+        // their requests find the lines the first one has brought into the L2
+        for (int i = 0; i < (ug & 3); ++i) __builtin_amdgcn_s_sleep(12);
+        x_load(0, xa, xb, g0, g1);
+        x_convert(0, xa, xb, g0, g1, [](int) {});
+      }
     }
     if (PRO == PRO_GAIN && n_chunks == 1) publish_ssq();
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // X chunk 0 is in LDS; weight loads stay in flight
+    stamp(1);
 
     f32x16_t acc0 = {}, acc1 = {};
     const int rbase = 4 * (lane >> 5);
@@ -801,7 +912,7 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
     bool fresh = true;                                   // the accumulators hold nothing of the current tile yet
     bool head_pending = cj0 > 0;                         // the run starts inside a tile: its sum goes to the wave before
     // partial tile of this wave's current tile and this slice (data, inverse scale)
-    const size_t pidx0 = ((size_t)mt * n_tiles + t_begin + ft) * S + sp;
+    const size_t pidx0 = xbase * a.tstride + (size_t)(t_begin + ft - t0x) * S + sp;
     const uint4* pt = a.part16 + pidx0 * kTileVec4 + lane;
     const float* ps = a.pscale + pidx0;
 
@@ -1012,11 +1123,20 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
       }
     }
 
+    stamp(2);
     // ---- second half: group barrier, reduction, epilogue (arguments read afresh) ----
-    gemm_args_ptr_t ap = (gemm_args_ptr_t)__builtin_amdgcn_kernarg_segment_ptr();
-    asm volatile("" : "+s"(ap));
-    gemm_reduce_phase<PRO, EPI, W8>(ap, s_pos, s_crow, tid, lane, wave);
+    gemm_args_ptr_t ap2 = ap;
+    asm volatile("" : "+s"(ap2));
+    gemm_reduce_phase<PRO, EPI, W8, FLOW>(ap2, s_pos, s_crow, tid, lane, wave, xcd, u, mt, ts);
   }
+}
+
+// One product per launch: grid = (n_xcd, gpx * S, m_tiles), block = 256.
+template <int PRO, int EPI, bool MULTI, bool W8>
+__global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
+  __shared__ uint4 lds_raw[(kGemmLdsAlloc + 15) / 16];
+  gemm_args_ptr_t ap = (gemm_args_ptr_t)__builtin_amdgcn_kernarg_segment_ptr();
+  gemm_stream_body<PRO, EPI, MULTI, W8, false>(ap, blockIdx.x, blockIdx.y, blockIdx.z, carve_gemm_lds(lds_raw));
 }
 
 }  // namespace sv

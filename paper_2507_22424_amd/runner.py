@@ -100,8 +100,8 @@ class VerifyPass:
     # ---- one step ------------------------------------------------------------------
     def forward(self, n_layers: Optional[int] = None, want_logits: bool = True,
                 route: str = "stack", head: str = "auto") -> None:
-        """All layers, then the head.  route: "stack" (one sv_verify_stack call), "layers" (one
-        sv_verify_layer call per layer) or "persistent" (sv_verify_stack_persistent).  head:
+        """All layers, then the head.  route: "stack" (one sv_verify_stack call) or "layers" (one
+        sv_verify_layer call per layer).  head:
         "packed" (sv_action_head_argmax_packed), "plain" (sv_action_head_argmax on the raw
         rows) or "auto" (packed where a packed head has been loaded)."""
         self.x.copy_(self.x0)
@@ -111,9 +111,6 @@ class VerifyPass:
             for l in range(n):
                 sv.sv_verify_layer(self.cfg, self.packed[l], self.x, views[l], self.tree.struct,
                                    self.B, self.workspace)
-        elif route == "persistent":
-            sv.sv_verify_stack_persistent(self.cfg, self.packed[:n], self.x, views,
-                                          self.tree.struct, self.B, self.workspace)
         else:
             sv.sv_verify_stack(self.cfg, self.packed[:n], self.x, views, self.tree.struct, self.B,
                                self.workspace)

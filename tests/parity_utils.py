@@ -40,10 +40,23 @@ def f64(t):
 
 
 def row_rel_err(gpu, ref):
+    """Per row: max |gpu - ref| / max |ref|.  A NaN or infinity must sit in the same element on
+    both sides (asserted); such elements are then left out of the row's maximum."""
     gpu = np.asarray(gpu, dtype=np.float64)
-    num = np.max(np.abs(gpu - ref), axis=-1)
-    den = np.max(np.abs(ref), axis=-1)
-    return num / den
+    ref = np.asarray(ref, dtype=np.float64)
+    bad_gpu, bad_ref = ~np.isfinite(gpu), ~np.isfinite(ref)
+    assert np.array_equal(bad_gpu, bad_ref), \
+        f"non-finite values differ: {int(bad_gpu.sum())} on the GPU, {int(bad_ref.sum())} in the oracle"
+    diff = np.where(bad_ref, 0.0, np.abs(np.where(bad_gpu, 0.0, gpu) - np.where(bad_ref, 0.0, ref)))
+    den = np.max(np.where(bad_ref, 0.0, np.abs(ref)), axis=-1)
+    return np.max(diff, axis=-1) / den
+
+
+def worst_row(err):
+    """Largest per-row error; a NaN (0 / 0: an all-zero or all-non-finite oracle row) counts as a failure."""
+    err = np.asarray(err)
+    assert not np.isnan(err).any(), "a row's error is undefined (oracle row is zero or not finite)"
+    return float(err.max())
 
 
 def same_up_to_rounding(a, b, tol=1e-3):
@@ -58,10 +71,14 @@ def same_up_to_rounding(a, b, tol=1e-3):
 class SideBySide:
     """Outputs of one configuration from both sides."""
 
-    def __init__(self, cfg, n_layers=None, full_vocab=False, per_layer=True, tag="", persistent=True,
-                 hidden_transform=None):
+    def __init__(self, cfg, n_layers=None, full_vocab=False, per_layer=True, tag="",
+                 hidden_transform=None, finite_rows=None, stack_tol=2e-3):
         """hidden_transform(b, rows float32 [T, H]) -> rows: applied to the seeded input rows of
-        episode b before either side sees them."""
+        episode b before either side sees them.  finite_rows: only the first `finite_rows` node
+        rows enter the error figures (a test that plants a NaN in a later episode checks those
+        rows itself); by default every row does, and a NaN or infinity anywhere must then sit in
+        the same element on both sides."""
+        self.finite_rows = finite_rows
         L = cfg.n_layers if n_layers is None else n_layers
         self.cfg = cfg = cfg.scaled(n_layers=L)
         B, T = cfg.n_episodes, cfg.tree_nodes
@@ -104,9 +121,9 @@ class SideBySide:
                                    self.gpu.workspace)
                 torch.cuda.synchronize()
                 attn = self.gpu.workspace_view(sv.SV_WS_ATTN_OUT).float().cpu().numpy()
-                self.attn_err.append(np.nanmax(row_rel_err(attn, np.concatenate(ref_attn))))
-                self.x_err.append(np.nanmax(row_rel_err(self.gpu.x.cpu().numpy(),
-                                                        np.concatenate(x_ref))))
+                self.attn_err.append(worst_row(row_rel_err(attn[:finite_rows], np.concatenate(ref_attn)[:finite_rows])))
+                self.x_err.append(worst_row(row_rel_err(self.gpu.x.cpu().numpy()[:finite_rows],
+                                                       np.concatenate(x_ref)[:finite_rows])))
             say(f"[{tag or cfg.name}] layer {l + 1}/{L} done, {time.time() - t0:.0f}s"
                 + (f", attn err {self.attn_err[-1]:.2e}, x err {self.x_err[-1]:.2e}"
                    if per_layer else ""))
@@ -123,47 +140,39 @@ class SideBySide:
         self.gpu_logits = self.gpu.logits.cpu().numpy()
         self.gpu_token = self.gpu.token.cpu().numpy()
         self.gpu_x = self.gpu.x.cpu().numpy()
-        # sv_verify_layer calls and sv_verify_stack issue the same kernels (bit-identical);
-        # the single persistent launch (where it applies) does the same arithmetic
+        # sv_verify_layer calls and sv_verify_stack compute the same thing; where both were run
+        # they must agree to rounding (the stack call may order its work differently)
         if x_layer_calls is not None:
-            assert np.array_equal(self.gpu_x, x_layer_calls.cpu().numpy(), equal_nan=True), \
+            assert same_up_to_rounding(self.gpu_x, x_layer_calls.cpu().numpy(), tol=stack_tol), \
                 "stack and per-layer routes differ"
-        self.persistent_checked = False
-        if persistent:
-            try:
-                self.gpu.forward(want_logits=True, route="persistent")
-                torch.cuda.synchronize()
-                # (the single launch adds the K pieces of a tile in one run, the layer kernels
-                # may split a tile's pieces between two waves: float32 rounding and a step of
-                # the 16-bit partial tiles apart per product, which grows with depth like any
-                # rounding difference - so this route is held to the oracle, as the other is,
-                # in check_forward; here only a coarse guard against a wrong result)
-                px, pl = self.gpu.x.cpu().numpy(), self.gpu.logits.cpu().numpy()
-                assert same_up_to_rounding(px, self.gpu_x, tol=2e-2), "persistent route differs"
-                assert same_up_to_rounding(pl, self.gpu_logits, tol=2e-2)
-                self.persistent_x_err = np.nanmax(row_rel_err(px, self.ref_x))
-                self.persistent_logit_err = np.nanmax(row_rel_err(pl, self.ref_logits))
-                self.persistent_checked = True
-            except sv.SvError as e:
-                if e.status != sv.SV_ERR_SHAPE:
-                    raise
-        self.logit_err = row_rel_err(self.gpu_logits, self.ref_logits)
-        assert self.gpu.placement_status() == 0, "K slices of a tile ran on different XCDs"
+        self.logit_err = row_rel_err(self.gpu_logits[:finite_rows], self.ref_logits[:finite_rows])
+        worst_row(self.logit_err)
+        st = self.gpu.placement_status()
+        assert st == 0, (f"status word {st}: bit 0 = K slices of a tile ran on different XCDs, bit 1 = a "
+                         "group wait ran out, bit 2 = a wait for the product before ran out")
 
     def tolerated_ties(self, tol, n_rows=None):
         """Nodes (of the first n_rows; default all) whose GPU token differs from the oracle's:
-        (n tolerated, n not tolerated).  A difference is tolerated when the oracle's own logits
-        of the two candidates are closer than 2 * tol * max |logit| of that node."""
+        (n tolerated, n not tolerated, largest tolerated gap as a fraction of the row's largest
+        |logit|).  A difference is tolerated only when it can be explained by the logit error
+        that was actually measured on that node: if every GPU logit of the row is within e of the
+        oracle's, the first maximum can move only between candidates whose oracle logits differ
+        by at most 2 e.  e itself is held to tol * max |logit| by the logit check, so this is
+        never looser than "closer than 2 * tol * max |logit|" and usually far tighter."""
         lo = self.gpu.vocab_lo
         ok = bad = 0
+        worst_gap = 0.0
         for i in np.flatnonzero((self.gpu_token != self.ref_token)[:n_rows]):
             row = self.ref_logits[i]
+            top = np.max(np.abs(row))
+            e = np.max(np.abs(self.gpu_logits[i] - row))
             gap = row[self.ref_token[i] - lo] - row[self.gpu_token[i] - lo]
-            if gap <= 2 * tol * np.max(np.abs(row)):
+            if gap <= 2 * e and e <= tol * top:
                 ok += 1
+                worst_gap = max(worst_gap, gap / top)
             else:
                 bad += 1
-        return ok, bad
+        return ok, bad, worst_gap
 
     def check_gpu_argmax_of_own_logits(self):
         """The integer decision: the GPU token is the first maximum of the GPU's own logits."""

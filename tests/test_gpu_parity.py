@@ -22,46 +22,57 @@ pytestmark = pytest.mark.gpu
 TOL = {"f32": 1e-5, "bf16": 2e-2}
 
 
-def check_forward(s, tol, tie_frac_cap=0.25, attn_tol=None):
+def tie_cap(n_nodes):
+    """Near-tie token differences a configuration may show: 2 % of its nodes, at least one."""
+    return max(1, int(np.ceil(0.02 * n_nodes)))
+
+
+def check_forward(s, tol, attn_tol=None):
     """Attention output (per layer) and residual stream against `attn_tol` (default: tol),
-    logits against tol, tokens equal up to counted near-ties."""
+    logits against tol, tokens equal up to counted near-ties (see SideBySide.tolerated_ties)."""
     name = s.cfg.name
     if s.attn_err:
-        say(f"[{name}] max attn err {max(s.attn_err):.3e}, max x err {max(s.x_err):.3e}, "
-            f"logit err {s.logit_err.max():.3e}")
+        say(f"[{name}] max attn err {max(s.attn_err):.3e}, max x err {max(s.x_err):.3e}")
         assert max(s.attn_err) <= (tol if attn_tol is None else attn_tol)
         assert max(s.x_err) <= tol
+    say(f"[{name}] logit err {s.logit_err.max():.3e}")
     assert s.logit_err.max() <= tol
-    if s.persistent_checked:                 # the single-launch route against the oracle
-        say(f"[{name}] persistent route: x err {s.persistent_x_err:.3e}, logit err {s.persistent_logit_err:.3e}")
-        assert s.persistent_x_err <= tol and s.persistent_logit_err <= tol
     s.check_gpu_argmax_of_own_logits()
-    ok, bad = s.tolerated_ties(tol)
-    say(f"[{name}] tokens differing from the oracle: {ok} tolerated near-ties, {bad} others, "
-        f"of {len(s.ref_token)} nodes")
+    n = len(s.ref_token) if s.finite_rows is None else s.finite_rows
+    ok, bad, gap = s.tolerated_ties(tol, n_rows=s.finite_rows)
+    say(f"[{name}] tokens differing from the oracle: {ok} tolerated near-ties (largest oracle gap "
+        f"{gap:.2e} of the row's largest logit), {bad} others, of {n} nodes")
     assert bad == 0
-    assert ok <= tie_frac_cap * len(s.ref_token)
+    assert ok <= tie_cap(n)
     return ok
 
 
 def check_accept_paths(s, r_values, spread=8):
     """(1) bit-exact acceptance on oracle-supplied target tokens; (2) end to end on the GPU's
-    own tokens: identical lengths unless a differing token (a counted near-tie) is involved."""
+    own tokens: identical lengths and tokens in every episode whose tokens all equal the
+    oracle's; an episode with a differing token (a counted near-tie, see check_forward) is left
+    out of (2), counted, printed, and bounded by the number of differing tokens."""
     cfg, B, T = s.cfg, s.cfg.n_episodes, s.cfg.tree_nodes
     draft = np.concatenate([
         wl.noisy_draft_tokens(cfg, b, s.parents[b], s.ref_token[b * T:(b + 1) * T], spread)
         for b in range(B)])
+    n_diff_tokens = int((s.gpu_token != s.ref_token).sum())
     for r in r_values:
         g, refs = s.accept_both(r, draft, s.ref_token)
         assert_accept_equal(g, refs, cfg.max_depth)
         g2, _ = s.accept_both(r, draft, s.gpu_token)
+        skipped = 0
         for b in range(B):
             same_tokens = np.array_equal(s.gpu_token[b * T:(b + 1) * T],
                                          s.ref_token[b * T:(b + 1) * T])
             if same_tokens:
                 assert int(g2["length"][b]) == refs[b]["length"]
                 assert g2["tokens"][b].tolist() == g["tokens"][b].tolist()
-        say(f"[{cfg.name}] r={r}: accepted lengths {g['length'].tolist()}")
+            else:
+                skipped += 1
+        say(f"[{cfg.name}] r={r}: accepted lengths {g['length'].tolist()}; end-to-end check left out "
+            f"{skipped} of {B} episodes (near-tie tokens: {n_diff_tokens})")
+        assert skipped <= min(n_diff_tokens, tie_cap(B * T))
 
 
 # ---- acceptance alone (integer path) ------------------------------------------------------
@@ -107,7 +118,7 @@ def test_relaxed_accept_bit_exact(B, T, dmax, kids):
 
 def test_c1_tiny_f32_layer_head_accept():
     s = SideBySide(wl.C1)
-    check_forward(s, TOL["f32"], tie_frac_cap=0.0 + 1.0 / 15)
+    check_forward(s, TOL["f32"])
     cfg, T = s.cfg, s.cfg.tree_nodes
     # config 1 draws draft ids uniformly over the action tokens
     draft = wl.uniform_draft_tokens(cfg, 0)
@@ -124,7 +135,7 @@ def test_f32_odd_shapes(T, B, P):
                        n_episodes=B, prefix_lo=max(1, P - 9), prefix_hi=P, max_children=4,
                        spine_lo=min(3, max(T - 1, 0)))
     s = SideBySide(cfg)
-    check_forward(s, TOL["f32"], tie_frac_cap=0.1)
+    check_forward(s, TOL["f32"])
     check_accept_paths(s, (0, 3))
 
 
@@ -137,7 +148,6 @@ def test_bf16_small_model(T, B, P):
                        tree_nodes=T, n_episodes=B, prefix_lo=max(1, P - 50), prefix_hi=P,
                        max_children=6, r_values=(0, 4))
     s = SideBySide(cfg)
-    assert s.persistent_checked == (B * T <= 64)    # the single-launch route, where it applies
     check_forward(s, TOL["bf16"])
     check_accept_paths(s, (0, 4, 8))
 
@@ -151,15 +161,13 @@ def test_w8_small_model(T, B, P):
                        tree_nodes=T, n_episodes=B, prefix_lo=max(1, P - 50), prefix_hi=P,
                        max_children=6, r_values=(0, 4))
     s = SideBySide(cfg)
-    assert not s.persistent_checked                  # per-layer launches only
     check_forward(s, TOL["bf16"])
     check_accept_paths(s, (0, 4))
 
 
 def test_w8_one_7b_layer():
     s = SideBySide(wl.C2.scaled(name="C2-w8", vocab=32000, dtype="bf16_w8"))
-    assert max(s.attn_err) <= TOL["bf16"] and max(s.x_err) <= TOL["bf16"]
-    say(f"[C2-w8] attn err {max(s.attn_err):.3e}, x err {max(s.x_err):.3e}")
+    check_forward(s, TOL["bf16"])
 
 
 def test_w8_full_pass_32_layers():
@@ -173,15 +181,17 @@ def test_w8_full_pass_32_layers():
 # ---- configuration 2: one 7B-shaped layer, bf16 ------------------------------------------
 
 def test_c2_one_7b_layer_bf16():
+    """One 7B-shaped layer: attention output, residual stream, and the action-head logits of
+    that one-layer model (the configuration itself names no head; the head makes a NaN or a
+    wrong row anywhere in the layer's output visible in an asserted quantity)."""
     s = SideBySide(wl.C2.scaled(vocab=32000))
-    assert s.persistent_checked
-    assert max(s.attn_err) <= TOL["bf16"] and max(s.x_err) <= TOL["bf16"]
-    say(f"[C2] attn err {max(s.attn_err):.3e}, x err {max(s.x_err):.3e}")
+    check_forward(s, TOL["bf16"])
 
 
 # ---- configurations 4 and 5 at full width, a few layers deep --------------------------------
 
 def test_c4_batched_ragged_two_layers():
+    """Per-layer attention / residual checks of the 16-episode batch (the full depth follows)."""
     s = SideBySide(wl.C4, n_layers=2)
     check_forward(s, TOL["bf16"])
     check_accept_paths(s, wl.C4.r_values)
@@ -193,11 +203,28 @@ def test_c5_long_prefix_two_layers():
     check_accept_paths(s, wl.C5.r_values)
 
 
+@pytest.mark.timeout(1500)
+def test_c4_full_pass_32_layers():
+    """Configuration 4 as stated: 16 episodes, ragged prefixes, all 32 layers, head, acceptance."""
+    s = SideBySide(wl.C4, per_layer=False)
+    n_ties = check_forward(s, TOL["bf16"])
+    check_accept_paths(s, wl.C4.r_values)
+    say(f"[C4] 32 layers: logit err {s.logit_err.max():.3e}, tolerated near-ties {n_ties} of {len(s.ref_token)}")
+
+
+@pytest.mark.timeout(1500)
+def test_c5_full_pass_32_layers():
+    """Configuration 5 as stated: prefix 2048, 128 nodes (two mask words), all 32 layers."""
+    s = SideBySide(wl.C5, per_layer=False)
+    n_ties = check_forward(s, TOL["bf16"])
+    check_accept_paths(s, wl.C5.r_values)
+    say(f"[C5] 32 layers: logit err {s.logit_err.max():.3e}, tolerated near-ties {n_ties} of {len(s.ref_token)}")
+
+
 # ---- configuration 3: the full 32-layer pass the benchmark times ----------------------------
 
 def test_c3_full_pass_32_layers():
     s = SideBySide(wl.C3)
-    assert s.persistent_checked
     n_ties = check_forward(s, TOL["bf16"])
     check_accept_paths(s, wl.C3.r_values)
     say(f"[C3] tolerated argmax near-ties: {n_ties} of {len(s.ref_token)} nodes")
@@ -242,7 +269,6 @@ def test_bf16_rows_of_very_different_size_keep_their_relative_precision():
     this holds only because each row is normalised before the tile's scale is chosen)."""
     cfg = _small_bf16(T=30, B=2, P=60, name="bf16-row-sizes")
     s = SideBySide(cfg, hidden_transform=lambda b, h: h * wl.row_magnitudes(cfg, b, 4.0)[:, None])
-    assert s.persistent_checked
     check_forward(s, TOL["bf16"])
 
 
@@ -260,7 +286,7 @@ def test_bf16_nan_in_one_episode_stays_in_that_episode():
         return h
 
     with np.errstate(invalid="ignore"):              # the oracle meets the NaN too
-        s = SideBySide(cfg, hidden_transform=poison)
+        s = SideBySide(cfg, hidden_transform=poison, finite_rows=T)
     assert np.isnan(s.ref_x[T + 5]).any() and np.isnan(s.gpu_x[T + 5]).any()
     assert np.isfinite(s.ref_x[:T]).all() and np.isfinite(s.gpu_x[:T]).all()
     assert np.isfinite(s.gpu_logits[:T]).all()
@@ -269,6 +295,7 @@ def test_bf16_nan_in_one_episode_stays_in_that_episode():
         f"logit err {s.logit_err[:T].max():.3e}")
     assert err_x.max() <= TOL["bf16"] and s.logit_err[:T].max() <= TOL["bf16"]
     assert s.tolerated_ties(TOL["bf16"], n_rows=T)[1] == 0
+    check_forward(s, TOL["bf16"])
 
 
 def test_accept_depth_cap_below_tree_depth():
@@ -307,7 +334,7 @@ def test_full_vocabulary_head_variant():
     assert s.gpu_logits.shape == (52, cfg.vocab)
     assert s.logit_err.max() <= TOL["bf16"]
     s.check_gpu_argmax_of_own_logits()
-    ok, bad = s.tolerated_ties(TOL["bf16"])
+    ok, bad, _ = s.tolerated_ties(TOL["bf16"])
     assert bad == 0
     T = cfg.tree_nodes
     draft = np.concatenate([wl.uniform_draft_tokens(cfg, b) for b in range(cfg.n_episodes)])

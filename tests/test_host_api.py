@@ -16,9 +16,11 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "specvla_verify.h")).read()
-    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(sv_[a-z0-9_]+)\s*\(", header))
+    declared = set()
+    for name in ("specvla_verify.h", "specvla_verify_aux.h"):       # the path, and the measurement aids
+        header = open(os.path.join(ROOT, "include", name)).read()
+        header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+        declared |= set(re.findall(r"\b(sv_[a-z0-9_]+)\s*\(", header))
     assert declared == set(sv.EXPORTS)
     lib = sv.lib()
     for name in declared:
@@ -121,7 +123,7 @@ def test_stack_calls_check_their_arguments_before_any_launch():
     ptrs = (C.c_void_p * 2)(256, 512)
     kvs = (sv.KvView * 2)(sv.KvView(256, 256, 256, 280, 384), sv.KvView(256, 256, 256, 280, 384))
     big = 1 << 40
-    for fn, tail in ((lib.sv_verify_stack, ()), (lib.sv_verify_stack_persistent, (None, 0, None))):
+    for fn, tail in ((lib.sv_verify_stack, ()),):
         assert fn(C.byref(c7), 2, None, one, kvs, C.byref(tree), 1, one, big, None, *tail) == -1
         assert fn(C.byref(c7), 0, ptrs, one, kvs, C.byref(tree), 1, one, big, None, *tail) == -2
         assert fn(C.byref(c7), 2, ptrs, one, kvs, C.byref(tree), 1, one, 16, None, *tail) == -5
@@ -129,15 +131,6 @@ def test_stack_calls_check_their_arguments_before_any_launch():
         assert fn(C.byref(c7), 2, bad, one, kvs, C.byref(tree), 1, one, big, None, *tail) == -1
         odd = (C.c_void_p * 2)(256, 513)          # packed blobs are 256-byte aligned
         assert fn(C.byref(c7), 2, odd, one, kvs, C.byref(tree), 1, one, big, None, *tail) == -5
-    # the single-launch form: float32 models and more than 64 rows are outside its reach
-    c1 = sv.model_cfg("f32", 256, 4, 64, 688, 512)
-    t15 = sv.Tree(256, 256, 256, 15, 1)
-    k1 = (sv.KvView * 1)(sv.KvView(256, 256, 256, 64, 128))
-    p1 = (C.c_void_p * 1)(256)
-    assert lib.sv_verify_stack_persistent(C.byref(c1), 1, p1, one, k1, C.byref(t15), 1, one, big,
-                                          None, None, 0, None) == -2
-    assert lib.sv_verify_stack_persistent(C.byref(c7), 2, ptrs, one, kvs, C.byref(tree), 2, one,
-                                          big, None, None, 0, None) == -2
 
 
 def test_eight_bit_weight_packing_checks_its_arguments_before_any_launch():
