@@ -38,21 +38,6 @@ int sv_verify_layer_timed(const sv_model_cfg *cfg, const void *packed, float *x,
                           const sv_kv_view *kv, const sv_tree *tree, int B, void *workspace,
                           size_t ws_bytes, void *stream, void *const *events);
 
-/* Measurement aid: exactly sv_verify_stack for a bf16 model of up to 64 tree rows (the
- * single-launch form), with the device clock (100 MHz) written at fixed points of every
- * workgroup's life.  Workgroup w of layer l (w < *workgroups_per_layer; the products follow each
- * other in the order q/k/v, attention, output, gate/up, down, each with its workgroups in XCD-
- * interleaved order) writes timeline[(l * *workgroups_per_layer + w) * SV_FLOW_STAMPS + i]:
- * i = 0 start, 1 activations staged (attention: inputs ready), 2 main loop done, 3 group
- * complete, 4 outputs written and reported.
- *   timeline: [device] int64, timeline_len entries (SV_ERR_WORKSPACE if too few)
- * SV_ERR_SHAPE where the single-launch form does not apply. */
-#define SV_FLOW_STAMPS 8
-int sv_verify_stack_timeline(const sv_model_cfg *cfg, int n_layers, const void *const *packed,
-                             float *x, const sv_kv_view *kv, const sv_tree *tree, int B,
-                             void *workspace, size_t ws_bytes, void *stream, long long *timeline,
-                             size_t timeline_len, int *workgroups_per_layer);
-
 /* Measurement aid, no part of the verification path: reads `bytes` of device memory once with
  * the access pattern of the weight stream (16-byte non-temporal loads, 1 KiB per wave and
  * instruction, 8 KiB per wave in flight) and discards the data.  bench.py times it to report

@@ -25,7 +25,7 @@ SV_WS_ATTN_OUT, SV_WS_Q, SV_WS_STATUS = 0, 1, 2
 EXPORTS = ("sv_version", "sv_strerror", "sv_tree_build_masks", "sv_packed_layer_bytes",
            "sv_pack_layer", "sv_pack_layer_w8", "sv_workspace_bytes", "sv_workspace_init", "sv_workspace_region",
            "sv_verify_layer",
-           "sv_verify_layer_timed", "sv_verify_stack", "sv_verify_stack_timeline",
+           "sv_verify_layer_timed", "sv_verify_stack",
            "sv_action_head_argmax", "sv_packed_head_bytes", "sv_pack_head",
            "sv_action_head_argmax_packed", "sv_stream_read", "sv_relaxed_accept",
            "sv_commit_path", "sv_advance_prefix", "sv_tree_build_device")
@@ -95,8 +95,6 @@ def lib() -> C.CDLL:
         l.sv_verify_stack.argtypes = [C.POINTER(ModelCfg), C.c_int, C.POINTER(C.c_void_p), C.c_void_p,
                                       C.POINTER(KvView), C.POINTER(Tree), C.c_int, C.c_void_p,
                                       C.c_size_t, C.c_void_p]
-        l.sv_verify_stack_timeline.argtypes = l.sv_verify_stack.argtypes + [
-            C.c_void_p, C.c_size_t, C.POINTER(C.c_int)]
         l.sv_action_head_argmax.argtypes = [C.POINTER(ModelCfg), C.c_void_p, C.c_void_p, C.c_void_p,
                                             C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                             C.c_void_p, C.c_size_t, C.c_void_p]
@@ -260,20 +258,6 @@ def sv_verify_stack(cfg: ModelCfg, packed: Sequence[torch.Tensor], x: torch.Tens
     _check(lib().sv_verify_stack(C.byref(cfg), n, ptrs, _dev(x, torch.float32, "x"), views,
                                  C.byref(tree), B, _dev(workspace, torch.uint8, "workspace"),
                                  workspace.numel(), _stream(stream)), "sv_verify_stack")
-
-
-def sv_verify_stack_timeline(cfg: ModelCfg, packed: Sequence[torch.Tensor], x: torch.Tensor,
-                             kv: Sequence[KvView], tree: Tree, B: int, workspace: torch.Tensor,
-                             timeline: torch.Tensor, stream=None) -> int:
-    """Returns the workgroups per layer (timeline: int64, device; see specvla_verify_aux.h)."""
-    n, ptrs, views = _stack_arrays(packed, kv)
-    n_wg = C.c_int(0)
-    _check(lib().sv_verify_stack_timeline(
-        C.byref(cfg), n, ptrs, _dev(x, torch.float32, "x"), views, C.byref(tree), B,
-        _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream),
-        _dev(timeline, torch.int64, "timeline"), timeline.numel(), C.byref(n_wg)),
-        "sv_verify_stack_timeline")
-    return n_wg.value
 
 
 def sv_action_head_argmax(cfg: ModelCfg, g_final: torch.Tensor, w_lm: torch.Tensor,

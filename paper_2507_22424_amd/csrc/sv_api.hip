@@ -11,9 +11,9 @@
 #include "sv_accept.h"
 #include "sv_attention.h"
 #include "sv_gemm_mfma.h"
+#include "sv_gemm_rows.h"
 #include "sv_internal.h"
 #include "sv_kernels.h"
-#include "sv_flow.h"
 #include "sv_tree_build.h"
 
 namespace sv {
@@ -131,19 +131,17 @@ static WorkspaceLayout workspace_layout(const sv_model_cfg& c, int m_rows, int n
   L.q = o;           o = align_up(o + mp * D * 4, kAlign);
   L.attn = o;        o = align_up(o + mp * D * 4, kAlign);
   L.act = o;         o = align_up(o + mp * F * 4, kAlign);
-  // single-launch form (bf16 models, one row tile): every layer of a launch has its own
-  // activation buffers - slot 0 starts with the q / attn / act regions above - plus the table of
-  // per-layer launch descriptions and the completion counters
-  L.flow_layers = 0;
-  L.flow_x1 = L.flow_x2 = L.flow_stride = L.flow_tab = L.flow_done = 0;
-  if (c.dtype != SV_F32 && mt == 1) {
-    L.flow_layers = kFlowMaxLayers;
-    L.flow_x1 = o;   o = align_up(o + mp * H * 4, kAlign);
-    L.flow_x2 = o;   o = align_up(o + mp * H * 4, kAlign);
-    L.flow_stride = o - L.q;                       // bytes from one layer's slot to the next
-    o = L.q + (size_t)kFlowMaxLayers * L.flow_stride;
-    L.flow_tab = o;  o = align_up(o + (size_t)kFlowMaxLayers * sizeof(FlowLayer), kAlign);
-    L.flow_done = o; o = align_up(o + (size_t)kFlowMaxLayers * 5 * kFlowCntStride * 4, kAlign);
+  // many rows (bf16 weights, more than two row tiles): activation fragments of one product,
+  // 1 / rms of the rows, float32 partial blocks of the products that split K
+  L.rows_xs = L.rows_rstd = L.rows_part = 0;
+  L.rows_pad = 0;
+  if (c.dtype == SV_BF16 && mt > kRowsMinTiles) {
+    size_t k_max = H > D ? H : D;
+    if (F > k_max) k_max = F;
+    L.rows_pad = ceil_div(m_rows, kRowsTM) * kRowsTM;
+    L.rows_xs = o;   o = align_up(o + (size_t)L.rows_pad * k_max * 4, kAlign);
+    L.rows_rstd = o; o = align_up(o + (size_t)L.rows_pad * 4, kAlign);
+    L.rows_part = o; o = align_up(o + (size_t)kRowsKsplit * L.rows_pad * H * 4, kAlign);
   }
   L.head_z = o;      o = align_up(o + mp * H * 4, kAlign);
   L.head_logits = o; o = align_up(o + mp * (size_t)(n_scored > 0 ? n_scored : 0) * 4 * 16, kAlign);   // up to 16 K-slice planes
@@ -279,24 +277,27 @@ static int verify_layer_bf16(const sv_model_cfg& c, const char* packed, float* x
   float* q = (float*)(ws + wl.q);
   float* attn = (float*)(ws + wl.attn);
   float* act = (float*)(ws + wl.act);
-  dim3 grid(n_xcd, 1, wl.m_tiles);           // workgroup (x, y) -> XCD x, unit y
+  dim3 grid(n_xcd, 1, 1);                    // workgroup (x, y) -> XCD x, unit (and row tile) y
+  const bool rows = wl.m_tiles > 1;
   bool multi = false;
   a.ucap = wl.ucap; a.tstride = wl.tstride;
   auto shape = [&](int N, int K) {
     const GemmPlan p = fill_plan(a, N, K, n_xcd);
-    grid.y = p.gpx * p.S;
+    grid.y = p.gpx * p.S * wl.m_tiles;
     multi = p.multi;
   };
   // the kernel form for the shape just planned: single- or multi-chunk K slices
-#define SV_LAUNCH_GEMM(PRO, EPI)                                                     \
-  do {                                                                               \
-    if (w8) {                                                                        \
-      if (multi) gemm_stream_bf16<PRO, EPI, true, true><<<grid, 256, 0, st>>>(a);    \
-      else gemm_stream_bf16<PRO, EPI, false, true><<<grid, 256, 0, st>>>(a);         \
-    } else {                                                                         \
-      if (multi) gemm_stream_bf16<PRO, EPI, true, false><<<grid, 256, 0, st>>>(a);   \
-      else gemm_stream_bf16<PRO, EPI, false, false><<<grid, 256, 0, st>>>(a);        \
-    }                                                                                \
+#define SV_LAUNCH_GEMM2(PRO, EPI, W8, ROWS)                                             \
+  do {                                                                                 \
+    if (multi) gemm_stream_bf16<PRO, EPI, true, W8, ROWS><<<grid, 256, 0, st>>>(a);    \
+    else gemm_stream_bf16<PRO, EPI, false, W8, ROWS><<<grid, 256, 0, st>>>(a);         \
+  } while (0)
+#define SV_LAUNCH_GEMM(PRO, EPI)                                                       \
+  do {                                                                                 \
+    if (w8 && rows) SV_LAUNCH_GEMM2(PRO, EPI, true, true);                             \
+    else if (w8) SV_LAUNCH_GEMM2(PRO, EPI, true, false);                               \
+    else if (rows) SV_LAUNCH_GEMM2(PRO, EPI, false, true);                             \
+    else SV_LAUNCH_GEMM2(PRO, EPI, false, false);                                      \
   } while (0)
 
   const bool w8 = c.dtype == SV_BF16_W8;
@@ -335,98 +336,76 @@ static int verify_layer_bf16(const sv_model_cfg& c, const char* packed, float* x
   SV_LAUNCH_GEMM(PRO_PLAIN, EPI_RESID);
   mark(8);
 #undef SV_LAUNCH_GEMM
+#undef SV_LAUNCH_GEMM2
   return launch_status();
 }
 
-// ---- bf16 models, up to 64 rows: all layers of a call as one launch (sv_flow.h) -------------
+// ---- bf16 models, many rows: products bound by the matrix cores (sv_gemm_rows.h) -----------
 
-static int verify_flow_bf16(const sv_model_cfg& c, int n_layers, const void* const* packed,
-                            float* x, const sv_kv_view* kv, const sv_tree& tree, int B, char* ws,
-                            hipStream_t st, long long* timeline = nullptr, size_t timeline_len = 0,
-                            int* units_per_layer = nullptr) {
+static int verify_layer_rows(const sv_model_cfg& c, const char* packed, float* x,
+                             const sv_kv_view& kv, const sv_tree& tree, int B, char* ws,
+                             hipStream_t st, hipEvent_t* ev) {
   const int T_ = tree.n_nodes, M = B * T_;
+  auto mark = [&](int i) {
+    if (ev) (void)hipEventRecord(ev[i], st);
+  };
   const int H = c.hidden, D = c.n_heads * c.head_dim, F = c.mlp_dim;
   const PackedLayout pl = packed_layout(c);
   const WorkspaceLayout wl = workspace_layout(c, M, 0);
   const int n_xcd = device_xcds();
-  const bool w8 = c.dtype == SV_BF16_W8;
-  FlowSetup s;
-  memset(&s, 0, sizeof(s));
-  FlowPlan p;
-  memset(&p, 0, sizeof(p));
-  int* status = (int*)(ws + wl.counters + wl.counter_bytes) - 1;
-  const int NK[4][2] = {{3 * D, H}, {H, D}, {2 * F, H}, {H, F}};
-  int units[5];
-  for (int i = 0; i < 4; ++i) {
-    GemmArgs& a = s.g[i];
-    const GemmPlan gp = fill_plan(a, NK[i][0], NK[i][1], n_xcd);
-    a.M = M; a.ucap = wl.ucap; a.tstride = wl.tstride;
-    a.part16 = (uint4*)(ws + wl.part);
-    a.pscale = (float*)(ws + wl.part + wl.part_bytes / 2);
-    a.sumsq = (float*)(ws + wl.sumsq);
-    a.group_cnt = (unsigned*)(ws + wl.counters);
-    a.status = status;
-    a.eps = c.rms_eps;
-    a.depth = tree.depth; a.prefix_len = kv[0].prefix_len; a.p_max = kv[0].prefix_len_max;
-    a.cap = kv[0].capacity; a.T = T_; a.nh = c.n_heads; a.theta = c.rope_theta;
-    a.n_spin = kFlowSpin;
-    p.multi[i] = gp.multi ? 1 : 0;
-    units[i < 1 ? 0 : i + 1] = gp.gpx * gp.S;
-    s.n_wg[i < 1 ? 0 : i + 1] = (unsigned)(n_xcd * gp.gpx * gp.S);
-  }
-  FlowAtt& A = s.att;
-  A.prefix_len = kv[0].prefix_len; A.anc = tree.anc_mask; A.p_max = kv[0].prefix_len_max;
-  A.n_words = tree.n_words; A.T = T_; A.nh = c.n_heads; A.cap = kv[0].capacity;
-  A.gx = B * ceil_div(T_, kAttQ);
-  A.total = A.gx * c.n_heads;
-  A.per_xcd = ceil_div(A.total, n_xcd);
-  A.status = status;
-  units[1] = A.per_xcd;
-  s.n_wg[1] = (unsigned)A.total;
-  p.ustart[0] = 0;
-  for (int i = 0; i < 5; ++i) p.ustart[i + 1] = p.ustart[i] + units[i];
-  s.off_g1 = pl.g1; s.off_g2 = pl.g2; s.off_wqkv = pl.wqkv; s.off_wo = pl.wo; s.off_wgu = pl.wgu;
-  s.off_wd = pl.wd; s.off_sqkv = pl.sqkv; s.off_so = pl.so; s.off_sgu = pl.sgu; s.off_sd = pl.sd;
-  s.w8 = w8 ? 1 : 0;
-  s.acts = (float*)(ws + wl.q);
-  s.act_stride = wl.flow_stride / 4;
-  s.off_q = 0; s.off_attn = (wl.attn - wl.q) / 4; s.off_act = (wl.act - wl.q) / 4;
-  s.off_x1 = (wl.flow_x1 - wl.q) / 4; s.off_x2 = (wl.flow_x2 - wl.q) / 4;
-  s.done = (unsigned*)(ws + wl.flow_done);
-  s.table = (FlowLayer*)(ws + wl.flow_tab);
-  p.table = s.table;
-  if (units_per_layer) *units_per_layer = p.ustart[5] * n_xcd;
-  if (timeline && timeline_len < (size_t)n_layers * p.ustart[5] * n_xcd * kFlowStamps) return SV_ERR_WORKSPACE;
-  // deeper stacks than the table holds: one launch per run of layers (a launch boundary orders
-  // and publishes everything, so the activation slots can be used again)
-  for (int l0 = 0; l0 < n_layers; l0 += kFlowMaxLayers) {
-    const int n = n_layers - l0 < kFlowMaxLayers ? n_layers - l0 : kFlowMaxLayers;
-    for (int l = 0; l < n; ++l) {
-      s.packed[l] = (const unsigned char*)packed[l0 + l];
-      s.kc[l] = (bf16_t*)kv[l0 + l].k;
-      s.vc[l] = (bf16_t*)kv[l0 + l].v;
+  uint4* xs = (uint4*)(ws + wl.rows_xs);
+  float* rstd = (float*)(ws + wl.rows_rstd);
+  float* part = (float*)(ws + wl.rows_part);
+  float* q = (float*)(ws + wl.q);
+  float* attn = (float*)(ws + wl.attn);
+  float* act = (float*)(ws + wl.act);
+  RowsArgs a;
+  memset(&a, 0, sizeof(a));
+  a.Xs = xs; a.M = M; a.m_tiles = wl.rows_pad / kRowsTM; a.n_xcd = n_xcd; a.part = part;
+  a.q_out = q; a.kc = (bf16_t*)kv.k; a.vc = (bf16_t*)kv.v; a.depth = tree.depth;
+  a.prefix_len = kv.prefix_len; a.p_max = kv.prefix_len_max; a.cap = kv.capacity; a.T = T_;
+  a.nh = c.n_heads; a.theta = c.rope_theta; a.act = act;
+  const int mb = wl.rows_pad / 32;
+  auto split = [&](const float* src, const float* gain, int K) {
+    if (gain) {
+      rows_rstd_kernel<<<M, 256, 0, st>>>(src, K, c.rms_eps, rstd);
+      split_rows_kernel<true><<<dim3(mb, K / 256), 256, 0, st>>>(src, gain, rstd, M, K, xs);
+    } else {
+      split_rows_kernel<false><<<dim3(mb, K / 256), 256, 0, st>>>(src, nullptr, nullptr, M, K, xs);
     }
-    s.n_layers = n;
-    s.x = x;
-    p.n_layers = n;
-    p.ts = timeline ? timeline + (size_t)l0 * p.ustart[5] * n_xcd * kFlowStamps : nullptr;
-    flow_setup_kernel<<<1, 64, 0, st>>>(s);
-    const dim3 grid(n_xcd, p.ustart[5] * n);
-    if (w8) verify_flow_kernel<true><<<grid, 256, 0, st>>>(p);
-    else verify_flow_kernel<false><<<grid, 256, 0, st>>>(p);
-  }
+  };
+  auto shape = [&](size_t w_off, int N, int K, int ksplit) {
+    a.Wp = (const uint4*)(packed + w_off); a.N = N; a.K = K; a.n_tiles = N / kRowsTN; a.ksplit = ksplit;
+    return dim3(n_xcd, ceil_div(a.n_tiles, n_xcd) * a.m_tiles, ksplit);
+  };
+  auto reduce_resid = [&](int ksplit) {
+    const size_t n4 = (size_t)M * H / 4;
+    rows_reduce_resid_kernel<<<(unsigned)((n4 + 255) / 256), 256, 0, st>>>(
+        part, ksplit, (size_t)wl.rows_pad * H, x, x, n4);
+  };
+  mark(0);
+  split(x, (const float*)(packed + pl.g1), H);
+  gemm_rows_kernel<EPI_QKV, false><<<shape(pl.wqkv, 3 * D, H, 1), 256, 0, st>>>(a);
+  mark(1);
+  mark(2);
+  tree_attention_mfma<4><<<dim3(B * ceil_div(T_, kAttQ), c.n_heads), 256, 0, st>>>(
+      q, (const bf16_t*)kv.k, (const bf16_t*)kv.v, kv.prefix_len, kv.prefix_len_max,
+      tree.anc_mask, tree.n_words, T_, c.n_heads, kv.capacity, attn);
+  mark(3);
+  split(attn, nullptr, D);
+  gemm_rows_kernel<EPI_RESID, true><<<shape(pl.wo, H, D, kRowsKsplit), 256, 0, st>>>(a);
+  reduce_resid(kRowsKsplit);
+  mark(4);
+  mark(5);
+  split(x, (const float*)(packed + pl.g2), H);
+  gemm_rows_kernel<EPI_SWIGLU, false><<<shape(pl.wgu, 2 * F, H, 1), 256, 0, st>>>(a);
+  mark(6);
+  mark(7);
+  split(act, nullptr, F);
+  gemm_rows_kernel<EPI_RESID, true><<<shape(pl.wd, H, F, kRowsKsplit), 256, 0, st>>>(a);
+  reduce_resid(kRowsKsplit);
+  mark(8);
   return launch_status();
-}
-
-// The single-launch form applies to bf16 models with one row tile whose layers share the
-// prefix lengths and the cache geometry.
-static bool flow_applies(const sv_model_cfg& c, int n_layers, const sv_kv_view* kv, int M) {
-  if (c.dtype == SV_F32 || M > kMTile) return false;
-  for (int l = 1; l < n_layers; ++l)
-    if (kv[l].prefix_len != kv[0].prefix_len || kv[l].prefix_len_max != kv[0].prefix_len_max ||
-        kv[l].capacity != kv[0].capacity)
-      return false;
-  return true;
 }
 
 template <typename T>
@@ -505,9 +484,14 @@ static int head_packed(const sv_model_cfg& c, const char* packed, const float* x
   a.status = (int*)(ws + wl.counters + wl.counter_bytes) - 1;   // the layers' status word
   a.eps = c.rms_eps;
   a.x_io = logits;
-  const dim3 grid(n_xcd, p.gpx * p.S, wl.m_tiles);
-  if (p.multi) gemm_stream_bf16<PRO_GAIN, EPI_OUT, true, false><<<grid, 256, 0, st>>>(a);
-  else gemm_stream_bf16<PRO_GAIN, EPI_OUT, false, false><<<grid, 256, 0, st>>>(a);
+  const dim3 grid(n_xcd, p.gpx * p.S * wl.m_tiles);
+  if (wl.m_tiles > 1) {
+    if (p.multi) gemm_stream_bf16<PRO_GAIN, EPI_OUT, true, false, true><<<grid, 256, 0, st>>>(a);
+    else gemm_stream_bf16<PRO_GAIN, EPI_OUT, false, false, true><<<grid, 256, 0, st>>>(a);
+  } else {
+    if (p.multi) gemm_stream_bf16<PRO_GAIN, EPI_OUT, true, false, false><<<grid, 256, 0, st>>>(a);
+    else gemm_stream_bf16<PRO_GAIN, EPI_OUT, false, false, false><<<grid, 256, 0, st>>>(a);
+  }
   argmax_rows_wide<<<n_rows, 256, 0, st>>>(logits, out_logits, n, lo, out_token);
   return launch_status();
 }
@@ -515,7 +499,6 @@ static int head_packed(const sv_model_cfg& c, const char* packed, const float* x
 }  // namespace sv
 
 using namespace sv;
-static_assert(kFlowStamps == SV_FLOW_STAMPS, "timeline stamps per workgroup");
 
 extern "C" {
 
@@ -696,8 +679,9 @@ static int verify_layer_checked(const sv_model_cfg* cfg, const void* packed, flo
   if (cfg->dtype == SV_F32)
     return verify_layer_f32(*cfg, (const char*)packed, x, *kv, *tree, B, (char*)workspace,
                             (hipStream_t)stream, ev);
-  if (!ev && flow_applies(*cfg, 1, kv, B * T))
-    return verify_flow_bf16(*cfg, 1, &packed, x, kv, *tree, B, (char*)workspace, (hipStream_t)stream);
+  if (cfg->dtype == SV_BF16 && ceil_div(B * T, kMTile) > kRowsMinTiles)
+    return verify_layer_rows(*cfg, (const char*)packed, x, *kv, *tree, B, (char*)workspace,
+                             (hipStream_t)stream, ev);
   return verify_layer_bf16(*cfg, (const char*)packed, x, *kv, *tree, B, (char*)workspace,
                            (hipStream_t)stream, ev);
 }
@@ -747,27 +731,12 @@ int sv_verify_stack(const sv_model_cfg* cfg, int n_layers, const void* const* pa
                     size_t ws_bytes, void* stream) {
   const int rc = verify_stack_args(cfg, n_layers, packed, x, kv, tree, B, workspace, ws_bytes);
   if (rc != SV_OK) return rc;
-  if (flow_applies(*cfg, n_layers, kv, B * tree->n_nodes))
-    return verify_flow_bf16(*cfg, n_layers, packed, x, kv, *tree, B, (char*)workspace,
-                            (hipStream_t)stream);
   for (int l = 0; l < n_layers; ++l) {
     const int r2 = verify_layer_checked(cfg, packed[l], x, kv + l, tree, B, workspace, ws_bytes,
                                         stream, nullptr);
     if (r2 != SV_OK) return r2;
   }
   return SV_OK;
-}
-
-int sv_verify_stack_timeline(const sv_model_cfg* cfg, int n_layers, const void* const* packed,
-                             float* x, const sv_kv_view* kv, const sv_tree* tree, int B,
-                             void* workspace, size_t ws_bytes, void* stream, long long* timeline,
-                             size_t timeline_len, int* workgroups_per_layer) {
-  const int rc = verify_stack_args(cfg, n_layers, packed, x, kv, tree, B, workspace, ws_bytes);
-  if (rc != SV_OK) return rc;
-  if (!timeline) return SV_ERR_NULL;
-  if (!flow_applies(*cfg, n_layers, kv, B * tree->n_nodes)) return SV_ERR_SHAPE;
-  return verify_flow_bf16(*cfg, n_layers, packed, x, kv, *tree, B, (char*)workspace,
-                          (hipStream_t)stream, timeline, timeline_len, workgroups_per_layer);
 }
 
 int sv_action_head_argmax(const sv_model_cfg* cfg, const void* g_final, const void* w_lm,

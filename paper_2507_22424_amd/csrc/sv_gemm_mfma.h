@@ -155,13 +155,6 @@ struct GemmArgs {
   const int32_t* prefix_len;
   int p_max, cap, T, nh;
   float theta;
-  // FLOW (all products of a pass in one launch): this product starts once *wait_cnt has
-  // reached wait_val (the workgroups of the product before it have all signalled), and every
-  // workgroup adds 1 to *done_cnt when its outputs are in memory.  n_spin bounds the wait.
-  const unsigned* wait_cnt;
-  unsigned wait_val;
-  unsigned* done_cnt;
-  int n_spin;
 };
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
@@ -348,17 +341,9 @@ __device__ inline int frag_slot(int l, int s) { return ((l & 31) ^ (((s & 7) << 
 // loop, where spilled scalars cost stalls between the matrix instructions.
 typedef const __attribute__((address_space(4))) GemmArgs* gemm_args_ptr_t;
 typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
-// Store that readers on other XCDs of the same launch may rely on (FLOW: written through to
-// memory at device scope; the signalling workgroup waits for its completion), or a plain store.
-template <bool DEV, typename T>
-__device__ __forceinline__ void store_out(__attribute__((address_space(1))) T* p, T v) {
-  if (DEV) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  else *p = v;
-}
-template <int PRO, int EPI, bool W8, bool FLOW>
+template <int PRO, int EPI, bool W8>
 __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos, int* s_crow,
-                                                  int tid, int lane, int wave, int xcd, int u, int mt,
-                                                  long long* ts = nullptr) {
+                                                  int tid, int lane, int wave, int xcd, int u, int mt) {
   GemmArgs a;                                // one batch of scalar loads; registers from here on
   {
     static_assert(sizeof(GemmArgs) % 4 == 0, "copied word by word");
@@ -377,7 +362,6 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
   const auto status = SV_GLOBAL(int, a.status);
   const auto x_io = SV_GLOBAL(float, a.x_io);
   const auto x_res = SV_GLOBAL(const float, a.x_res);
-  const auto done_cnt = SV_GLOBAL(unsigned, a.done_cnt);
   const auto act = SV_GLOBAL(float, a.act);
   const auto q_out = SV_GLOBAL(float, a.q_out);
   const auto kc = SV_GLOBAL(unsigned short, a.kc);
@@ -436,7 +420,6 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
     if (bad) __hip_atomic_fetch_or(status, bad, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   __syncthreads();
-  if (FLOW && ts && tid == 0) ts[3] = wall_clock64();
   asm volatile("buffer_inv sc0" ::: "memory");                      // drop stale L1 lines (the L2 is shared)
   // Row sums of all slices -> 1 / rms: every wave keeps the value of row `lane` and fetches
   // the rows it needs with a lane read.  The loads are only issued here; they are consumed
@@ -575,13 +558,13 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
 #pragma unroll
           for (int j = 0; j < 4; ++j)
             if (m0 + row0 + j < a.M)
-              store_out<FLOW>(x_io + ((size_t)(m0 + row0 + j) * a.N + tile * 32 + ln), xres[bi][j] + v[j]);
+              x_io[(size_t)(m0 + row0 + j) * a.N + tile * 32 + ln] = xres[bi][j] + v[j];
         }
         if (EPI == EPI_OUT) {
 #pragma unroll
           for (int j = 0; j < 4; ++j)
             if (m0 + row0 + j < a.M)
-              store_out<FLOW>(x_io + ((size_t)(m0 + row0 + j) * a.N + tile * 32 + ln), v[j]);
+              x_io[(size_t)(m0 + row0 + j) * a.N + tile * 32 + ln] = v[j];
         }
         if (EPI == EPI_SWIGLU) {             // lanes 0..15 gate, 16..31 up of the same column
           const int F = a.N / 2;
@@ -589,7 +572,7 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
           for (int j = 0; j < 4; ++j) {
             const float up = lane_xor16(v[j], lane);
             if (ln < 16 && m0 + row0 + j < a.M)
-              store_out<FLOW>(act + ((size_t)(m0 + row0 + j) * F + tile * 16 + ln), silu_fast(v[j]) * up);
+              act[(size_t)(m0 + row0 + j) * F + tile * 16 + ln] = silu_fast(v[j]) * up;
           }
         }
         if (EPI == EPI_QKV) {
@@ -615,10 +598,9 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
             }
             if (m0 + ml < a.M) {
               if (which == 0)
-                store_out<FLOW>(q_out + ((size_t)(m0 + ml) * D + head * 128 + dcol), val);
+                q_out[(size_t)(m0 + ml) * D + head * 128 + dcol] = val;
               else
-                store_out<FLOW>(cache + (((size_t)s_crow[ml] + (size_t)head * a.cap) * 128 + dcol),
-                                (unsigned short)f32_to_bf16(val).bits);
+                cache[((size_t)s_crow[ml] + (size_t)head * a.cap) * 128 + dcol] = f32_to_bf16(val).bits;
             }
           }
         }
@@ -630,15 +612,6 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
       __hip_atomic_fetch_add(gcnt + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(S - 1)) {
     gcnt[0] = 0;
     gcnt[1] = 0;
-  }
-  if (FLOW) {
-    // outputs of every wave are in memory, then the workgroup reports in
-    __builtin_amdgcn_s_waitcnt(0);
-    asm volatile("s_barrier" ::: "memory");
-    if (tid == 0) {
-      __hip_atomic_fetch_add(done_cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (ts) ts[4] = wall_clock64();
-    }
   }
 }
 
@@ -652,7 +625,6 @@ struct GemmLds {
   int* s_pos;           // EPI_QKV: rotary position of each row of the m tile
   int* s_crow;          // EPI_QKV: cache row (b * nh * cap + P + t) of each row
   float* s_rowscale;    // 2^-h of each row for this slice's partial tiles
-  int* s_flag;          // FLOW: result of the first look at the dependency word
 };
 __device__ __forceinline__ GemmLds carve_gemm_lds(uint4* base) {
   GemmLds l;
@@ -661,10 +633,9 @@ __device__ __forceinline__ GemmLds carve_gemm_lds(uint4* base) {
   l.s_pos = reinterpret_cast<int*>(base + kGemmXsVec + kGemmHeadVec);
   l.s_crow = l.s_pos + kMTile;
   l.s_rowscale = reinterpret_cast<float*>(l.s_crow + kMTile);
-  l.s_flag = reinterpret_cast<int*>(l.s_rowscale + kMTile);
   return l;
 }
-constexpr size_t kGemmLdsAlloc = kGemmLdsBytes + 16;     // + the flag word
+constexpr size_t kGemmLdsAlloc = kGemmLdsBytes;
 
 // One workgroup of the streaming GEMM: unit u of XCD xcd, row tile mt.  Launch shape of the
 // stand-alone kernel: grid = (n_xcd, gpx * S, m_tiles), block = 256, 1 workgroup per CU (LDS).
@@ -674,14 +645,12 @@ constexpr size_t kGemmLdsAlloc = kGemmLdsBytes + 16;     // + the flag word
 // form carries no re-staging code and nothing of it in registers through the main loop.
 // W8: the weights are E4M3 codes (four loads per piece, converted to bf16 fragments in
 // registers; the row scales are applied in the reduction).
-// FLOW: the workgroup is one of many products inside one launch: it requests its first weight
-// pieces, waits until the product before it has signalled completion (a bounded wait), reads its
-// activations (written through to memory by that product; the buffers of one launch are never
-// rewritten, so no cache holds an older copy), and writes its own outputs through to memory
-// before it signals.
-template <int PRO, int EPI, bool MULTI, bool W8, bool FLOW>
+// KEEP: the weights are read again, shortly afterwards, by the workgroups that multiply the
+// same tiles with the other row tiles (more than 64 rows): the loads are ordinary ones, which the
+// XCD's L2 keeps, instead of the non-temporal ones of the single-row-tile case.
+template <int PRO, int EPI, bool MULTI, bool W8, bool KEEP>
 __device__ __forceinline__ void gemm_stream_body(gemm_args_ptr_t ap, const int xcd, const int u,
-                                                 const int mt, const GemmLds lds, long long* ts = nullptr) {
+                                                 const int mt, const GemmLds lds) {
   const __attribute__((address_space(4))) GemmArgs& a = *ap;
   constexpr int kLoads = W8 ? kPieceFrags / 2 : kPieceFrags;   // 16-byte loads per piece and lane
   uint4* const xs = lds.xs;
@@ -691,11 +660,6 @@ __device__ __forceinline__ void gemm_stream_body(gemm_args_ptr_t ap, const int x
   uint4* const s_head = lds.s_head;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: bookkeeping stays in scalar registers
-  // measurement aid: device clock (100 MHz) at fixed points of this workgroup's life
-  auto stamp = [&](int i) {
-    if (FLOW && ts && tid == 0) ts[i] = wall_clock64();
-  };
-  stamp(0);
   const int m0 = mt * kMTile;
   const int K = a.K, S = a.S;
   // (workgroups are dealt to the XCDs in turn: xcd = linear workgroup index modulo n_xcd; u =
@@ -755,7 +719,7 @@ __device__ __forceinline__ void gemm_stream_body(gemm_args_ptr_t ap, const int x
     auto issue = [&](u32x4_t* buf) {
 #pragma unroll
       for (int f = 0; f < kLoads; ++f)        // streamed once: do not keep it in the caches
-        buf[f] = __builtin_nontemporal_load(ip + ((unsigned)lane + f * 64u));
+        buf[f] = KEEP ? ip[(unsigned)lane + f * 64u] : __builtin_nontemporal_load(ip + ((unsigned)lane + f * 64u));
       if (to_issue > 0) {
         ip += kLoads * 64;
         if (++ij == np) {
@@ -844,55 +808,18 @@ __device__ __forceinline__ void gemm_stream_body(gemm_args_ptr_t ap, const int x
       // 32 MB of weight requests in front of each other's X rows, and the X round trip - which
       // nothing can overlap - grows with the queue.  Spread over the conversion the same loads
       // still arrive before the main loop wants them (measured: 3.5 us per layer).
-      // FLOW: the activations exist only once the product before this one has signalled.  One
-      // look at its counter decides: if it is complete (the usual case for a workgroup that
-      // starts late in the hand-over) the order above is kept; otherwise the whole ring is
-      // requested first - the weights do not depend on anything - and the wait that follows
-      // costs nothing that the loads would not have cost anyway.
-      bool ready = true;
-      if (FLOW && a.wait_val != 0) {
-        const auto wc = (const __attribute__((address_space(1))) unsigned*)a.wait_cnt;
-        if (tid == 0)
-          *lds.s_flag = __hip_atomic_load(wc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= a.wait_val;
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        ready = __builtin_amdgcn_readfirstlane(*lds.s_flag) != 0;
-      }
       float4 xa[16], xb[16], g0, g1;
-      if (ready) {
-        x_load(0, xa, xb, g0, g1);
-        issue(ring[0]);
-        x_convert(0, xa, xb, g0, g1, [&](int r) {
-          static_assert(kRing == 4, "one slot every fourth row");
-          if (r == 4) issue(ring[1]);
-          if (r == 8) issue(ring[2]);
-          if (r == 12) issue(ring[3]);
-        });
-      } else {
-#pragma unroll
-        for (int sl = 0; sl < kRing; ++sl) issue(ring[sl]);
-        if (tid == 0) {
-          const auto wc = (const __attribute__((address_space(1))) unsigned*)a.wait_cnt;
-          int spin = 0;
-          while (__hip_atomic_load(wc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < a.wait_val) {
-            if (++spin > a.n_spin) {               // gave up: results are invalid, say so
-              __hip_atomic_fetch_or((__attribute__((address_space(1))) int*)a.status, 4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-              break;
-            }
-            __builtin_amdgcn_s_sleep(2);
-          }
-        }
-        asm volatile("s_barrier" ::: "memory");
-        // the workgroups of an XCD that share a K slice (one per tile group) all leave the wait at
-        // the same moment and ask for the same rows: later groups hold back a little, so that
-        // their requests find the lines the first one has brought into the L2
-        for (int i = 0; i < (ug & 3); ++i) __builtin_amdgcn_s_sleep(12);
-        x_load(0, xa, xb, g0, g1);
-        x_convert(0, xa, xb, g0, g1, [](int) {});
-      }
+      x_load(0, xa, xb, g0, g1);
+      issue(ring[0]);
+      x_convert(0, xa, xb, g0, g1, [&](int r) {
+        static_assert(kRing == 4, "one slot every fourth row");
+        if (r == 4) issue(ring[1]);
+        if (r == 8) issue(ring[2]);
+        if (r == 12) issue(ring[3]);
+      });
     }
     if (PRO == PRO_GAIN && n_chunks == 1) publish_ssq();
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // X chunk 0 is in LDS; weight loads stay in flight
-    stamp(1);
 
     f32x16_t acc0 = {}, acc1 = {};
     const int rbase = 4 * (lane >> 5);
@@ -1123,20 +1050,33 @@ __device__ __forceinline__ void gemm_stream_body(gemm_args_ptr_t ap, const int x
       }
     }
 
-    stamp(2);
     // ---- second half: group barrier, reduction, epilogue (arguments read afresh) ----
     gemm_args_ptr_t ap2 = ap;
     asm volatile("" : "+s"(ap2));
-    gemm_reduce_phase<PRO, EPI, W8, FLOW>(ap2, s_pos, s_crow, tid, lane, wave, xcd, u, mt, ts);
+    gemm_reduce_phase<PRO, EPI, W8>(ap2, s_pos, s_crow, tid, lane, wave, xcd, u, mt);
   }
 }
 
-// One product per launch: grid = (n_xcd, gpx * S, m_tiles), block = 256.
-template <int PRO, int EPI, bool MULTI, bool W8>
+// One product per launch, block = 256.
+//  - up to 64 rows (ROWS = false): grid = (n_xcd, gpx * S); y = unit.
+//  - more rows (ROWS = true): grid = (n_xcd, gpx * m_tiles * S); y = (group * m_tiles + row tile)
+//    * S + slice.  The S slices of one (group, row tile) follow each other - they meet at the
+//    group barrier and must be resident together - and the row tiles of one group follow each
+//    other on the same XCD: they stream the same weights at about the same time, so that all but
+//    the first find them in that XCD's L2 and the matrix leaves HBM about once per launch however
+//    many rows there are.
+template <int PRO, int EPI, bool MULTI, bool W8, bool ROWS>
 __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
   __shared__ uint4 lds_raw[(kGemmLdsAlloc + 15) / 16];
   gemm_args_ptr_t ap = (gemm_args_ptr_t)__builtin_amdgcn_kernarg_segment_ptr();
-  gemm_stream_body<PRO, EPI, MULTI, W8, false>(ap, blockIdx.x, blockIdx.y, blockIdx.z, carve_gemm_lds(lds_raw));
+  int u = blockIdx.y, mt = 0;
+  if (ROWS) {
+    const int m_tiles = (a.M + kMTile - 1) / kMTile;
+    const int sp = (int)blockIdx.y % a.S, gm = (int)blockIdx.y / a.S;
+    mt = gm % m_tiles;
+    u = (gm / m_tiles) * a.S + sp;
+  }
+  gemm_stream_body<PRO, EPI, MULTI, W8, ROWS>(ap, blockIdx.x, u, mt, carve_gemm_lds(lds_raw));
 }
 
 }  // namespace sv

@@ -1,0 +1,309 @@
+// The layer's products for MANY rows (several episodes verified together: hundreds of tree
+// rows) on the gfx950 matrix cores.
+//
+// With up to 64 rows the products are bound by the bytes of the weights and
+// gemm_stream_bf16 streams them once past activations that wait in LDS.  With hundreds of rows
+// the same products are bound by the matrix cores, and what has to be kept small is the traffic
+// per matrix instruction: every workgroup owns a 128-row x 256-column block of the output, keeps
+// it in accumulator registers and walks the whole K range; both operands arrive already cut into
+// matrix-core fragments (1 KiB = 32 rows x 16 k-values, lane-major), so a fragment travels from
+// memory into LDS with one direct-to-LDS load instruction per wave and from LDS into operand
+// registers with one 16-byte read per lane, without any shuffling:
+//   * weights: the packed layout of gemm_stream_bf16 as it is (same row permutations, so the
+//     RoPE / SwiGLU epilogues stay tile local);
+//   * activations: split_rows_kernel turns the float32 rows into hi + lo bf16 fragments once per
+//     product (RMSNorm applied on the way), so that the error of a product stays at float32
+//     rounding level as in the streaming kernel.
+// A ring of eight k-steps (16 KiB each: 8 activation + 8 weight fragments) lives in LDS; the
+// loads of a k-step are issued seven steps ahead, each wave waits for its own four loads with an
+// exact count and one barrier per k-step publishes them; operands of the next k-step are read
+// while the 16 matrix instructions of the current one run.
+// Workgroups are numbered so that an XCD works on four neighbouring column blocks times all row
+// blocks at a time: whatever two of them share is fetched into that XCD's L2 once.
+// Products with few columns (N = hidden) split K across two workgroups; their float32 partial
+// blocks are added in fixed order by rows_reduce_resid_kernel, which also adds the residual.
+#ifndef SV_GEMM_ROWS_H
+#define SV_GEMM_ROWS_H
+
+#include "sv_gemm_mfma.h"
+
+namespace sv {
+
+constexpr int kRowsTM = 128;        // rows of a workgroup's output block
+constexpr int kRowsTN = 256;        // columns
+constexpr int kRowsRing = 8;        // k-steps resident in LDS
+constexpr int kRowsFrags = 16;      // fragments per k-step: 4 row blocks x (hi, lo), 8 weight tiles
+constexpr int kRowsKsplit = 2;      // K split of the products with N = hidden (too few column blocks to fill the chip)
+constexpr int kRowsMinTiles = 2;    // more 64-row tiles than this: the products run on gemm_rows_kernel
+
+struct RowsArgs {
+  const uint4* Xs;       // activations as fragments: [M_pad / 32][K / 16][hi, lo][64 lanes]
+  const uint4* Wp;       // packed weights: [N / 32][K / 16][64 lanes]
+  int M, N, K;
+  int m_tiles, n_tiles;  // blocks of kRowsTM rows / kRowsTN columns
+  int n_xcd;
+  int ksplit;            // workgroups that share one output block along K (1 or 2)
+  float* part;           // ksplit > 1: [ksplit][m_tiles * kRowsTM][N] float32 partial sums
+  // epilogues (ksplit == 1), as in gemm_stream_bf16
+  float* act;            // EPI_SWIGLU: [M, N/2]
+  float* q_out;          // EPI_QKV
+  bf16_t* kc;
+  bf16_t* vc;
+  const int32_t* depth;
+  const int32_t* prefix_len;
+  int p_max, cap, T, nh;
+  float theta;
+};
+
+// 1 / sqrt(mean(x^2) + eps) of every row.  grid = rows, block = 256.
+__global__ __launch_bounds__(256) void rows_rstd_kernel(const float* __restrict__ x, int K, float eps,
+                                                        float* __restrict__ rstd) {
+  __shared__ float red[4];
+  const float* xr = x + (size_t)blockIdx.x * K;
+  float ss = 0.f;
+  for (int i = threadIdx.x * 4; i < K; i += 1024) {
+    const float4 v = *reinterpret_cast<const float4*>(xr + i);
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  ss = block_sum_256(ss, red);
+  if (threadIdx.x == 0) rstd[blockIdx.x] = 1.0f / sqrtf(ss / (float)K + eps);
+}
+
+// float32 rows -> hi + lo bf16 fragments.  GAIN: every value is first multiplied by gain[k] *
+// rstd[row] (RMSNorm).  Rows beyond M become zeros.  grid = (M_pad / 32, K / 256), block = 256:
+// a workgroup converts 32 rows x 256 k-values; one thread handles 8 consecutive k-values of a
+// row at a time, which are the 16 bytes one lane holds of a fragment.
+template <bool GAIN>
+__global__ __launch_bounds__(256) void split_rows_kernel(const float* __restrict__ x,
+                                                         const float* __restrict__ gain,
+                                                         const float* __restrict__ rstd, int M, int K,
+                                                         uint4* __restrict__ Xs) {
+  const int mb = blockIdx.x, kc = blockIdx.y;
+  const int nks = K / kFragK;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int c = it * 256 + threadIdx.x;
+    const int r = c >> 5, kq = c & 31;                  // row inside the block, 8-wide k chunk inside the 256
+    const int row = mb * 32 + r, k = kc * 256 + kq * 8;
+    float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (row < M) {
+      const float4 a0 = *reinterpret_cast<const float4*>(x + (size_t)row * K + k);
+      const float4 a1 = *reinterpret_cast<const float4*>(x + (size_t)row * K + k + 4);
+      v[0] = a0.x; v[1] = a0.y; v[2] = a0.z; v[3] = a0.w; v[4] = a1.x; v[5] = a1.y; v[6] = a1.z; v[7] = a1.w;
+      if (GAIN) {
+        const float rs = rstd[row];
+        const float4 g0 = *reinterpret_cast<const float4*>(gain + k);
+        const float4 g1 = *reinterpret_cast<const float4*>(gain + k + 4);
+        v[0] *= g0.x * rs; v[1] *= g0.y * rs; v[2] *= g0.z * rs; v[3] *= g0.w * rs;
+        v[4] *= g1.x * rs; v[5] *= g1.y * rs; v[6] *= g1.z * rs; v[7] *= g1.w * rs;
+      }
+    }
+    uint4 hi4, lo4;
+    hi4.x = pack_bf16x2(v[0], v[1]); hi4.y = pack_bf16x2(v[2], v[3]);
+    hi4.z = pack_bf16x2(v[4], v[5]); hi4.w = pack_bf16x2(v[6], v[7]);
+    lo4.x = pack_bf16x2(v[0] - bf16_lo_f32(hi4.x), v[1] - bf16_hi_f32(hi4.x));
+    lo4.y = pack_bf16x2(v[2] - bf16_lo_f32(hi4.y), v[3] - bf16_hi_f32(hi4.y));
+    lo4.z = pack_bf16x2(v[4] - bf16_lo_f32(hi4.z), v[5] - bf16_hi_f32(hi4.z));
+    lo4.w = pack_bf16x2(v[6] - bf16_lo_f32(hi4.w), v[7] - bf16_hi_f32(hi4.w));
+    const int ks = (k / kFragK), lane = r + 32 * (kq & 1);
+    uint4* dst = Xs + (((size_t)mb * nks + ks) * 2) * 64 + lane;
+    dst[0] = hi4;
+    dst[64] = lo4;
+  }
+}
+
+// x_io[m][n] = x_res[m][n] + part[0][m][n] + part[1][m][n] + ..  (fixed order).  One thread = 4 columns.
+__global__ __launch_bounds__(256) void rows_reduce_resid_kernel(const float* __restrict__ part, int ksplit,
+                                                                size_t plane, const float* x_res,
+                                                                float* x_io, size_t n_vec4) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n_vec4) return;
+  float4 s = reinterpret_cast<const float4*>(x_res)[i];
+  for (int z = 0; z < ksplit; ++z) {
+    const float4 p = reinterpret_cast<const float4*>(part + (size_t)z * plane)[i];
+    s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+  }
+  reinterpret_cast<float4*>(x_io)[i] = s;
+}
+
+// grid = (n_xcd, ceil(n_tiles / n_xcd) * m_tiles, ksplit), block = 256 (waves 2 x 2: rows wm * 64,
+// columns wn * 128 of the block).
+template <int EPI, bool SPLIT>
+__global__ __launch_bounds__(256, 1) void gemm_rows_kernel(const RowsArgs a) {
+  __shared__ uint4 ring[kRowsRing][kRowsFrags][64];          // 128 KiB
+  __shared__ int s_pos[kRowsTM], s_crow[kRowsTM];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int seq = blockIdx.y;
+  const int mt = seq % a.m_tiles, nt = (int)blockIdx.x + a.n_xcd * (seq / a.m_tiles);
+  if (nt >= a.n_tiles) return;
+  const int nks_all = a.K / kFragK;
+  const int nks = nks_all / a.ksplit, ks0 = (int)blockIdx.z * nks;
+  const int m0 = mt * kRowsTM;
+
+  if (EPI == EPI_QKV && tid < kRowsTM) {
+    const int m = min(m0 + tid, a.M - 1);
+    const int b = m / a.T, t = m - b * a.T;
+    int P = a.prefix_len[b];
+    P = P < 0 ? 0 : (P > a.p_max ? a.p_max : P);
+    s_pos[tid] = P + a.depth[m];
+    s_crow[tid] = b * a.nh * a.cap + P + t;
+  }
+
+  // this wave's four fragment loads per k-step: waves 0, 1 bring the activation fragments
+  // (row block f / 2, hi or lo), waves 2, 3 the weight fragments (tile f - 8)
+  typedef const __attribute__((address_space(1))) uint4* gptr_t;
+  gptr_t src[4];
+  size_t step;                                               // uint4 from one k-step to the next
+  if (wave < 2) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int f = 4 * wave + i;
+      src[i] = (gptr_t)a.Xs + ((((size_t)(mt * 4 + (f >> 1)) * nks_all + ks0) * 2 + (f & 1)) * 64 + lane);
+    }
+    step = 128;
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int f = 4 * (wave - 2) + i;
+      src[i] = (gptr_t)a.Wp + (((size_t)(nt * 8 + f) * nks_all + ks0) * 64 + lane);
+    }
+    step = 64;
+  }
+  // k-step j of this workgroup -> ring slot j % kRowsRing.  Past the last k-step the loads
+  // repeat it (into a slot nobody reads any more): the number of loads in flight stays fixed
+  // and the waits below are exact.
+  auto issue = [&](int j) {
+    const int jc = j < nks ? j : nks - 1;
+    const int slot = j & (kRowsRing - 1);
+    // Direct-to-LDS loads (lane l's 16 bytes land at the LDS address in M0 + 16 l), written as
+    // inline assembly: the compiler, when it sees such a load, waits for ALL outstanding loads
+    // before the next LDS read that might touch the same array, which would drain the ring at
+    // every k-step; the waits that are really needed are the explicit ones below.
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) void*)&ring[slot][4 * wave][0];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      gptr_t g = src[i] + (size_t)jc * step;
+      asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds0 + 1024u * i), "v"(g) : "memory");
+    }
+  };
+
+  f32x16_t acc[2][4];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = f32x16_t{};
+
+  struct Ops {
+    bf16x8_t ah[2], al[2], b[4];
+  };
+  auto read_ops = [&](int j, Ops& o) {
+    const int slot = j & (kRowsRing - 1);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      o.ah[i] = __builtin_bit_cast(bf16x8_t, ring[slot][2 * (2 * wm + i)][lane]);
+      o.al[i] = __builtin_bit_cast(bf16x8_t, ring[slot][2 * (2 * wm + i) + 1][lane]);
+    }
+#pragma unroll
+    for (int jn = 0; jn < 4; ++jn) o.b[jn] = __builtin_bit_cast(bf16x8_t, ring[slot][8 + 4 * wn + jn][lane]);
+  };
+  auto multiply = [&](const Ops& o) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int jn = 0; jn < 4; ++jn) {
+        acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.ah[i], o.b[jn], acc[i][jn], 0, 0, 0);
+        acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.al[i], o.b[jn], acc[i][jn], 0, 0, 0);
+      }
+  };
+
+  static_assert(kRowsRing == 8, "the wait counts below are written for a ring of eight");
+#pragma unroll
+  for (int j = 0; j < kRowsRing - 1; ++j) issue(j);
+  // k-step 0 complete: own loads (6 younger k-steps x 4 may still be in flight), then everybody's
+  asm volatile("s_waitcnt vmcnt(24)\n\ts_barrier" ::: "memory");
+  Ops o0, o1;
+  read_ops(0, o0);
+  // One iteration = k-step ks: wait for k-step ks + 1 (own loads, then the barrier, which also
+  // tells that every wave is done with the slot of k-step ks - 1), refill that slot, read the
+  // operands of ks + 1, multiply ks.
+  auto iteration = [&](int ks, const Ops& cur, Ops& nxt) {
+    asm volatile("s_waitcnt vmcnt(20)\n\ts_barrier" ::: "memory");
+    issue(ks + kRowsRing - 1);
+    read_ops(ks + 1, nxt);
+    multiply(cur);
+  };
+  for (int ks = 0; ks < nks; ks += 2) {          // nks is even (K is a multiple of 256)
+    iteration(ks, o0, o1);
+    iteration(ks + 1, o1, o0);
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing of the ring is in flight when the wave ends
+
+  // ---- output: register r of lane l of block (i, jn) is row 8*(r/4) + 4*(l/32) + r%4, column l%32 ----
+  // The 128 accumulator registers of a lane go through LDS (the ring is free now: 32 KiB per
+  // wave) and come back four at a time inside a loop, so that the epilogue is a short piece of
+  // code run 32 times instead of 40 KiB of straight-line code fetched for a single pass.
+  asm volatile("s_barrier" ::: "memory");            // every wave has read its last operands
+  f32x4_t* stage = reinterpret_cast<f32x4_t*>(&ring[0][0][0]) + (size_t)wave * (32 * 64) + lane;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int jn = 0; jn < 4; ++jn)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        stage[((i * 4 + jn) * 4 + q) * 64] = f32x4_t{acc[i][jn][4 * q], acc[i][jn][4 * q + 1], acc[i][jn][4 * q + 2], acc[i][jn][4 * q + 3]};
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // (own data only: no barrier needed)
+  const int ln = lane & 31, rbase = 4 * (lane >> 5);
+#pragma unroll 1
+  for (int item = 0; item < 32; ++item) {
+    const int i = item >> 4, jn = (item >> 2) & 3, q = item & 3;
+    const int tile = nt * 8 + wn * 4 + jn;               // 32-row weight tile = 32 output columns
+    const int ml0 = wm * 64 + i * 32 + 8 * q + rbase;    // row inside the block of the first value
+    const f32x4_t vv = stage[item * 64];
+    float v[4] = {vv[0], vv[1], vv[2], vv[3]};
+    if (SPLIT) {
+      float* dst = a.part + ((size_t)blockIdx.z * a.m_tiles * kRowsTM + m0 + ml0) * a.N + tile * 32 + ln;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) dst[(size_t)j * a.N] = v[j];
+    } else if (EPI == EPI_SWIGLU) {                      // lanes 0..15 gate, 16..31 up of the same column
+      const int F = a.N / 2;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float up = lane_xor16(v[j], lane);
+        if (ln < 16 && m0 + ml0 + j < a.M)
+          a.act[(size_t)(m0 + ml0 + j) * F + tile * 16 + ln] = silu_fast(v[j]) * up;
+      }
+    } else if (EPI == EPI_QKV) {
+      const int tiles_per_mat = a.nh * 4;
+      const int which = tile / tiles_per_mat;
+      const int head = (tile % tiles_per_mat) / 4, uq = tile % 4;
+      const int jr = 16 * uq + (ln & 15);
+      const int dcol = jr + 64 * (ln >> 4);
+      const float turn_freq = exp2f(-(float)jr * (1.0f / 64.0f) * log2f(a.theta)) * 0.15915494309189535f;
+      const float sgn = (ln & 16) ? 1.0f : -1.0f;
+      const int D = a.nh * 128;
+      bf16_t* cache = which == 1 ? a.kc : a.vc;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int ml = ml0 + j;
+        float val = v[j];
+        const float partner = lane_xor16(val, lane);
+        if (which != 2) {
+          float turns = (float)s_pos[ml] * turn_freq;
+          turns -= floorf(turns);
+          val = val * __builtin_amdgcn_cosf(turns) + sgn * partner * __builtin_amdgcn_sinf(turns);
+        }
+        if (m0 + ml < a.M) {
+          if (which == 0)
+            a.q_out[(size_t)(m0 + ml) * D + head * 128 + dcol] = val;
+          else
+            cache[((size_t)s_crow[ml] + (size_t)head * a.cap) * 128 + dcol] = f32_to_bf16(val);
+        }
+      }
+    }
+  }
+}
+
+}  // namespace sv
+#endif

@@ -102,12 +102,11 @@ inline PackedLayout packed_layout(const sv_model_cfg& c) {
 struct WorkspaceLayout {
   size_t counters, sumsq, part, xhat, q, attn, act, head_z, head_logits, total;
   size_t counter_bytes, part_bytes;
-  // single-launch form (bf16, one row tile): per-layer activation slots (q, attn, act, x1, x2;
-  // slot 0 starts at `q`, the slots are flow_stride bytes apart), launch table, completion counters
-  size_t flow_x1, flow_x2, flow_stride, flow_tab, flow_done;
-  int flow_layers;
   // packed head (bf16, scored rows a multiple of 32): its own counters, row sums, partial tiles
   size_t head_cnt, head_cnt_bytes, head_sumsq, head_part, head_part_bytes;
+  // many rows (matrix-core bound products): activation fragments, 1 / rms, split-K partial blocks
+  size_t rows_xs, rows_rstd, rows_part;
+  int rows_pad;
   int m_pad, m_tiles;
   int ucap, tstride, head_ucap, head_tstride;   // per-XCD extents of the split-K scratch regions (units, partial tiles)
 };
