@@ -82,6 +82,15 @@ static void scratch_extent(int N, int K, int* ucap, int* tstride) {
   }
 }
 
+// Workgroups that share the keys of one (episode, head, 16 queries) task of the tree attention:
+// more than one where the tasks alone would leave the chip short of waves (long prefix, one
+// episode), at least 8 key tiles each.
+static int attention_splits(int n_tasks, int n_keys) {
+  int s = 1;
+  while (s < 8 && n_tasks * s < kAttSplitFill && (n_keys / kAttKeys) / (2 * s) >= 8) s *= 2;
+  return s;
+}
+
 static int device_xcds() {
   static int cached[64] = {0};               // hardware facts only; a race rewrites the same value
   int dev = 0;
@@ -142,6 +151,12 @@ static WorkspaceLayout workspace_layout(const sv_model_cfg& c, int m_rows, int n
     L.rows_xs = o;   o = align_up(o + (size_t)L.rows_pad * k_max * 4, kAlign);
     L.rows_rstd = o; o = align_up(o + (size_t)L.rows_pad * 4, kAlign);
     L.rows_part = o; o = align_up(o + (size_t)kRowsKsplit * L.rows_pad * H * 4, kAlign);
+  }
+  // partial results of the tree attention when the keys of a task are split (bf16 models)
+  L.att_part = 0;
+  if (c.dtype != SV_F32) {
+    L.att_part = o;
+    o = align_up(o + (size_t)8 * mp * c.n_heads * kAttPartStride * 4, kAlign);
   }
   L.head_z = o;      o = align_up(o + mp * H * 4, kAlign);
   L.head_logits = o; o = align_up(o + mp * (size_t)(n_scored > 0 ? n_scored : 0) * 4 * 16, kAlign);   // up to 16 K-slice planes
@@ -311,9 +326,14 @@ static int verify_layer_bf16(const sv_model_cfg& c, const char* packed, float* x
   SV_LAUNCH_GEMM(PRO_GAIN, EPI_QKV);
   mark(1);
   mark(2);
-  tree_attention_mfma<4><<<dim3(B * ceil_div(T_, kAttQ), c.n_heads), 256, 0, st>>>(
-      q, (const bf16_t*)kv.k, (const bf16_t*)kv.v, kv.prefix_len, kv.prefix_len_max,
-      tree.anc_mask, tree.n_words, T_, c.n_heads, kv.capacity, attn);
+  {
+    const int ns = attention_splits(B * ceil_div(T_, kAttQ) * c.n_heads, kv.prefix_len_max + T_);
+    float* apart = (float*)(ws + wl.att_part);
+    tree_attention_mfma<4><<<dim3(B * ceil_div(T_, kAttQ), c.n_heads, ns), 256, 0, st>>>(
+        q, (const bf16_t*)kv.k, (const bf16_t*)kv.v, kv.prefix_len, kv.prefix_len_max,
+        tree.anc_mask, tree.n_words, T_, c.n_heads, kv.capacity, attn, apart, M);
+    if (ns > 1) attention_merge_kernel<<<dim3(M, c.n_heads), 128, 0, st>>>(apart, ns, M, c.n_heads, attn);
+  }
   mark(3);
   a.X = attn; a.gain = nullptr; a.Wp = (const uint4*)(packed + pl.wo);
   a.wscale = w8 ? (const float*)(packed + pl.so) : nullptr;
@@ -388,9 +408,14 @@ static int verify_layer_rows(const sv_model_cfg& c, const char* packed, float* x
   gemm_rows_kernel<EPI_QKV, false><<<shape(pl.wqkv, 3 * D, H, 1), 256, 0, st>>>(a);
   mark(1);
   mark(2);
-  tree_attention_mfma<4><<<dim3(B * ceil_div(T_, kAttQ), c.n_heads), 256, 0, st>>>(
-      q, (const bf16_t*)kv.k, (const bf16_t*)kv.v, kv.prefix_len, kv.prefix_len_max,
-      tree.anc_mask, tree.n_words, T_, c.n_heads, kv.capacity, attn);
+  {
+    const int ns = attention_splits(B * ceil_div(T_, kAttQ) * c.n_heads, kv.prefix_len_max + T_);
+    float* apart = (float*)(ws + wl.att_part);
+    tree_attention_mfma<4><<<dim3(B * ceil_div(T_, kAttQ), c.n_heads, ns), 256, 0, st>>>(
+        q, (const bf16_t*)kv.k, (const bf16_t*)kv.v, kv.prefix_len, kv.prefix_len_max,
+        tree.anc_mask, tree.n_words, T_, c.n_heads, kv.capacity, attn, apart, M);
+    if (ns > 1) attention_merge_kernel<<<dim3(M, c.n_heads), 128, 0, st>>>(apart, ns, M, c.n_heads, attn);
+  }
   mark(3);
   split(attn, nullptr, D);
   gemm_rows_kernel<EPI_RESID, true><<<shape(pl.wo, H, D, kRowsKsplit), 256, 0, st>>>(a);
@@ -444,16 +469,14 @@ static int pack_layer_t(const sv_model_cfg& c, const sv_layer_weights& w, char* 
   return launch_status();
 }
 
+// z: [n_rows, H] float32 normalised rows; parts: [planes][m_pad * n] float32 logit planes.
 template <typename T>
 static int head_t(const sv_model_cfg& c, const T* g_final, const T* w_lm, const float* x,
-                  int n_rows, int lo, int hi, int32_t* out_token, float* out_logits, char* ws,
-                  hipStream_t st) {
-  const WorkspaceLayout wl = workspace_layout(c, n_rows, hi - lo);
+                  int n_rows, int lo, int hi, int32_t* out_token, float* out_logits, float* z,
+                  float* parts, hipStream_t st) {
   const int H = c.hidden, n = hi - lo;
-  float* z = (float*)(ws + wl.head_z);
-  float* parts = (float*)(ws + wl.head_logits);
   const int planes = head_planes(H);
-  const size_t plane = (size_t)wl.m_pad * n;
+  const size_t plane = (size_t)ceil_div(n_rows, kMTile) * kMTile * n;
   rmsnorm_rows_tg<T, float><<<n_rows, 256, 0, st>>>(x, g_final, z, H, c.rms_eps);
   dim3 grid(ceil_div(n, 64), ceil_div(n_rows, 64), planes);   // K cut into `planes` slices
   gemm_nt_fma<float, T><<<grid, 256, 0, st>>>(z, H, w_lm + (size_t)lo * H, H, parts, n, plane,
@@ -752,11 +775,14 @@ int sv_action_head_argmax(const sv_model_cfg* cfg, const void* g_final, const vo
   if (((uintptr_t)workspace % kAlign) ||
       ws_bytes < workspace_layout(*cfg, n_rows, vocab_hi - vocab_lo).total)
     return SV_ERR_WORKSPACE;
+  const WorkspaceLayout wl = workspace_layout(*cfg, n_rows, vocab_hi - vocab_lo);
+  float* z = (float*)((char*)workspace + wl.head_z);
+  float* parts = (float*)((char*)workspace + wl.head_logits);
   if (cfg->dtype == SV_F32)
     return head_t<float>(*cfg, (const float*)g_final, (const float*)w_lm, x, n_rows, vocab_lo,
-                         vocab_hi, out_token, out_logits, (char*)workspace, (hipStream_t)stream);
+                         vocab_hi, out_token, out_logits, z, parts, (hipStream_t)stream);
   return head_t<bf16_t>(*cfg, (const bf16_t*)g_final, (const bf16_t*)w_lm, x, n_rows, vocab_lo,
-                        vocab_hi, out_token, out_logits, (char*)workspace, (hipStream_t)stream);
+                        vocab_hi, out_token, out_logits, z, parts, (hipStream_t)stream);
 }
 
 int sv_packed_head_bytes(const sv_model_cfg* cfg, int vocab_lo, int vocab_hi, size_t* bytes) {

@@ -27,6 +27,7 @@ namespace sv {
 
 constexpr int kAttQ = 16;        // queries per workgroup
 constexpr int kAttKeys = 32;     // keys per tile
+constexpr int kAttSplitFill = 256;   // split the keys of a task while there are fewer workgroups than this
 constexpr int kVtPitch = 72;     // LDS per wave = 128 * kVtPitch bytes (V tile in the loop, merge buffer after it)
 // V tile in LDS: 288 bytes per key row (a row starts 8 banks after the one before), and rows
 // 8..15 of every 16 hold their two 128-byte halves swapped: the 32 lanes that read together
@@ -67,12 +68,18 @@ __device__ inline void split8(const float* v, bf16x8_t& hi, bf16x8_t& lo) {
 // (for readers on other XCDs inside the same launch).
 // head_dim = 128.
 // q: float32 [M, nh*128] (rotated);  kc, vc: bf16 [B][nh][cap][128];  out: float32 [M, nh*128].
+// Long prefixes: the key tiles can be dealt to n_split workgroups (split = which of them this
+// is); each then leaves, per query, its unnormalised output, running maximum and sum in
+// `part` ([n_split][M][nh][kAttPartStride] floats) and attention_merge_kernel combines them in
+// split order.  With n_split = 1 the result goes straight to `out`.
+constexpr int kAttPartStride = 132;   // 128 outputs, maximum, sum, padding
 template <int NW, bool DEV_OUT, typename Sync>
 __device__ inline void tree_attention_body(
     const float* __restrict__ q, const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc,
     const int32_t* __restrict__ prefix_len, int p_max, const uint64_t* __restrict__ anc,
     int n_words, int T, int nh, int cap, float* __restrict__ out, int bx, int by,
-    unsigned char* lds_raw, float (*s_m)[kAttQ], float (*s_l)[kAttQ], int tid, Sync sync) {
+    unsigned char* lds_raw, float (*s_m)[kAttQ], float (*s_l)[kAttQ], int tid, Sync sync,
+    int split = 0, int n_split = 1, float* __restrict__ part = nullptr, int M_total = 0) {
   const int lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 4, c = lane & 15;      // lane group (0..3), column = query
   const int qblocks = (T + kAttQ - 1) / kAttQ;
@@ -82,7 +89,10 @@ __device__ inline void tree_attention_body(
   int P = prefix_len[b];
   P = P < 0 ? 0 : (P > p_max ? p_max : P);
   const int nkeys = P + T;
-  const int ntiles = (nkeys + kAttKeys - 1) / kAttKeys;
+  const int ntiles_all = (nkeys + kAttKeys - 1) / kAttKeys;
+  // this workgroup's run of key tiles [t_first, ntiles)
+  const int t_first = (int)(((long long)ntiles_all * split) / n_split);
+  const int ntiles = (int)(((long long)ntiles_all * (split + 1)) / n_split);
   const int tq = min(qb * kAttQ + c, T - 1);   // this lane's query node (clamped in the tail)
   const size_t mrow = (size_t)b * T + tq;
   const bf16_t* kbase = kc + ((size_t)b * nh + h) * cap * 128;
@@ -131,7 +141,7 @@ __device__ inline void tree_attention_body(
   for (int dt = 0; dt < 8; ++dt) o[dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   float m_run = kNegBig, l_run = 0.f;
 
-  int t = wave;
+  int t = t_first + wave;
   if (t < ntiles) load_tile(t);
   for (; t < ntiles; t += NW) {
     // ---- S^T = K Q^T for the two 16-key sub-tiles ----
@@ -178,6 +188,9 @@ __device__ inline void tree_attention_body(
     tile_max = fmaxf(tile_max, __shfl_xor(tile_max, 16, kWave));
     tile_max = fmaxf(tile_max, __shfl_xor(tile_max, 32, kWave));
     const float m_new = fmaxf(m_run, tile_max);
+    // the running maximum moves in the first tiles and rarely afterwards: the rescaling of the
+    // 32 output registers is skipped when no query of the wave needs it
+    const bool rescale = __builtin_amdgcn_ballot_w64(m_new != m_run) != 0;
     const float corr = __expf(m_run - m_new);
     float psum = 0.f;
 #pragma unroll
@@ -187,7 +200,7 @@ __device__ inline void tree_attention_body(
     }
     psum += __shfl_xor(psum, 16, kWave);
     psum += __shfl_xor(psum, 32, kWave);
-    l_run = l_run * corr + psum;
+    l_run = (rescale ? l_run * corr : l_run) + psum;
     m_run = m_new;
     bf16x8_t ph, pl;
     split8(p, ph, pl);
@@ -208,7 +221,9 @@ __device__ inline void tree_attention_body(
       const uint2 va2 = __builtin_bit_cast(uint2, va), vb2 = __builtin_bit_cast(uint2, vb);
       const bf16x8_t v8 = __builtin_bit_cast(bf16x8_t, make_uint4(va2.x, va2.y, vb2.x, vb2.y));
       f32x4_t acc = o[dt];
-      acc[0] *= corr; acc[1] *= corr; acc[2] *= corr; acc[3] *= corr;
+      if (rescale) {
+        acc[0] *= corr; acc[1] *= corr; acc[2] *= corr; acc[3] *= corr;
+      }
       acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v8, ph, acc, 0, 0, 0);
       acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v8, pl, acc, 0, 0, 0);
       o[dt] = acc;
@@ -247,24 +262,34 @@ __device__ inline void tree_attention_body(
       }
       const int tnode = qb * kAttQ + qq;
       if (tnode < T) {
-        float* dst = out + ((size_t)b * T + tnode) * D + h * 128 + d;
-        if (DEV_OUT)
-          __hip_atomic_store((__attribute__((address_space(1))) float*)dst, num / den, __ATOMIC_RELAXED,
-                             __HIP_MEMORY_SCOPE_AGENT);
-        else
-          *dst = num / den;
+        if (n_split > 1) {
+          float* dst = part + (((size_t)split * M_total + (size_t)b * T + tnode) * nh + h) * kAttPartStride;
+          dst[d] = num;
+          if (d == 0) {
+            dst[128] = m_all;
+            dst[129] = den;
+          }
+        } else {
+          float* dst = out + ((size_t)b * T + tnode) * D + h * 128 + d;
+          if (DEV_OUT)
+            __hip_atomic_store((__attribute__((address_space(1))) float*)dst, num / den, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+          else
+            *dst = num / den;
+        }
       }
     }
   }
 }
 
-// grid = (B * ceil(T / 16), n_heads), block = 64 * NW (NW waves split the keys; at 340 keys the
-// kernel is latency bound and 8 waves measured slower than 4).
+// grid = (B * ceil(T / 16), n_heads, n_split), block = 64 * NW (NW waves split the keys; at 340
+// keys the kernel is latency bound and 8 waves measured slower than 4).
 template <int NW>
 __global__ __launch_bounds__(64 * NW) void tree_attention_mfma(
     const float* __restrict__ q, const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc,
     const int32_t* __restrict__ prefix_len, int p_max, const uint64_t* __restrict__ anc,
-    int n_words, int T, int nh, int cap, float* __restrict__ out) {
+    int n_words, int T, int nh, int cap, float* __restrict__ out, float* __restrict__ part,
+    int M_total) {
   // per wave: transposed V tile [128 d][32 keys] with padded rows; reused for the merge
   __shared__ __attribute__((aligned(16))) unsigned char lds_raw[NW * 128 * kVtPitch];
   __shared__ float s_m[NW][kAttQ], s_l[NW][kAttQ];
@@ -272,12 +297,35 @@ __global__ __launch_bounds__(64 * NW) void tree_attention_mfma(
   // L2: the tasks are renumbered so that an XCD gets a contiguous run of (head, query tile)
   // pairs - the query tiles of one head then read that head's K/V through one L2 instead of
   // fetching it from HBM once per XCD.
-  const unsigned total = gridDim.x * gridDim.y, lin = blockIdx.x + gridDim.x * blockIdx.y;
-  const unsigned task = (total & 7u) ? lin : (lin & 7u) * (total >> 3) + (lin >> 3);
+  // (the splits of one task follow each other on the same XCD)
+  const unsigned ns = gridDim.z;
+  const unsigned total = gridDim.x * gridDim.y * ns;
+  const unsigned lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+  const unsigned item = (total & 7u) ? lin : (lin & 7u) * (total >> 3) + (lin >> 3);
+  const unsigned task = item / ns, split = item - task * ns;
   const unsigned head = task / gridDim.x;
   tree_attention_body<NW, false>(q, kc, vc, prefix_len, p_max, anc, n_words, T, nh, cap, out,
                                  (int)(task - head * gridDim.x), (int)head, lds_raw, s_m, s_l,
-                                 (int)threadIdx.x, [] { __syncthreads(); });
+                                 (int)threadIdx.x, [] { __syncthreads(); }, (int)split, (int)ns, part,
+                                 M_total);
+}
+
+// out[m][h*128 + d] = sum_s e^(m_s - m) num_s[d] / sum_s e^(m_s - m) den_s, m = max_s m_s, the
+// splits taken in order.  grid = (M, n_heads), block = 128 (thread = d).
+__global__ __launch_bounds__(128) void attention_merge_kernel(const float* __restrict__ part, int n_split,
+                                                              int M, int nh, float* __restrict__ out) {
+  const int m = blockIdx.x, h = blockIdx.y, d = threadIdx.x;
+  float m_all = kNegBig;
+  for (int s = 0; s < n_split; ++s)
+    m_all = fmaxf(m_all, part[(((size_t)s * M + m) * nh + h) * kAttPartStride + 128]);
+  float num = 0.f, den = 0.f;
+  for (int s = 0; s < n_split; ++s) {
+    const float* p = part + (((size_t)s * M + m) * nh + h) * kAttPartStride;
+    const float sc = __expf(p[128] - m_all);
+    num += sc * p[d];
+    den += sc * p[129];
+  }
+  out[(size_t)m * nh * 128 + h * 128 + d] = num / den;
 }
 
 }  // namespace sv

@@ -106,6 +106,7 @@ struct WorkspaceLayout {
   size_t head_cnt, head_cnt_bytes, head_sumsq, head_part, head_part_bytes;
   // many rows (matrix-core bound products): activation fragments, 1 / rms, split-K partial blocks
   size_t rows_xs, rows_rstd, rows_part;
+  size_t att_part;               // split tree attention: per split, query and head the unnormalised output, maximum, sum
   int rows_pad;
   int m_pad, m_tiles;
   int ucap, tstride, head_ucap, head_tstride;   // per-XCD extents of the split-K scratch regions (units, partial tiles)

@@ -141,8 +141,10 @@ def test_f32_odd_shapes(T, B, P):
 
 # ---- bf16, small model: several tiles, ragged prefixes, 2e-2 -------------------------------
 
-@pytest.mark.parametrize("T,B,P", [(26, 3, 90), (60, 1, 280), (128, 1, 300), (70, 2, 40)])
+@pytest.mark.parametrize("T,B,P", [(26, 3, 90), (60, 1, 280), (128, 1, 300), (70, 2, 40), (26, 1, 1200)])
 def test_bf16_small_model(T, B, P):
+    """Several row tiles, ragged prefixes; the last case has so few (episode, head, query block)
+    tasks and so long a prefix that the tree attention splits its keys across workgroups."""
     cfg = wl.C2.scaled(name=f"bf16-small-T{T}-B{B}", index=20 + B, n_layers=3, hidden=512,
                        n_heads=4, head_dim=128, mlp_dim=1536, vocab=1024, n_bins=256,
                        tree_nodes=T, n_episodes=B, prefix_lo=max(1, P - 50), prefix_hi=P,
