@@ -214,6 +214,19 @@ int sv_action_head_argmax(const sv_model_cfg *cfg, const void *g_final, const vo
                           int32_t *out_token, float *out_logits, void *workspace,
                           size_t ws_bytes, void *stream);
 
+/* sv_action_head_argmax for callers that cannot allocate device memory and have no workspace to
+ * hand over: code recorded into a HIP graph, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same kernels, same results; the scratch (normalised rows, logit planes: 3 MiB) is
+ * a fixed array inside the library image, one copy per GPU for the life of the process.  The
+ * call allocates nothing and frees nothing.  Limits: n_rows <= 64, vocab_hi - vocab_lo <= 256,
+ * hidden <= 8192; beyond them SV_ERR_WORKSPACE and nothing is launched.  All calls on one GPU
+ * share that GPU's array: calls that overlap in time on one GPU (different streams or threads)
+ * race; calls on one stream are ordered and fine.  Every byte a call reads from the array it
+ * has written itself first, so nothing needs clearing between calls. */
+int sv_action_head_argmax_noalloc(const sv_model_cfg *cfg, const void *g_final, const void *w_lm,
+                                  const float *x, int n_rows, int vocab_lo, int vocab_hi,
+                                  int32_t *out_token, float *out_logits, void *stream);
+
 /* The same head for bf16 models (SV_BF16, SV_BF16_W8) on the streaming matrix-core kernel of
  * the layers: the head rows [vocab_lo, vocab_hi) are re-tiled once at load time, and every
  * call then reads them once at streaming speed (final RMSNorm, Eq. 1; Sec. 4.3 for the

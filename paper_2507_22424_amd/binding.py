@@ -26,7 +26,7 @@ EXPORTS = ("sv_version", "sv_strerror", "sv_tree_build_masks", "sv_packed_layer_
            "sv_pack_layer", "sv_pack_layer_w8", "sv_workspace_bytes", "sv_workspace_init", "sv_workspace_region",
            "sv_verify_layer",
            "sv_verify_layer_timed", "sv_verify_stack",
-           "sv_action_head_argmax", "sv_packed_head_bytes", "sv_pack_head",
+           "sv_action_head_argmax", "sv_action_head_argmax_noalloc", "sv_packed_head_bytes", "sv_pack_head",
            "sv_action_head_argmax_packed", "sv_stream_read", "sv_relaxed_accept",
            "sv_commit_path", "sv_advance_prefix", "sv_tree_build_device")
 SV_N_TIMING_EVENTS = 9
@@ -98,6 +98,9 @@ def lib() -> C.CDLL:
         l.sv_action_head_argmax.argtypes = [C.POINTER(ModelCfg), C.c_void_p, C.c_void_p, C.c_void_p,
                                             C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                             C.c_void_p, C.c_size_t, C.c_void_p]
+        l.sv_action_head_argmax_noalloc.argtypes = [C.POINTER(ModelCfg), C.c_void_p, C.c_void_p,
+                                                    C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p,
+                                                    C.c_void_p, C.c_void_p]
         l.sv_packed_head_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int, C.c_int, C.POINTER(C.c_size_t)]
         l.sv_pack_head.argtypes = [C.POINTER(ModelCfg), C.c_void_p, C.c_void_p, C.c_int, C.c_int,
                                    C.c_void_p, C.c_size_t, C.c_void_p]
@@ -276,6 +279,23 @@ def sv_action_head_argmax(cfg: ModelCfg, g_final: torch.Tensor, w_lm: torch.Tens
         _dev(out_token, torch.int32, "out_token"), _dev(out_logits, torch.float32, "out_logits"),
         _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)),
         "sv_action_head_argmax")
+
+
+def sv_action_head_argmax_noalloc(cfg: ModelCfg, g_final: torch.Tensor, w_lm: torch.Tensor,
+                                  x: torch.Tensor, n_rows: int, vocab_lo: int, vocab_hi: int,
+                                  out_token: torch.Tensor, out_logits: Optional[torch.Tensor],
+                                  stream=None) -> None:
+    dt = storage_dtype(cfg)
+    if w_lm.numel() != cfg.vocab * cfg.hidden or x.numel() < n_rows * cfg.hidden:
+        raise ValueError("w_lm must be [vocab, hidden] and x [n_rows, hidden]")
+    if out_token.numel() < n_rows or (out_logits is not None and
+                                      out_logits.numel() < n_rows * (vocab_hi - vocab_lo)):
+        raise ValueError("output tensors too small")
+    _check(lib().sv_action_head_argmax_noalloc(
+        C.byref(cfg), _dev(g_final, dt, "g_final"), _dev(w_lm, dt, "w_lm"),
+        _dev(x, torch.float32, "x"), n_rows, vocab_lo, vocab_hi,
+        _dev(out_token, torch.int32, "out_token"), _dev(out_logits, torch.float32, "out_logits"),
+        _stream(stream)), "sv_action_head_argmax_noalloc")
 
 
 def sv_packed_head_bytes(cfg: ModelCfg, vocab_lo: int, vocab_hi: int) -> int:

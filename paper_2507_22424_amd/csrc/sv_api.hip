@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstdint>
 #include <cstring>
+#include <mutex>
 
 #include "specvla_verify.h"
 #include "specvla_verify_aux.h"
@@ -485,6 +486,30 @@ static int head_t(const sv_model_cfg& c, const T* g_final, const T* w_lm, const 
   return launch_status();
 }
 
+// Scratch of sv_action_head_argmax_noalloc: the normalised rows and the logit planes of one call,
+// in device memory that belongs to the library image (one copy per GPU, for the life of the
+// process).  Host code never uses the array's name as an address: scratch_address() asks the
+// runtime where the current device's copy lives, once per device.
+constexpr int kNoallocMaxRows = 64, kNoallocMaxScored = 256, kNoallocMaxHidden = 8192;
+constexpr size_t kNoallocZBytes = (size_t)kNoallocMaxRows * kNoallocMaxHidden * 4;
+constexpr size_t kNoallocScratchBytes = kNoallocZBytes + (size_t)16 * kMTile * kNoallocMaxScored * 4;
+static __device__ __align__(256) unsigned char scratch[kNoallocScratchBytes];
+
+static int scratch_address(unsigned char** out) {
+  static void* per_device[64] = {nullptr};
+  static std::mutex lock;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return SV_ERR_LAUNCH;
+  std::lock_guard<std::mutex> guard(lock);
+  if (!per_device[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SV_ERR_LAUNCH;
+    per_device[dev] = p;
+  }
+  *out = (unsigned char*)per_device[dev];
+  return SV_OK;
+}
+
 // Head on the streaming kernel: RMSNorm gain in the staging pass, 1 / rms after the reduction,
 // logits to the workspace, then the row argmax.
 static int head_packed(const sv_model_cfg& c, const char* packed, const float* x, int n_rows,
@@ -778,6 +803,27 @@ int sv_action_head_argmax(const sv_model_cfg* cfg, const void* g_final, const vo
   const WorkspaceLayout wl = workspace_layout(*cfg, n_rows, vocab_hi - vocab_lo);
   float* z = (float*)((char*)workspace + wl.head_z);
   float* parts = (float*)((char*)workspace + wl.head_logits);
+  if (cfg->dtype == SV_F32)
+    return head_t<float>(*cfg, (const float*)g_final, (const float*)w_lm, x, n_rows, vocab_lo,
+                         vocab_hi, out_token, out_logits, z, parts, (hipStream_t)stream);
+  return head_t<bf16_t>(*cfg, (const bf16_t*)g_final, (const bf16_t*)w_lm, x, n_rows, vocab_lo,
+                        vocab_hi, out_token, out_logits, z, parts, (hipStream_t)stream);
+}
+
+int sv_action_head_argmax_noalloc(const sv_model_cfg* cfg, const void* g_final, const void* w_lm,
+                                  const float* x, int n_rows, int vocab_lo, int vocab_hi,
+                                  int32_t* out_token, float* out_logits, void* stream) {
+  const int rc = check_cfg(cfg);
+  if (rc != SV_OK) return rc;
+  if (!g_final || !w_lm || !x || !out_token) return SV_ERR_NULL;
+  if (n_rows < 1 || vocab_lo < 0 || vocab_lo >= vocab_hi || vocab_hi > cfg->vocab) return SV_ERR_SHAPE;
+  if (n_rows > kNoallocMaxRows || vocab_hi - vocab_lo > kNoallocMaxScored || cfg->hidden > kNoallocMaxHidden)
+    return SV_ERR_WORKSPACE;                  // beyond what the built-in scratch holds
+  unsigned char* base = nullptr;
+  const int rs = scratch_address(&base);
+  if (rs != SV_OK) return rs;
+  float* z = (float*)base;
+  float* parts = (float*)(base + kNoallocZBytes);
   if (cfg->dtype == SV_F32)
     return head_t<float>(*cfg, (const float*)g_final, (const float*)w_lm, x, n_rows, vocab_lo,
                          vocab_hi, out_token, out_logits, z, parts, (hipStream_t)stream);
