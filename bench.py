@@ -2,9 +2,9 @@
 
 step = sv_verify_stack (32 layers) -> sv_action_head_argmax_packed -> sv_relaxed_accept for the full
 7B-shaped configuration (60-node tree, 280-token prefix, bf16 weights), all inputs resident
-in HBM.  Prints ONE JSON line: verified tree tokens/s, step latency, the HBM roofline of the
-dominant kernel (the weight-streaming GEMM, timed live with HIP events) and the CPU oracle
-timed on a bounded sample of the same workload.
+in HBM.  Prints ONE JSON line: verified tree tokens/s, step latency, the roofline of the
+dominant kernel (timed live with HIP events), the CPU oracle timed on the same workload, and
+the acceptance rule alone CPU against GPU.
 """
 import argparse
 import ctypes as C
@@ -18,11 +18,14 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM-side bytes per launch of the dominant kernel (average over the four GEMM launches of a
-# layer), from the two rocprofv3 --pmc runs summarised in profiles/c3_step_hbm_traffic.txt:
-# fetched (FETCH_SIZE x 2, calibrated with a 1 GiB copy) + written (WRITE_SIZE x 1):
-# gate/up 211.7 + 25.3, q/k/v 122.0 + 14.6, down 117.0 + 5.2, output 47.1 + 5.2 (MB).
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = (211.68 + 25.30 + 121.97 + 14.64 + 117.04 + 5.20 + 47.08 + 5.20) / 4 * 1e6
+MFMA_PEAK_TFLOPS = 2500.0           # dense bf16
+# HBM-side bytes per launch of the dominant kernel, from the two rocprofv3 --pmc runs (FETCH_SIZE
+# calibrated with a 1 GiB copy in the same run, then WRITE_SIZE) whose summaries are under
+# profiles/: average over the four GEMM launches of a layer.  None where no such summary exists.
+TRAFFIC_BYTES_PER_LAUNCH = {
+    ("C3", "bf16"): (211.68 + 25.30 + 121.97 + 14.64 + 117.04 + 5.20 + 47.08 + 5.20) / 4 * 1e6,
+}
+TRAFFIC_SOURCE = {("C3", "bf16"): "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/c3_step_hbm_traffic.txt"}
 
 
 def log(msg):
@@ -51,12 +54,22 @@ class HipEvents:
         return out.value
 
 
-def cpu_baseline(cfg, wl, n_sample_layers=2):
-    """The oracle as it stands on a bounded sample: n_sample_layers of the 32 layers of the
-    same workload + head + acceptance, scaled to a whole step."""
-    import numpy as np
-    import torch
+def host_cores():
+    """(logical cores the process may run on, threads the BLAS pool behind numpy uses)."""
     from threadpoolctl import threadpool_info
+    try:
+        nproc = len(os.sched_getaffinity(0))
+    except AttributeError:
+        nproc = os.cpu_count() or 1
+    blas = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return nproc, blas
+
+
+def cpu_baseline(cfg, wl):
+    """The oracle as it stands on the whole step of the same workload, episode 0: every layer,
+    head, acceptance (float64 numpy; its matrix products go through numpy's BLAS).  Weights are
+    drawn layer by layer outside the timed parts."""
+    import torch
     from oracle import verify_oracle as vo
     f64 = lambda t: t.to(torch.float64).numpy()
     P = int(wl.prefix_lengths(cfg)[0])
@@ -65,7 +78,7 @@ def cpu_baseline(cfg, wl, n_sample_layers=2):
     head = wl.head_weights(cfg)
     gf, wlm = f64(head["g_final"]), f64(head["w_lm"])
     t_layers = 0.0
-    for l in range(n_sample_layers):
+    for l in range(cfg.n_layers):
         w = {k: f64(v) for k, v in wl.layer_weights(cfg, l).items()}
         kp, vp = (f64(t) for t in wl.prefix_kv(cfg, 0, l, P))
         t0 = time.perf_counter()
@@ -76,13 +89,58 @@ def cpu_baseline(cfg, wl, n_sample_layers=2):
     draft = wl.noisy_draft_tokens(cfg, 0, parent, tok)
     vo.relaxed_accept(parent, draft, tok, cfg.action_lo, cfg.n_bins, 4)
     t_tail = time.perf_counter() - t0
-    step_s = t_layers / n_sample_layers * cfg.n_layers + t_tail
-    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    return {"value": cfg.tree_nodes / step_s, "unit": "verified tree tokens/s", "cores": threads,
+    step_s = t_layers + t_tail
+    nproc, blas = host_cores()
+    return {"value": cfg.tree_nodes / step_s, "unit": "verified tree tokens/s", "cores": blas,
             "kind": "oracle",
-            "sample": f"{n_sample_layers} of {cfg.n_layers} layers + head + accept of the same "
-                      f"workload, float64 numpy; layer time scaled x{cfg.n_layers / n_sample_layers:g}",
-            "step_s_extrapolated": step_s}
+            "sample": f"one whole step of episode 0 ({cfg.n_layers} layers + head + accept), float64 "
+                      "numpy, matrix products through numpy's BLAS",
+            "nproc": nproc, "blas_threads": blas, "step_s": step_s}
+
+
+def accept_alone(sv, wl, steps=200):
+    """sv_relaxed_accept against the oracle's relaxed_accept on 16 trees of 60 nodes (seeded
+    target tokens, drafts within +-8 bins, r = 4): microseconds per call for all 16 episodes."""
+    import numpy as np
+    import torch
+    from oracle import verify_oracle as vo
+    B, T, dmax, lo, nb, r = 16, 60, 7, 31744, 256, 4
+    rng = np.random.default_rng(16060)
+    parents = [wl.draft_tree(T, dmax, 4, dmax, rng) for _ in range(B)]
+    target = lo + rng.integers(0, nb, size=B * T)
+    draft = np.empty(B * T, dtype=np.int64)
+    for b in range(B):
+        for c in range(T):
+            p = max(int(parents[b][c]), 0)
+            draft[b * T + c] = np.clip(target[b * T + p] + rng.integers(-8, 9), lo, lo + nb - 1)
+    t0 = time.perf_counter()
+    reps = 20
+    for _ in range(reps):
+        ref = [vo.relaxed_accept(parents[b], draft[b * T:(b + 1) * T], target[b * T:(b + 1) * T], lo, nb, r)
+               for b in range(B)]
+    cpu_us = (time.perf_counter() - t0) / reps * 1e6
+    tree = sv.DeviceTree(np.concatenate(parents), B, T, dmax)
+    d_t = torch.from_numpy(draft.astype(np.int32)).cuda()
+    t_t = torch.from_numpy(target.astype(np.int32)).cuda()
+    out = dict(mask=torch.zeros(B * T, dtype=torch.uint8, device="cuda"),
+               length=torch.zeros(B, dtype=torch.int32, device="cuda"),
+               best=torch.zeros(B, dtype=torch.int32, device="cuda"),
+               path=torch.zeros(B, dmax + 1, dtype=torch.int32, device="cuda"),
+               tokens=torch.zeros(B, dmax + 1, dtype=torch.int32, device="cuda"))
+    call = lambda: sv.sv_relaxed_accept(tree.struct, d_t, t_t, lo, nb, r, B, dmax, out["mask"], out["length"],
+                                        out["best"], out["path"], out["tokens"])
+    for _ in range(10):
+        call()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        call()
+    e1.record()
+    torch.cuda.synchronize()
+    gpu_us = e0.elapsed_time(e1) / steps * 1e3
+    same = out["length"].cpu().tolist() == [x["length"] for x in ref]
+    return {"episodes": B, "tree_nodes": T, "r": r, "cpu_oracle_us": cpu_us, "gpu_us": gpu_us,
+            "lengths_equal": same, "note": "GPU figure is one launch of one workgroup per episode, i.e. launch latency"}
 
 
 def main():
@@ -91,12 +149,13 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--r", type=int, default=4)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true",
+                    help="skip the legs that run the CPU oracle (whole-step baseline, acceptance alone)")
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers (invalid as a result)")
     ap.add_argument("--config", choices=("C3", "C4", "C5"), default="C3",
                     help="C3 is the benchmark workload; C4 (16 episodes) and C5 (prefix 2048, 128 "
                          "nodes) are parity configurations that can be timed and profiled the "
-                         "same way (no CPU baseline, no stored traffic figure)")
+                         "same way (no CPU baseline)")
     ap.add_argument("--weights", choices=("bf16", "w8"), default="bf16",
                     help="w8: the same workload with 8-bit (E4M3 + row scale) matrices, a variant "
                          "of its own: half the weight bytes, not the headline configuration")
@@ -105,7 +164,7 @@ def main():
                          "FETCH_SIZE / WRITE_SIZE counters in the same profile)")
     ap.add_argument("--launch", choices=("stream", "graph"), default="stream",
                     help="issue the timed steps launch by launch from the host (default) or as "
-                         "replays of one HIP graph (measured: the same step time within 0.2 %%)")
+                         "replays of one HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures ONE GPU only (the tree-verification pass of one "
@@ -122,14 +181,13 @@ def main():
     w8 = args.weights == "w8"
     if w8:
         cfg = cfg.scaled(dtype="bf16_w8")
-    if w8 or args.config != "C3":
-        args.no_cpu_baseline = True      # the baseline leg times the bf16 benchmark workload
+    headline = args.config == "C3" and not w8 and args.layers is None
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
     B, T, L = cfg.n_episodes, cfg.tree_nodes, cfg.n_layers
+    M = B * T
     prefix_len = wl.prefix_lengths(cfg)
     parents = [wl.episode_tree(cfg, b) for b in range(B)]
-    parent = parents[0]
     vp = VerifyPass(cfg, prefix_len, np.concatenate(parents))
 
     t0 = time.time()
@@ -154,8 +212,6 @@ def main():
     vp.set_draft(np.concatenate([wl.noisy_draft_tokens(cfg, b, parents[b], tok[b * T:(b + 1) * T])
                                  for b in range(B)]))
 
-    # --launch graph: the step recorded once into a HIP graph and replayed (the same launches in
-    # the same order)
     graph = vp.capture_step(args.r) if args.launch == "graph" else None
     one_step = graph.replay if graph is not None else (lambda: vp.step(args.r))
     for _ in range(args.warmup):
@@ -177,16 +233,35 @@ def main():
     torch.cuda.synchronize()
     step_ms = sorted(e0.elapsed_time(e1) for e0, e1 in se)
     pct = lambda q: step_ms[min(len(step_ms) - 1, int(q * len(step_ms)))]
-    tokens_per_s = B * T / (dt / args.steps)
+    tokens_per_s = M / (dt / args.steps)
     accepted = vp.accepted_len.cpu().tolist()
     accepted_by_r = {}
     for r in cfg.r_values:
         vp.accept(r)
         torch.cuda.synchronize()
         accepted_by_r[str(r)] = vp.accepted_len.cpu().tolist()
-    assert vp.placement_status() == 0, "GEMM placement check failed (see SV_WS_STATUS)"
+    assert vp.placement_status() == 0, "status word raised (see SV_WS_STATUS)"
 
-    # per-kernel durations with HIP events around single launches, same stream, same inputs
+    # the layers alone, untimed by events, for the split of the step into layers and tail
+    views = [kv.struct for kv in vp.kv]
+    def layers_only():
+        sv.sv_verify_stack(vp.cfg, vp.packed, vp.x, views, vp.tree.struct, B, vp.workspace)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(3):
+        layers_only()
+    e0.record()
+    n_lay = max(1, min(args.steps, 20))
+    for _ in range(n_lay):
+        layers_only()
+    e1.record()
+    torch.cuda.synchronize()
+    layers_ms = e0.elapsed_time(e1) / n_lay
+
+    # per-kernel durations with HIP events around single launches, same stream, same inputs.
+    # An event pair costs the stream about 2 us per interval, so the raw figures add up to more
+    # than the layers take unobserved; `kernel_ms_per_step` is therefore the raw figures scaled
+    # by (layers unobserved) / (their sum) - it adds up to `layers_ms_per_step` - and the raw
+    # ones are kept beside it.
     n_ev = sv.SV_N_TIMING_EVENTS
     evs = HipEvents(n_ev * L)
     prof_steps = max(1, min(args.steps, 10))
@@ -201,15 +276,48 @@ def main():
         for l in range(L):
             for k, (a, b) in pairs.items():
                 acc_ms[k] += evs.elapsed_ms(l * n_ev + a, l * n_ev + b)
-    per_step_ms = {k: v / prof_steps for k, v in acc_ms.items()}
+    raw_ms = {k: v / prof_steps for k, v in acc_ms.items()}
+    scale = layers_ms / sum(raw_ms.values())
+    per_step_ms = {k: v * scale for k, v in raw_ms.items()}
     H, D, F = cfg.hidden, cfg.n_heads * cfg.head_dim, cfg.mlp_dim
     wb = 1 if w8 else 2                  # bytes per weight (the row scales of w8 are 0.1 % more)
     gemm_bytes = {"qkv": 3 * D * H * wb, "o": H * D * wb, "gate_up": 2 * F * H * wb, "down": H * F * wb}
-    gemm_ms = sum(per_step_ms[k] for k in gemm_bytes)
-    gemm_gbs = sum(gemm_bytes.values()) * L / (gemm_ms * 1e-3) / 1e9
+    gemm_flops = {k: 2.0 * M * v / wb for k, v in gemm_bytes.items()}          # algorithmic, per layer
+    gemm_ms_raw = sum(raw_ms[k] for k in gemm_bytes)
+    gemm_gbs = sum(gemm_bytes.values()) * L / (gemm_ms_raw * 1e-3) / 1e9
+    # matrix-core work as issued: every product is done on the hi and on the lo half of the
+    # float32 activations (2 x the algorithmic flops), on row tiles padded to 64 (128 for the
+    # many-row kernel)
+    m_issue = -(-M // 128) * 128 if M > 128 else -(-M // 64) * 64
+    issued_flops = 2.0 * sum(gemm_flops.values()) * L * m_issue / M
+    mfma_tflops = issued_flops / (gemm_ms_raw * 1e-3) / 1e12
     kv_bytes = sum(2 * cfg.n_heads * (int(p) + T) * cfg.head_dim * 2 for p in prefix_len)   # all episodes, one layer
     weights_total = sum(gemm_bytes.values()) * L
-    step_bytes = weights_total + kv_bytes * L + cfg.n_bins * H * 2 + 2 * cfg.n_heads * B * T * cfg.head_dim * 2 * L
+    step_bytes = weights_total + kv_bytes * L + cfg.n_bins * H * 2 + 2 * cfg.n_heads * M * cfg.head_dim * 2 * L
+    step_flops = sum(gemm_flops.values()) * L
+
+    mfma_bound = M > 128                 # many rows: the products are bound by the matrix cores
+    key = (args.config, args.weights)
+    if mfma_bound:
+        roofline = {"bound": "mfma", "kernel": "gemm_rows_kernel (4 products per layer, with their split_rows / "
+                                               "rows_rstd / rows_reduce_resid launches)",
+                    "achieved": mfma_tflops, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": mfma_tflops / MFMA_PEAK_TFLOPS,
+                    "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(key),
+                    "flops_counted": "matrix-core flops as issued: hi and lo halves of the activations, rows padded to 128",
+                    "algorithmic_frac": step_flops / (gemm_ms_raw * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
+                    "flops_per_launch_avg": issued_flops / (4 * L),
+                    "avg_launch_us": gemm_ms_raw * 1e3 / (4 * L)}
+    else:
+        roofline = {"bound": "hbm", "kernel": "gemm_stream_bf16 (4 launches per layer: q/k/v, o, gate/up, down)",
+                    "achieved": gemm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": gemm_gbs / HBM_PEAK_GBS,
+                    "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(key),
+                    "traffic_source": TRAFFIC_SOURCE.get(key),
+                    "bytes_per_launch_avg": weights_total / (4 * L),
+                    "avg_launch_us": gemm_ms_raw * 1e3 / (4 * L),
+                    "timing": "HIP events around single launches (raw; about 2 us per interval above the "
+                              "profiler's kernel durations)"}
 
     out = {
         "metric": "verified tree tokens/sec + step latency (7B-shaped, tree 60); % HBM peak",
@@ -227,20 +335,19 @@ def main():
                    "launch": "HIP graph replay" if graph is not None else "host launches"},
         "step_hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "step_algorithmic_bytes": step_bytes,
+        "step_mfma_frac": 2.0 * step_flops * m_issue / M / (ms_per_step * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
+        "mfma_frac": mfma_tflops / MFMA_PEAK_TFLOPS,
         "accepted_len": accepted, "accepted_len_by_r": accepted_by_r,
+        "layers_ms_per_step": layers_ms,
+        "tail_ms_per_step": ms_per_step - layers_ms,
         "kernel_ms_per_step": per_step_ms,
-        "roofline": {"bound": "hbm", "kernel": "gemm_stream_bf16 (4 launches per layer: q/k/v, o, gate/up, down)",
-                     "achieved": gemm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": gemm_gbs / HBM_PEAK_GBS,
-                     "traffic": None if (w8 or args.config != "C3") else GEMM_TRAFFIC_BYTES_PER_LAUNCH,
-                     "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/c3_step_hbm_traffic.txt",
-                     "bytes_per_launch_avg": weights_total / (4 * L),
-                     "avg_launch_us": gemm_ms * 1e3 / (4 * L)},
+        "kernel_ms_per_step_event_timed": raw_ms,
+        "roofline": roofline,
         # the K/V stream of the tree attention (prefix + tree rows of every head, once per layer)
         "kv_stream": {"bound": "hbm", "kernel": "tree_attention_mfma", "bytes_per_launch": kv_bytes,
-                      "avg_launch_us": per_step_ms["attn"] * 1e3 / L,
-                      "achieved": kv_bytes * L / (per_step_ms["attn"] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
-                      "unit": "GB/s", "frac": kv_bytes * L / (per_step_ms["attn"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
+                      "avg_launch_us": raw_ms["attn"] * 1e3 / L,
+                      "achieved": kv_bytes * L / (raw_ms["attn"] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                      "unit": "GB/s", "frac": kv_bytes * L / (raw_ms["attn"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }
     # what a plain streaming read reaches on this GPU (sv_stream_read over 2 GiB, best of 5)
     probe = torch.empty(1 << 31, dtype=torch.uint8, device="cuda").fill_(1)
@@ -257,14 +364,36 @@ def main():
     del probe
     out["step_ms_p10_p50_p90"] = [pct(0.1), pct(0.5), pct(0.9)]
     out["roofline"]["stream_read_measured"] = ceiling
-    out["roofline"]["frac_of_stream_read"] = gemm_gbs / ceiling
+    if not mfma_bound:
+        out["roofline"]["frac_of_stream_read"] = gemm_gbs / ceiling
+    if headline:
+        # how often the greedy choice over the WHOLE vocabulary leaves the 256 action tokens
+        # (the acceptance rule then rejects): the full head on the packed streaming kernel, once
+        full = wl.head_weights(cfg, full_vocab=True)
+        nb = sv.sv_packed_head_bytes(vp.cfg, 0, cfg.vocab)
+        ph = torch.empty(nb, dtype=torch.uint8, device="cuda")
+        gf, wf = full["g_final"].cuda(), full["w_lm"].cuda()
+        sv.sv_pack_head(vp.cfg, gf, wf, 0, cfg.vocab, ph)
+        ws = torch.empty(sv.sv_workspace_bytes(vp.cfg, B, T, cfg.vocab), dtype=torch.uint8, device="cuda")
+        sv.sv_workspace_init(vp.cfg, B, T, cfg.vocab, ws)
+        tok_full = torch.zeros(M, dtype=torch.int32, device="cuda")
+        sv.sv_action_head_argmax_packed(vp.cfg, ph, vp.x, M, 0, cfg.vocab, tok_full, None, ws)
+        torch.cuda.synchronize()
+        outside = int((tok_full.cpu().numpy() < cfg.action_lo).sum())
+        out["full_vocabulary_argmax"] = {"nodes": M, "outside_action_slice": outside,
+                                         "note": "random-init head: with 32000 rows of equal scale the "
+                                                 "maximum lies among the 256 action rows with probability 0.8 %"}
+        del ph, ws, wf
     if args.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
         dst.copy_(src)
         torch.cuda.synchronize()
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, wl)
+        out["accept_alone"] = accept_alone(sv, wl)
+        if args.config == "C3" and not w8:
+            out["cpu_baseline"] = cpu_baseline(cfg, wl)
+            out["cpu_baseline"]["gpu_speedup"] = tokens_per_s / out["cpu_baseline"]["value"]
     print(json.dumps(out), flush=True)
 
 

@@ -11,9 +11,11 @@
  *
  * Conventions
  *   - Plain C ABI.  Every pointer is tagged [host] or [device] below.  The caller owns every
- *     buffer; the library allocates no device memory, keeps no state between calls and
- *     frees nothing.  `stream` is a hipStream_t passed as void*; all device work of a call
- *     is enqueued on it and the call returns without waiting for it.
+ *     buffer; the library allocates no device memory and frees nothing.  Between calls it keeps
+ *     nothing but read-only facts about the device (how many XCDs it has) and, for the one call
+ *     that takes no workspace (sv_action_head_argmax_noalloc), the address of its built-in
+ *     scratch.  `stream` is a hipStream_t passed as void*; all device work of a call is enqueued
+ *     on it and the call returns without waiting for it.
  *   - Every call returns an int status: SV_OK (0) or a negative SV_ERR_* code.  Arguments are
  *     checked on the host before anything is launched; on error nothing was launched.
  *     Faults inside kernels surface at the caller's next synchronisation, as with any launch.
@@ -183,9 +185,19 @@ int sv_tree_build_device(const int32_t *cand_parent, const float *cand_logp,
  *   kv, tree:  [host] structs of [device] pointers, see above; tree->n_nodes = T
  *   workspace: [device], 256-byte aligned, ws_bytes >= sv_workspace_bytes(cfg, B, T, *),
  *              prepared once with sv_workspace_init; calls sharing a workspace must not overlap
- * bf16 models: the projections are split along K and their partial sums travel in 16 bits with
- * one scale per 64-row x 32-column tile (error <= 2^-14 of the tile's largest partial sum); an
- * infinity or NaN anywhere in such a tile makes the whole tile (all its rows) NaN.
+ * bf16 models, up to 128 rows: the projections are split along K and their partial sums travel
+ * in 16 bits with one scale per 64-row x 32-column tile (error <= 2^-14 of the tile's largest
+ * partial sum, each row first brought to a common size).  A partial sum that is not finite
+ * travels as a code of its own and comes back as NaN: a NaN or infinity reaches exactly the
+ * outputs it reaches by the layer's own arithmetic, one exception aside - inside the tree
+ * attention a NaN in the value row of a tree node also reaches the other nodes of that episode
+ * and head, whether or not they attend to it (a probability of zero times NaN); other episodes
+ * are never touched.  The workgroups of such a projection wait for each other (bounded) and
+ * check where they ran; a wait that runs out or an unexpected placement leaves the outputs of
+ * the call undefined and raises the status word (sv_workspace_region, SV_WS_STATUS), which
+ * callers that cannot rule out a GPU shared with other work should read before they trust or
+ * commit the results.
+ * (long long) B * n_heads * capacity must stay below 2^31.
  * SV_ERR_SHAPE if B < 1, T outside 1..SV_MAX_TREE_NODES, capacity < prefix_len_max + T, or
  * cfg sizes are unsupported for the dtype (see sv_pack_layer). */
 int sv_verify_layer(const sv_model_cfg *cfg, const void *packed, float *x,
@@ -278,7 +290,10 @@ int sv_commit_path(const sv_model_cfg *cfg, const sv_kv_view *kv, int T, const i
                    const int32_t *accepted_len, int B, int d_cap, void *stream);
 
 /* prefix_len[b] += accepted_len[b] + 1 on the device ([device] int32[B] each).  The caller
- * raises its host-side bound kv.prefix_len_max by d_cap + 1 (or by what it reads back). */
+ * raises its host-side bound kv.prefix_len_max by d_cap + 1 (or by what it reads back) and must
+ * stop, or move to a larger cache, before prefix_len_max + T would exceed the capacity: the next
+ * sv_verify_layer refuses such a view (SV_ERR_SHAPE), and kernels clamp prefix_len[b] to
+ * prefix_len_max. */
 int sv_advance_prefix(int32_t *prefix_len, const int32_t *accepted_len, int B, int d_cap,
                       void *stream);
 

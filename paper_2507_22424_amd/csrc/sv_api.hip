@@ -721,6 +721,7 @@ static int verify_layer_checked(const sv_model_cfg* cfg, const void* packed, flo
     return SV_ERR_SHAPE;
   if (kv->prefix_len_max < 0 || (long long)kv->capacity < (long long)kv->prefix_len_max + T)
     return SV_ERR_SHAPE;
+  if ((long long)B * cfg->n_heads * kv->capacity >= (1ll << 31)) return SV_ERR_SHAPE;   // cache rows are indexed in 32 bits
   if (((uintptr_t)workspace % kAlign) || ((uintptr_t)packed % kAlign) ||
       ws_bytes < workspace_layout(*cfg, B * T, 0).total)
     return SV_ERR_WORKSPACE;
@@ -768,6 +769,7 @@ static int verify_stack_args(const sv_model_cfg* cfg, int n_layers, const void* 
     if ((uintptr_t)packed[l] % kAlign) return SV_ERR_WORKSPACE;
     if (kv[l].prefix_len_max < 0 || (long long)kv[l].capacity < (long long)kv[l].prefix_len_max + T)
       return SV_ERR_SHAPE;
+    if ((long long)B * cfg->n_heads * kv[l].capacity >= (1ll << 31)) return SV_ERR_SHAPE;
   }
   if (((uintptr_t)workspace % kAlign) || ws_bytes < workspace_layout(*cfg, B * T, 0).total)
     return SV_ERR_WORKSPACE;

@@ -160,15 +160,24 @@ class VerifyPass:
         self.tree = sv.DeviceTree(parent, self.B, self.T, self.d_cap, self.device)
 
     def commit(self) -> None:
-        """Make the accepted paths part of the prefix in every layer (outer loop of Alg. 1)."""
+        """Make the accepted paths part of the prefix in every layer (outer loop of Alg. 1).
+        Refuses when the last pass raised the status word (its results are then undefined) or
+        when the cache has no room left for another tree behind the longest possible prefix."""
+        st = self.placement_status()
+        if st != 0:
+            raise RuntimeError(f"verification pass raised status {st}: results undefined, nothing committed")
+        # (the status read above has synchronised: the accepted lengths are on hand)
+        advance = int(self.accepted_len.max().item()) + 1
+        if self.kv[0].struct.prefix_len_max + advance > self.capacity - self.T:
+            raise RuntimeError("KV cache full: prefix + accepted path + next tree exceed the capacity "
+                               "(construct VerifyPass with a larger extra_capacity)")
         for l in range(self.wc.n_layers):
             sv.sv_commit_path(self.cfg, self.kv[l].struct, self.T, self.path, self.accepted_len,
                               self.B, self.d_cap)
         # all layers share the prefix lengths of layer 0's holder
         sv.sv_advance_prefix(self.kv[0].prefix_len, self.accepted_len, self.B, self.d_cap)
         for l in range(self.wc.n_layers):
-            self.kv[l].struct.prefix_len_max = min(self.kv[l].struct.prefix_len_max + self.d_cap + 1,
-                                                   self.capacity - self.T)
+            self.kv[l].struct.prefix_len_max = self.kv[l].struct.prefix_len_max + advance
 
     def placement_status(self) -> int:
         """0 unless a GEMM saw the slices of one tile on different XCDs (see SV_WS_STATUS)."""
