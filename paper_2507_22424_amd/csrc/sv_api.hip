@@ -395,10 +395,15 @@ static int verify_layer_rows(const sv_model_cfg& c, const char* packed, float* x
       split_rows_kernel<false><<<dim3(mb, K / 256), 256, 0, st>>>(src, nullptr, nullptr, M, K, xs);
     }
   };
-  auto shape = [&](size_t w_off, int N, int K, int ksplit) {
-    a.Wp = (const uint4*)(packed + w_off); a.N = N; a.K = K; a.n_tiles = N / kRowsTN; a.ksplit = ksplit;
+  auto shape = [&](size_t w_off, int N, int K, int ksplit, int tn) {
+    a.Wp = (const uint4*)(packed + w_off); a.N = N; a.K = K; a.n_tiles = N / tn; a.ksplit = ksplit;
     return dim3(n_xcd, ceil_div(a.n_tiles, n_xcd) * a.m_tiles, ksplit);
   };
+  // 384-column blocks where they give a whole number of rounds of the chip and 256-column blocks
+  // do not (q/k/v of the 7B shape with 8 row blocks: 256 workgroups instead of 384)
+  const int cus = n_xcd * 32;
+  const bool wide_qkv = (3 * D) % 384 == 0 && ((3 * D / 384) * a.m_tiles) % cus == 0 &&
+                        ((3 * D / 256) * a.m_tiles) % cus != 0;
   auto reduce_resid = [&](int ksplit) {
     const size_t n4 = (size_t)M * H / 4;
     rows_reduce_resid_kernel<<<(unsigned)((n4 + 255) / 256), 256, 0, st>>>(
@@ -406,7 +411,8 @@ static int verify_layer_rows(const sv_model_cfg& c, const char* packed, float* x
   };
   mark(0);
   split(x, (const float*)(packed + pl.g1), H);
-  gemm_rows_kernel<EPI_QKV, false><<<shape(pl.wqkv, 3 * D, H, 1), 256, 0, st>>>(a);
+  if (wide_qkv) gemm_rows_kernel<EPI_QKV, false, 6><<<shape(pl.wqkv, 3 * D, H, 1, 384), 256, 0, st>>>(a);
+  else gemm_rows_kernel<EPI_QKV, false, 4><<<shape(pl.wqkv, 3 * D, H, 1, 256), 256, 0, st>>>(a);
   mark(1);
   mark(2);
   {
@@ -419,16 +425,16 @@ static int verify_layer_rows(const sv_model_cfg& c, const char* packed, float* x
   }
   mark(3);
   split(attn, nullptr, D);
-  gemm_rows_kernel<EPI_RESID, true><<<shape(pl.wo, H, D, kRowsKsplit), 256, 0, st>>>(a);
+  gemm_rows_kernel<EPI_RESID, true, 4><<<shape(pl.wo, H, D, kRowsKsplit, 256), 256, 0, st>>>(a);
   reduce_resid(kRowsKsplit);
   mark(4);
   mark(5);
   split(x, (const float*)(packed + pl.g2), H);
-  gemm_rows_kernel<EPI_SWIGLU, false><<<shape(pl.wgu, 2 * F, H, 1), 256, 0, st>>>(a);
+  gemm_rows_kernel<EPI_SWIGLU, false, 4><<<shape(pl.wgu, 2 * F, H, 1, 256), 256, 0, st>>>(a);
   mark(6);
   mark(7);
   split(act, nullptr, F);
-  gemm_rows_kernel<EPI_RESID, true><<<shape(pl.wd, H, F, kRowsKsplit), 256, 0, st>>>(a);
+  gemm_rows_kernel<EPI_RESID, true, 4><<<shape(pl.wd, H, F, kRowsKsplit, 256), 256, 0, st>>>(a);
   reduce_resid(kRowsKsplit);
   mark(8);
   return launch_status();

@@ -5,7 +5,7 @@
 // gemm_stream_bf16 streams them once past activations that wait in LDS.  With hundreds of rows
 // the same products are bound by the matrix cores, and what has to be kept small is the traffic
 // per matrix instruction: every workgroup owns a 128-row x 256-column block of the output, keeps
-// it in accumulator registers and walks the whole K range; both operands arrive already cut into
+// (or 384-column) block of the output, keeps it in accumulator registers and walks the whole K range; both operands arrive already cut into
 // matrix-core fragments (1 KiB = 32 rows x 16 k-values, lane-major), so a fragment travels from
 // memory into LDS with one direct-to-LDS load instruction per wave and from LDS into operand
 // registers with one 16-byte read per lane, without any shuffling:
@@ -30,9 +30,7 @@
 namespace sv {
 
 constexpr int kRowsTM = 128;        // rows of a workgroup's output block
-constexpr int kRowsTN = 256;        // columns
-constexpr int kRowsRing = 8;        // k-steps resident in LDS
-constexpr int kRowsFrags = 16;      // fragments per k-step: 4 row blocks x (hi, lo), 8 weight tiles
+constexpr int kRowsTN = 256;        // columns (384 for a product whose column count that divides into one round of the chip)
 constexpr int kRowsKsplit = 2;      // K split of the products with N = hidden (too few column blocks to fill the chip)
 constexpr int kRowsMinTiles = 2;    // more 64-row tiles than this: the products run on gemm_rows_kernel
 
@@ -127,10 +125,16 @@ __global__ __launch_bounds__(256) void rows_reduce_resid_kernel(const float* __r
 }
 
 // grid = (n_xcd, ceil(n_tiles / n_xcd) * m_tiles, ksplit), block = 256 (waves 2 x 2: rows wm * 64,
-// columns wn * 128 of the block).
-template <int EPI, bool SPLIT>
+// columns wn * 32 * NTW of the block).  NTW = weight tiles (32 columns) per wave: 4 gives blocks
+// of 256 columns, 6 blocks of 384 (for the q/k/v product of the 7B shape: 32 column blocks x 8 row
+// blocks = 256 workgroups, one full round of the chip instead of one and a half).
+template <int EPI, bool SPLIT, int NTW>
 __global__ __launch_bounds__(256, 1) void gemm_rows_kernel(const RowsArgs a) {
-  __shared__ uint4 ring[kRowsRing][kRowsFrags][64];          // 128 KiB
+  constexpr int kFr = 8 + 2 * NTW;                 // fragments per k-step: 4 row blocks x (hi, lo), 2 * NTW weight tiles
+  constexpr int kLw = kFr / 4;                     // direct-to-LDS loads per wave and k-step
+  constexpr int kR = NTW == 4 ? 8 : 6;             // k-steps resident in LDS (128 / 120 KiB)
+  static_assert(kFr % 4 == 0 && (NTW == 4 || NTW == 6), "fragment loads are dealt evenly to the four waves");
+  __shared__ uint4 ring[kR][kFr][64];
   __shared__ int s_pos[kRowsTM], s_crow[kRowsTM];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -151,88 +155,93 @@ __global__ __launch_bounds__(256, 1) void gemm_rows_kernel(const RowsArgs a) {
     s_crow[tid] = b * a.nh * a.cap + P + t;
   }
 
-  // this wave's four fragment loads per k-step: waves 0, 1 bring the activation fragments
-  // (row block f / 2, hi or lo), waves 2, 3 the weight fragments (tile f - 8)
+  // this wave's fragment loads per k-step: fragment f = kLw * wave + i; f < 8 is an activation
+  // fragment (row block f / 2, hi or lo), the others are the weight tiles f - 8
   typedef const __attribute__((address_space(1))) uint4* gptr_t;
-  gptr_t src[4];
-  size_t step;                                               // uint4 from one k-step to the next
-  if (wave < 2) {
+  gptr_t src[kLw];
+  unsigned step[kLw];                                        // uint4 from one k-step to the next
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int f = 4 * wave + i;
+  for (int i = 0; i < kLw; ++i) {
+    const int f = kLw * wave + i;
+    if (f < 8) {
       src[i] = (gptr_t)a.Xs + ((((size_t)(mt * 4 + (f >> 1)) * nks_all + ks0) * 2 + (f & 1)) * 64 + lane);
+      step[i] = 128;
+    } else {
+      src[i] = (gptr_t)a.Wp + (((size_t)(nt * 2 * NTW + (f - 8)) * nks_all + ks0) * 64 + lane);
+      step[i] = 64;
     }
-    step = 128;
-  } else {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int f = 4 * (wave - 2) + i;
-      src[i] = (gptr_t)a.Wp + (((size_t)(nt * 8 + f) * nks_all + ks0) * 64 + lane);
-    }
-    step = 64;
   }
-  // k-step j of this workgroup -> ring slot j % kRowsRing.  Past the last k-step the loads
-  // repeat it (into a slot nobody reads any more): the number of loads in flight stays fixed
-  // and the waits below are exact.
+  // k-step j of this workgroup -> ring slot j % kR.  Past the last k-step the loads repeat it
+  // (into a slot nobody reads any more): the number of loads in flight stays fixed and the
+  // waits below are exact.
   auto issue = [&](int j) {
     const int jc = j < nks ? j : nks - 1;
-    const int slot = j & (kRowsRing - 1);
+    const int slot = j % kR;
     // Direct-to-LDS loads (lane l's 16 bytes land at the LDS address in M0 + 16 l), written as
     // inline assembly: the compiler, when it sees such a load, waits for ALL outstanding loads
     // before the next LDS read that might touch the same array, which would drain the ring at
     // every k-step; the waits that are really needed are the explicit ones below.
-    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) void*)&ring[slot][4 * wave][0];
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) void*)&ring[slot][kLw * wave][0];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      gptr_t g = src[i] + (size_t)jc * step;
+    for (int i = 0; i < kLw; ++i) {
+      gptr_t g = src[i] + (size_t)jc * step[i];
       asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds0 + 1024u * i), "v"(g) : "memory");
     }
   };
 
-  f32x16_t acc[2][4];
+  f32x16_t acc[2][NTW];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = f32x16_t{};
+    for (int j = 0; j < NTW; ++j) acc[i][j] = f32x16_t{};
 
   struct Ops {
-    bf16x8_t ah[2], al[2], b[4];
+    bf16x8_t ah[2], al[2], b[NTW];
   };
   auto read_ops = [&](int j, Ops& o) {
-    const int slot = j & (kRowsRing - 1);
+    const int slot = j % kR;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       o.ah[i] = __builtin_bit_cast(bf16x8_t, ring[slot][2 * (2 * wm + i)][lane]);
       o.al[i] = __builtin_bit_cast(bf16x8_t, ring[slot][2 * (2 * wm + i) + 1][lane]);
     }
 #pragma unroll
-    for (int jn = 0; jn < 4; ++jn) o.b[jn] = __builtin_bit_cast(bf16x8_t, ring[slot][8 + 4 * wn + jn][lane]);
+    for (int jn = 0; jn < NTW; ++jn) o.b[jn] = __builtin_bit_cast(bf16x8_t, ring[slot][8 + NTW * wn + jn][lane]);
   };
-  auto multiply = [&](const Ops& o) {
+  // the two products (hi and lo half of the activations) of row block i with weight tiles [j0, j1)
+  auto multiply = [&](const Ops& o, int i, int j0, int j1) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int jn = 0; jn < 4; ++jn) {
-        acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.ah[i], o.b[jn], acc[i][jn], 0, 0, 0);
-        acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.al[i], o.b[jn], acc[i][jn], 0, 0, 0);
-      }
+    for (int jn = j0; jn < j1; ++jn) {
+      acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.ah[i], o.b[jn], acc[i][jn], 0, 0, 0);
+      acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.al[i], o.b[jn], acc[i][jn], 0, 0, 0);
+    }
   };
 
-  static_assert(kRowsRing == 8, "the wait counts below are written for a ring of eight");
 #pragma unroll
-  for (int j = 0; j < kRowsRing - 1; ++j) issue(j);
-  // k-step 0 complete: own loads (6 younger k-steps x 4 may still be in flight), then everybody's
-  asm volatile("s_waitcnt vmcnt(24)\n\ts_barrier" ::: "memory");
+  for (int j = 0; j < kR - 1; ++j) issue(j);
+  // k-step 0 complete: own loads (kR - 2 younger k-steps may still be in flight), then everybody's
+  if (NTW == 4) asm volatile("s_waitcnt vmcnt(24)\n\ts_barrier" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(20)\n\ts_barrier" ::: "memory");
   Ops o0, o1;
   read_ops(0, o0);
-  // One iteration = k-step ks: wait for k-step ks + 1 (own loads, then the barrier, which also
-  // tells that every wave is done with the slot of k-step ks - 1), refill that slot, read the
-  // operands of ks + 1, multiply ks.
+  // One iteration = k-step ks, in an order that is pinned (the scheduler may not move anything
+  // across the fences): a first few products; then wait for k-step ks + 1 (own loads: kR - 3
+  // younger k-steps may be in flight; then the barrier, which also tells that every wave has read
+  // k-step ks - 1, whose slot is refilled next), refill, start the LDS reads of the operands of
+  // k-step ks + 1; then the other products, which run while those reads return.  Left to itself
+  // the scheduler moves each read down to just before its first use and the matrix cores then
+  // wait for LDS at every k-step.
   auto iteration = [&](int ks, const Ops& cur, Ops& nxt) {
-    asm volatile("s_waitcnt vmcnt(20)\n\ts_barrier" ::: "memory");
-    issue(ks + kRowsRing - 1);
+    multiply(cur, 0, 0, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    if (NTW == 4) asm volatile("s_waitcnt vmcnt(20)\n\ts_barrier" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(15)\n\ts_barrier" ::: "memory");
+    issue(ks + kR - 1);
     read_ops(ks + 1, nxt);
-    multiply(cur);
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(cur, 0, 2, NTW);
+    multiply(cur, 1, 0, NTW);
+    __builtin_amdgcn_sched_barrier(0);
   };
   for (int ks = 0; ks < nks; ks += 2) {          // nks is even (K is a multiple of 256)
     iteration(ks, o0, o1);
@@ -241,64 +250,66 @@ __global__ __launch_bounds__(256, 1) void gemm_rows_kernel(const RowsArgs a) {
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing of the ring is in flight when the wave ends
 
   // ---- output: register r of lane l of block (i, jn) is row 8*(r/4) + 4*(l/32) + r%4, column l%32 ----
-  // The 128 accumulator registers of a lane go through LDS (the ring is free now: 32 KiB per
-  // wave) and come back four at a time inside a loop, so that the epilogue is a short piece of
-  // code run 32 times instead of 40 KiB of straight-line code fetched for a single pass.
-  asm volatile("s_barrier" ::: "memory");            // every wave has read its last operands
-  f32x4_t* stage = reinterpret_cast<f32x4_t*>(&ring[0][0][0]) + (size_t)wave * (32 * 64) + lane;
+  // The accumulator registers of a lane go through LDS (the ring is free now), one row block of
+  // the wave at a time (at most 24 KiB per wave), and come back four at a time inside a loop, so
+  // that the epilogue is a short piece of code run many times instead of 40 KiB of straight-line
+  // code fetched for a single pass.
+  const int ln = lane & 31, rbase = 4 * (lane >> 5);
+  f32x4_t* stage = reinterpret_cast<f32x4_t*>(&ring[0][0][0]) + (size_t)wave * (NTW * 4 * 64) + lane;
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < 2; ++i) {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // the ring (i = 0) / the first half (i = 1) has been read by all
 #pragma unroll
-    for (int jn = 0; jn < 4; ++jn)
+    for (int jn = 0; jn < NTW; ++jn)
 #pragma unroll
       for (int q = 0; q < 4; ++q)
-        stage[((i * 4 + jn) * 4 + q) * 64] = f32x4_t{acc[i][jn][4 * q], acc[i][jn][4 * q + 1], acc[i][jn][4 * q + 2], acc[i][jn][4 * q + 3]};
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // (own data only: no barrier needed)
-  const int ln = lane & 31, rbase = 4 * (lane >> 5);
+        stage[(jn * 4 + q) * 64] = f32x4_t{acc[i][jn][4 * q], acc[i][jn][4 * q + 1], acc[i][jn][4 * q + 2], acc[i][jn][4 * q + 3]};
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // (own data only)
 #pragma unroll 1
-  for (int item = 0; item < 32; ++item) {
-    const int i = item >> 4, jn = (item >> 2) & 3, q = item & 3;
-    const int tile = nt * 8 + wn * 4 + jn;               // 32-row weight tile = 32 output columns
-    const int ml0 = wm * 64 + i * 32 + 8 * q + rbase;    // row inside the block of the first value
-    const f32x4_t vv = stage[item * 64];
-    float v[4] = {vv[0], vv[1], vv[2], vv[3]};
-    if (SPLIT) {
-      float* dst = a.part + ((size_t)blockIdx.z * a.m_tiles * kRowsTM + m0 + ml0) * a.N + tile * 32 + ln;
+    for (int item = 0; item < NTW * 4; ++item) {
+      const int jn = item >> 2, q = item & 3;
+      const int tile = nt * 2 * NTW + wn * NTW + jn;       // 32-row weight tile = 32 output columns
+      const int ml0 = wm * 64 + i * 32 + 8 * q + rbase;    // row inside the block of the first value
+      const f32x4_t vv = stage[item * 64];
+      float v[4] = {vv[0], vv[1], vv[2], vv[3]};
+      if (SPLIT) {
+        float* dst = a.part + ((size_t)blockIdx.z * a.m_tiles * kRowsTM + m0 + ml0) * a.N + tile * 32 + ln;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) dst[(size_t)j * a.N] = v[j];
-    } else if (EPI == EPI_SWIGLU) {                      // lanes 0..15 gate, 16..31 up of the same column
-      const int F = a.N / 2;
+        for (int j = 0; j < 4; ++j) dst[(size_t)j * a.N] = v[j];
+      } else if (EPI == EPI_SWIGLU) {                      // lanes 0..15 gate, 16..31 up of the same column
+        const int F = a.N / 2;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const float up = lane_xor16(v[j], lane);
-        if (ln < 16 && m0 + ml0 + j < a.M)
-          a.act[(size_t)(m0 + ml0 + j) * F + tile * 16 + ln] = silu_fast(v[j]) * up;
-      }
-    } else if (EPI == EPI_QKV) {
-      const int tiles_per_mat = a.nh * 4;
-      const int which = tile / tiles_per_mat;
-      const int head = (tile % tiles_per_mat) / 4, uq = tile % 4;
-      const int jr = 16 * uq + (ln & 15);
-      const int dcol = jr + 64 * (ln >> 4);
-      const float turn_freq = exp2f(-(float)jr * (1.0f / 64.0f) * log2f(a.theta)) * 0.15915494309189535f;
-      const float sgn = (ln & 16) ? 1.0f : -1.0f;
-      const int D = a.nh * 128;
-      bf16_t* cache = which == 1 ? a.kc : a.vc;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int ml = ml0 + j;
-        float val = v[j];
-        const float partner = lane_xor16(val, lane);
-        if (which != 2) {
-          float turns = (float)s_pos[ml] * turn_freq;
-          turns -= floorf(turns);
-          val = val * __builtin_amdgcn_cosf(turns) + sgn * partner * __builtin_amdgcn_sinf(turns);
+        for (int j = 0; j < 4; ++j) {
+          const float up = lane_xor16(v[j], lane);
+          if (ln < 16 && m0 + ml0 + j < a.M)
+            a.act[(size_t)(m0 + ml0 + j) * F + tile * 16 + ln] = silu_fast(v[j]) * up;
         }
-        if (m0 + ml < a.M) {
-          if (which == 0)
-            a.q_out[(size_t)(m0 + ml) * D + head * 128 + dcol] = val;
-          else
-            cache[((size_t)s_crow[ml] + (size_t)head * a.cap) * 128 + dcol] = f32_to_bf16(val);
+      } else if (EPI == EPI_QKV) {
+        const int tiles_per_mat = a.nh * 4;
+        const int which = tile / tiles_per_mat;
+        const int head = (tile % tiles_per_mat) / 4, uq = tile % 4;
+        const int jr = 16 * uq + (ln & 15);
+        const int dcol = jr + 64 * (ln >> 4);
+        const float turn_freq = exp2f(-(float)jr * (1.0f / 64.0f) * log2f(a.theta)) * 0.15915494309189535f;
+        const float sgn = (ln & 16) ? 1.0f : -1.0f;
+        const int D = a.nh * 128;
+        bf16_t* cache = which == 1 ? a.kc : a.vc;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int ml = ml0 + j;
+          float val = v[j];
+          const float partner = lane_xor16(val, lane);
+          if (which != 2) {
+            float turns = (float)s_pos[ml] * turn_freq;
+            turns -= floorf(turns);
+            val = val * __builtin_amdgcn_cosf(turns) + sgn * partner * __builtin_amdgcn_sinf(turns);
+          }
+          if (m0 + ml < a.M) {
+            if (which == 0)
+              a.q_out[(size_t)(m0 + ml) * D + head * 128 + dcol] = val;
+            else
+              cache[((size_t)s_crow[ml] + (size_t)head * a.cap) * 128 + dcol] = f32_to_bf16(val);
+          }
         }
       }
     }
