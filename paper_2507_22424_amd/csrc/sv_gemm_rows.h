@@ -129,10 +129,10 @@ __global__ __launch_bounds__(256) void rows_reduce_resid_kernel(const float* __r
 // of 256 columns, 6 blocks of 384 (for the q/k/v product of the 7B shape: 32 column blocks x 8 row
 // blocks = 256 workgroups, one full round of the chip instead of one and a half).
 template <int EPI, bool SPLIT, int NTW>
-__global__ __launch_bounds__(256, 1) void gemm_rows_kernel(const RowsArgs a) {
+__global__ __launch_bounds__(256, NTW == 4 ? 2 : 1) void gemm_rows_kernel(const RowsArgs a) {
   constexpr int kFr = 8 + 2 * NTW;                 // fragments per k-step: 4 row blocks x (hi, lo), 2 * NTW weight tiles
   constexpr int kLw = kFr / 4;                     // direct-to-LDS loads per wave and k-step
-  constexpr int kR = NTW == 4 ? 8 : 6;             // k-steps resident in LDS (128 / 120 KiB)
+  constexpr int kR = NTW == 4 ? 4 : 6;             // k-steps resident in LDS (64 KiB, two workgroups per CU / 120 KiB)
   static_assert(kFr % 4 == 0 && (NTW == 4 || NTW == 6), "fragment loads are dealt evenly to the four waves");
   __shared__ uint4 ring[kR][kFr][64];
   __shared__ int s_pos[kRowsTM], s_crow[kRowsTM];
@@ -220,8 +220,7 @@ __global__ __launch_bounds__(256, 1) void gemm_rows_kernel(const RowsArgs a) {
 #pragma unroll
   for (int j = 0; j < kR - 1; ++j) issue(j);
   // k-step 0 complete: own loads (kR - 2 younger k-steps may still be in flight), then everybody's
-  if (NTW == 4) asm volatile("s_waitcnt vmcnt(24)\n\ts_barrier" ::: "memory");
-  else asm volatile("s_waitcnt vmcnt(20)\n\ts_barrier" ::: "memory");
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((kR - 2) * kLw) : "memory");
   Ops o0, o1;
   read_ops(0, o0);
   // One iteration = k-step ks, in an order that is pinned (the scheduler may not move anything
@@ -234,8 +233,7 @@ __global__ __launch_bounds__(256, 1) void gemm_rows_kernel(const RowsArgs a) {
   auto iteration = [&](int ks, const Ops& cur, Ops& nxt) {
     multiply(cur, 0, 0, 2);
     __builtin_amdgcn_sched_barrier(0);
-    if (NTW == 4) asm volatile("s_waitcnt vmcnt(20)\n\ts_barrier" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(15)\n\ts_barrier" ::: "memory");
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((kR - 3) * kLw) : "memory");
     issue(ks + kR - 1);
     read_ops(ks + 1, nxt);
     __builtin_amdgcn_sched_barrier(0);
