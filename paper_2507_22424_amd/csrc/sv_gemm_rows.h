@@ -1,23 +1,24 @@
 // The layer's products for MANY rows (several episodes verified together: hundreds of tree
 // rows) on the gfx950 matrix cores.
 //
-// With up to 64 rows the products are bound by the bytes of the weights and
+// With up to 128 rows the products are bound by the bytes of the weights and
 // gemm_stream_bf16 streams them once past activations that wait in LDS.  With hundreds of rows
 // the same products are bound by the matrix cores, and what has to be kept small is the traffic
-// per matrix instruction: every workgroup owns a 128-row x 256-column block of the output, keeps
-// (or 384-column) block of the output, keeps it in accumulator registers and walks the whole K range; both operands arrive already cut into
-// matrix-core fragments (1 KiB = 32 rows x 16 k-values, lane-major), so a fragment travels from
-// memory into LDS with one direct-to-LDS load instruction per wave and from LDS into operand
-// registers with one 16-byte read per lane, without any shuffling:
+// per matrix instruction: every workgroup owns a 128-row x 256-column (or 384-column) block of
+// the output, keeps it in accumulator registers and walks the whole K range; both operands
+// arrive already cut into matrix-core fragments (1 KiB = 32 rows x 16 k-values, lane-major), so
+// a fragment travels from memory into LDS with one direct-to-LDS load instruction per wave and
+// from LDS into operand registers with one 16-byte read per lane, without any shuffling:
 //   * weights: the packed layout of gemm_stream_bf16 as it is (same row permutations, so the
 //     RoPE / SwiGLU epilogues stay tile local);
 //   * activations: split_rows_kernel turns the float32 rows into hi + lo bf16 fragments once per
 //     product (RMSNorm applied on the way), so that the error of a product stays at float32
 //     rounding level as in the streaming kernel.
-// A ring of eight k-steps (16 KiB each: 8 activation + 8 weight fragments) lives in LDS; the
-// loads of a k-step are issued seven steps ahead, each wave waits for its own four loads with an
-// exact count and one barrier per k-step publishes them; operands of the next k-step are read
-// while the 16 matrix instructions of the current one run.
+// A ring of k-steps lives in LDS (256 columns: four k-steps of 16 KiB = 8 activation + 8 weight
+// fragments, two workgroups per CU; 384 columns: six k-steps of 20 KiB, one workgroup per CU);
+// the loads of a k-step are issued ring depth - 1 steps ahead, each wave waits for its own loads
+// with an exact count and one barrier per k-step publishes them; operands of the next k-step
+// are read while the matrix instructions of the current one run.
 // Workgroups are numbered so that an XCD works on four neighbouring column blocks times all row
 // blocks at a time: whatever two of them share is fetched into that XCD's L2 once.
 // Products with few columns (N = hidden) split K across two workgroups; their float32 partial
@@ -30,7 +31,7 @@
 namespace sv {
 
 constexpr int kRowsTM = 128;        // rows of a workgroup's output block
-constexpr int kRowsTN = 256;        // columns (384 for a product whose column count that divides into one round of the chip)
+constexpr int kRowsTN = 256;        // columns (384 where that makes the workgroups of a product a whole number of rounds of the chip)
 constexpr int kRowsKsplit = 2;      // K split of the products with N = hidden (too few column blocks to fill the chip)
 constexpr int kRowsMinTiles = 2;    // more 64-row tiles than this: the products run on gemm_rows_kernel
 
