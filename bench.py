@@ -287,8 +287,9 @@ def main():
     gemm_gbs = sum(gemm_bytes.values()) * L / (gemm_ms_raw * 1e-3) / 1e9
     # matrix-core work as issued: every product is done on the hi and on the lo half of the
     # float32 activations (2 x the algorithmic flops), on row tiles padded to 64 (128 for the
-    # many-row kernel)
-    m_issue = -(-M // 128) * 128 if M > 128 else -(-M // 64) * 64
+    # many-row kernels)
+    rows_path = M > 64 and not w8        # what sv_verify_layer routes to the many-row kernels
+    m_issue = -(-M // 128) * 128 if rows_path else -(-M // 64) * 64
     issued_flops = 2.0 * sum(gemm_flops.values()) * L * m_issue / M
     mfma_tflops = issued_flops / (gemm_ms_raw * 1e-3) / 1e12
     kv_bytes = sum(2 * cfg.n_heads * (int(p) + T) * cfg.head_dim * 2 for p in prefix_len)   # all episodes, one layer
@@ -309,7 +310,10 @@ def main():
                     "flops_per_launch_avg": issued_flops / (4 * L),
                     "avg_launch_us": gemm_ms_raw * 1e3 / (4 * L)}
     else:
-        roofline = {"bound": "hbm", "kernel": "gemm_stream_bf16 (4 launches per layer: q/k/v, o, gate/up, down)",
+        roofline = {"bound": "hbm",
+                    "kernel": ("gemm_rows_kernel (4 products per layer, K split across workgroups, with their "
+                               "split_rows / rows_rstd / rows_reduce_* launches)" if rows_path else
+                               "gemm_stream_bf16 (4 launches per layer: q/k/v, o, gate/up, down)"),
                     "achieved": gemm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": gemm_gbs / HBM_PEAK_GBS,
                     "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(key),

@@ -92,6 +92,42 @@ static int attention_splits(int n_tasks, int n_keys) {
   return s;
 }
 
+// Launch shape of one many-row product: columns per output block and workgroups per block
+// along K.  K is split (by powers of two, an even number of at least 8 k-steps each) while the
+// output blocks alone would fill less than about two thirds of the CUs.
+struct RowsPlan {
+  int tn, ksplit;
+};
+static RowsPlan rows_plan(int m_tiles, int N, int K, int n_xcd, bool may_widen) {
+  RowsPlan p;
+  p.tn = kRowsTN;
+  p.ksplit = 1;
+  const int cus = n_xcd * 32, nks = K / kFragK;
+  const int blocks = (N / kRowsTN) * m_tiles;
+  while (blocks * p.ksplit * 3 < cus * 2 && p.ksplit < kRowsMaxKsplit) {
+    const int s2 = p.ksplit * 2;
+    if (nks % s2 || (nks / s2) % 2 || nks / s2 < 8) break;
+    p.ksplit = s2;
+  }
+  // 384-column blocks where they give a whole number of rounds of the chip and 256-column blocks
+  // do not (q/k/v of the 7B shape with 8 row blocks: 256 workgroups instead of 384)
+  if (may_widen && p.ksplit == 1 && N % 384 == 0 && ((N / 384) * m_tiles) % cus == 0 && blocks % cus != 0)
+    p.tn = 384;
+  return p;
+}
+// bytes of float32 partial blocks the split products of a layer need at most (any XCD count)
+static size_t rows_part_bytes(int rows_pad, int H, int D, int F) {
+  size_t need = 0;
+  const int dims[4][2] = {{3 * D, H}, {H, D}, {2 * F, H}, {H, F}};
+  for (int n_xcd = 1; n_xcd <= kXcds; n_xcd *= 2)
+    for (int i = 0; i < 4; ++i) {
+      const RowsPlan p = rows_plan(rows_pad / kRowsTM, dims[i][0], dims[i][1], n_xcd, i == 0);
+      const size_t b = p.ksplit > 1 ? (size_t)p.ksplit * rows_pad * dims[i][0] * 4 : 0;
+      if (b > need) need = b;
+    }
+  return need;
+}
+
 static int device_xcds() {
   static int cached[64] = {0};               // hardware facts only; a race rewrites the same value
   int dev = 0;
@@ -151,7 +187,7 @@ static WorkspaceLayout workspace_layout(const sv_model_cfg& c, int m_rows, int n
     L.rows_pad = ceil_div(m_rows, kRowsTM) * kRowsTM;
     L.rows_xs = o;   o = align_up(o + (size_t)L.rows_pad * k_max * 4, kAlign);
     L.rows_rstd = o; o = align_up(o + (size_t)L.rows_pad * 4, kAlign);
-    L.rows_part = o; o = align_up(o + (size_t)kRowsKsplit * L.rows_pad * H * 4, kAlign);
+    L.rows_part = o; o = align_up(o + rows_part_bytes(L.rows_pad, (int)H, (int)(c.n_heads * c.head_dim), (int)F), kAlign);
   }
   // partial results of the tree attention when the keys of a task are split (bf16 models)
   L.att_part = 0;
@@ -395,24 +431,38 @@ static int verify_layer_rows(const sv_model_cfg& c, const char* packed, float* x
       split_rows_kernel<false><<<dim3(mb, K / 256), 256, 0, st>>>(src, nullptr, nullptr, M, K, xs);
     }
   };
-  auto shape = [&](size_t w_off, int N, int K, int ksplit, int tn) {
-    a.Wp = (const uint4*)(packed + w_off); a.N = N; a.K = K; a.n_tiles = N / tn; a.ksplit = ksplit;
-    return dim3(n_xcd, ceil_div(a.n_tiles, n_xcd) * a.m_tiles, ksplit);
-  };
-  // 384-column blocks where they give a whole number of rounds of the chip and 256-column blocks
-  // do not (q/k/v of the 7B shape with 8 row blocks: 256 workgroups instead of 384)
-  const int cus = n_xcd * 32;
-  const bool wide_qkv = (3 * D) % 384 == 0 && ((3 * D / 384) * a.m_tiles) % cus == 0 &&
-                        ((3 * D / 256) * a.m_tiles) % cus != 0;
-  auto reduce_resid = [&](int ksplit) {
-    const size_t n4 = (size_t)M * H / 4;
-    rows_reduce_resid_kernel<<<(unsigned)((n4 + 255) / 256), 256, 0, st>>>(
-        part, ksplit, (size_t)wl.rows_pad * H, x, x, n4);
+  const size_t plane = (size_t)wl.rows_pad;       // rows of one partial block
+  // One product: the unsplit kernel with its fused epilogue, or the K-split kernel followed by the
+  // reduction that carries the same epilogue.
+  auto product = [&](int epi, size_t w_off, int N, int K) {
+    const RowsPlan p = rows_plan(a.m_tiles, N, K, n_xcd, epi == EPI_QKV);
+    a.Wp = (const uint4*)(packed + w_off); a.N = N; a.K = K; a.n_tiles = N / p.tn; a.ksplit = p.ksplit;
+    const dim3 grid(n_xcd, ceil_div(a.n_tiles, n_xcd) * a.m_tiles, p.ksplit);
+    if (p.ksplit == 1 && epi == EPI_QKV) {
+      if (p.tn == 384) gemm_rows_kernel<EPI_QKV, false, 6><<<grid, 256, 0, st>>>(a);
+      else gemm_rows_kernel<EPI_QKV, false, 4><<<grid, 256, 0, st>>>(a);
+      return;
+    }
+    if (p.ksplit == 1 && epi == EPI_SWIGLU) {
+      gemm_rows_kernel<EPI_SWIGLU, false, 4><<<grid, 256, 0, st>>>(a);
+      return;
+    }
+    if (a.m_tiles == 1) gemm_rows_kernel<EPI_RESID, true, 4, true><<<grid, 256, 0, st>>>(a);
+    else gemm_rows_kernel<EPI_RESID, true, 4><<<grid, 256, 0, st>>>(a);
+    if (epi == EPI_RESID) {
+      const size_t n4 = (size_t)M * N / 4;
+      rows_reduce_resid_kernel<<<(unsigned)((n4 + 255) / 256), 256, 0, st>>>(part, p.ksplit, plane * N, x, x, n4);
+    } else if (epi == EPI_SWIGLU) {
+      const size_t n = (size_t)M * (N / 32) * 4;
+      rows_reduce_swiglu_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(part, p.ksplit, plane * N, M, N, act);
+    } else {
+      const size_t n = (size_t)M * (N / 32) * 16;
+      rows_reduce_qkv_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(part, p.ksplit, plane * N, a);
+    }
   };
   mark(0);
   split(x, (const float*)(packed + pl.g1), H);
-  if (wide_qkv) gemm_rows_kernel<EPI_QKV, false, 6><<<shape(pl.wqkv, 3 * D, H, 1, 384), 256, 0, st>>>(a);
-  else gemm_rows_kernel<EPI_QKV, false, 4><<<shape(pl.wqkv, 3 * D, H, 1, 256), 256, 0, st>>>(a);
+  product(EPI_QKV, pl.wqkv, 3 * D, H);
   mark(1);
   mark(2);
   {
@@ -425,17 +475,15 @@ static int verify_layer_rows(const sv_model_cfg& c, const char* packed, float* x
   }
   mark(3);
   split(attn, nullptr, D);
-  gemm_rows_kernel<EPI_RESID, true, 4><<<shape(pl.wo, H, D, kRowsKsplit, 256), 256, 0, st>>>(a);
-  reduce_resid(kRowsKsplit);
+  product(EPI_RESID, pl.wo, H, D);
   mark(4);
   mark(5);
   split(x, (const float*)(packed + pl.g2), H);
-  gemm_rows_kernel<EPI_SWIGLU, false, 4><<<shape(pl.wgu, 2 * F, H, 1, 256), 256, 0, st>>>(a);
+  product(EPI_SWIGLU, pl.wgu, 2 * F, H);
   mark(6);
   mark(7);
   split(act, nullptr, F);
-  gemm_rows_kernel<EPI_RESID, true, 4><<<shape(pl.wd, H, F, kRowsKsplit, 256), 256, 0, st>>>(a);
-  reduce_resid(kRowsKsplit);
+  product(EPI_RESID, pl.wd, H, F);
   mark(8);
   return launch_status();
 }

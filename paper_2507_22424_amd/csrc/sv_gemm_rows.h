@@ -21,8 +21,10 @@
 // are read while the matrix instructions of the current one run.
 // Workgroups are numbered so that an XCD works on four neighbouring column blocks times all row
 // blocks at a time: whatever two of them share is fetched into that XCD's L2 once.
-// Products with few columns (N = hidden) split K across two workgroups; their float32 partial
-// blocks are added in fixed order by rows_reduce_resid_kernel, which also adds the residual.
+// A product whose output blocks alone would leave the chip short of workgroups (N = hidden, or
+// few rows) splits K across up to 16 workgroups per block; their float32 partial blocks are added
+// in fixed order by a reduction kernel that carries the product's epilogue (residual, SwiGLU,
+// RoPE + K/V append).
 #ifndef SV_GEMM_ROWS_H
 #define SV_GEMM_ROWS_H
 
@@ -32,8 +34,8 @@ namespace sv {
 
 constexpr int kRowsTM = 128;        // rows of a workgroup's output block
 constexpr int kRowsTN = 256;        // columns (384 where that makes the workgroups of a product a whole number of rounds of the chip)
-constexpr int kRowsKsplit = 2;      // K split of the products with N = hidden (too few column blocks to fill the chip)
-constexpr int kRowsMinTiles = 2;    // more 64-row tiles than this: the products run on gemm_rows_kernel
+constexpr int kRowsMaxKsplit = 16;  // K split of a product whose output blocks alone would leave the chip short of workgroups
+constexpr int kRowsMinTiles = 1;    // more 64-row tiles than this: the products run on gemm_rows_kernel
 
 struct RowsArgs {
   const uint4* Xs;       // activations as fragments: [M_pad / 32][K / 16][hi, lo][64 lanes]
@@ -41,7 +43,7 @@ struct RowsArgs {
   int M, N, K;
   int m_tiles, n_tiles;  // blocks of kRowsTM rows / kRowsTN columns
   int n_xcd;
-  int ksplit;            // workgroups that share one output block along K (1 or 2)
+  int ksplit;            // workgroups that share one output block along K (1 .. kRowsMaxKsplit)
   float* part;           // ksplit > 1: [ksplit][m_tiles * kRowsTM][N] float32 partial sums
   // epilogues (ksplit == 1), as in gemm_stream_bf16
   float* act;            // EPI_SWIGLU: [M, N/2]
@@ -125,15 +127,94 @@ __global__ __launch_bounds__(256) void rows_reduce_resid_kernel(const float* __r
   reinterpret_cast<float4*>(x_io)[i] = s;
 }
 
+// The other two epilogues for products whose K range is split (few rows: the column blocks
+// alone would leave most of the chip idle).  Both add the ksplit partial blocks in fixed order
+// and then do what the fused epilogue of the unsplit kernel does, with the same arithmetic.
+// Columns are in the packed order of the weights: tile = 32 columns, lanes 0..15 and 16..31 of a
+// tile hold the two partners of a pair (gate / up of one output column; the rotary pair
+// (j, j + 64) of a head).
+
+// act[m][tile * 16 + j] = silu(gate) * up.  One thread = 4 output columns.
+__global__ __launch_bounds__(256) void rows_reduce_swiglu_kernel(const float* __restrict__ part, int ksplit,
+                                                                 size_t plane, int M, int N,
+                                                                 float* __restrict__ act) {
+  const int F = N / 2;
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;   // (row, tile, quarter)
+  const size_t per_row = (size_t)(N / 32) * 4;
+  if (i >= (size_t)M * per_row) return;
+  const int m = (int)(i / per_row);
+  const int rem = (int)(i - (size_t)m * per_row);
+  const int tile = rem >> 2, j4 = (rem & 3) * 4;
+  float4 g = make_float4(0.f, 0.f, 0.f, 0.f), u = g;
+  for (int z = 0; z < ksplit; ++z) {
+    const float* p = part + (size_t)z * plane + (size_t)m * N + tile * 32 + j4;
+    const float4 pg = *reinterpret_cast<const float4*>(p);
+    const float4 pu = *reinterpret_cast<const float4*>(p + 16);
+    g.x += pg.x; g.y += pg.y; g.z += pg.z; g.w += pg.w;
+    u.x += pu.x; u.y += pu.y; u.z += pu.z; u.w += pu.w;
+  }
+  const float4 o = make_float4(silu_fast(g.x) * u.x, silu_fast(g.y) * u.y, silu_fast(g.z) * u.z,
+                               silu_fast(g.w) * u.w);
+  *reinterpret_cast<float4*>(act + (size_t)m * F + tile * 16 + j4) = o;
+}
+
+// q/k/v: RoPE at position prefix + depth on q and k, q written as float32, k and v appended to the
+// bf16 cache.  One thread = one pair of partner columns of one row.
+__global__ __launch_bounds__(256) void rows_reduce_qkv_kernel(const float* __restrict__ part, int ksplit,
+                                                              size_t plane, const RowsArgs a) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;   // (row, tile, j)
+  const size_t per_row = (size_t)(a.N / 32) * 16;
+  if (i >= (size_t)a.M * per_row) return;
+  const int m = (int)(i / per_row);
+  const int rem = (int)(i - (size_t)m * per_row);
+  const int tile = rem >> 4, j = rem & 15;
+  float v0 = 0.f, v1 = 0.f;
+  for (int z = 0; z < ksplit; ++z) {
+    const float* p = part + (size_t)z * plane + (size_t)m * a.N + tile * 32 + j;
+    v0 += p[0];
+    v1 += p[16];
+  }
+  const int b = m / a.T, t = m - b * a.T;
+  int P = a.prefix_len[b];
+  P = P < 0 ? 0 : (P > a.p_max ? a.p_max : P);
+  const int tiles_per_mat = a.nh * 4;
+  const int which = tile / tiles_per_mat;
+  const int head = (tile % tiles_per_mat) / 4, uq = tile % 4;
+  const int jr = 16 * uq + j;
+  float o0 = v0, o1 = v1;
+  if (which != 2) {
+    const float turn_freq = exp2f(-(float)jr * (1.0f / 64.0f) * log2f(a.theta)) * 0.15915494309189535f;
+    float turns = (float)(P + a.depth[m]) * turn_freq;
+    turns -= floorf(turns);
+    const float c = __builtin_amdgcn_cosf(turns), s = __builtin_amdgcn_sinf(turns);
+    o0 = v0 * c - v1 * s;
+    o1 = v1 * c + v0 * s;
+  }
+  const int D = a.nh * 128;
+  if (which == 0) {
+    float* q = a.q_out + (size_t)m * D + head * 128 + jr;
+    q[0] = o0;
+    q[64] = o1;
+  } else {
+    bf16_t* cache = which == 1 ? a.kc : a.vc;
+    bf16_t* dst = cache + ((size_t)b * a.nh * a.cap + (size_t)head * a.cap + P + t) * 128 + jr;
+    dst[0] = f32_to_bf16(o0);
+    dst[64] = f32_to_bf16(o1);
+  }
+}
+
 // grid = (n_xcd, ceil(n_tiles / n_xcd) * m_tiles, ksplit), block = 256 (waves 2 x 2: rows wm * 64,
 // columns wn * 32 * NTW of the block).  NTW = weight tiles (32 columns) per wave: 4 gives blocks
 // of 256 columns, 6 blocks of 384 (for the q/k/v product of the 7B shape: 32 column blocks x 8 row
 // blocks = 256 workgroups, one full round of the chip instead of one and a half).
-template <int EPI, bool SPLIT, int NTW>
-__global__ __launch_bounds__(256, NTW == 4 ? 2 : 1) void gemm_rows_kernel(const RowsArgs a) {
+// DEEP: eight k-steps in LDS and one workgroup per CU instead of four k-steps and two workgroups:
+// for a single block of rows, where every weight byte comes from HBM and is used once, the loads
+// in flight per workgroup are what sets its pace.
+template <int EPI, bool SPLIT, int NTW, bool DEEP = false>
+__global__ __launch_bounds__(256, (NTW == 4 && !DEEP) ? 2 : 1) void gemm_rows_kernel(const RowsArgs a) {
   constexpr int kFr = 8 + 2 * NTW;                 // fragments per k-step: 4 row blocks x (hi, lo), 2 * NTW weight tiles
   constexpr int kLw = kFr / 4;                     // direct-to-LDS loads per wave and k-step
-  constexpr int kR = NTW == 4 ? 4 : 6;             // k-steps resident in LDS (64 KiB, two workgroups per CU / 120 KiB)
+  constexpr int kR = NTW == 6 ? 6 : (DEEP ? 8 : 4);   // k-steps resident in LDS (120 / 128 / 64 KiB)
   static_assert(kFr % 4 == 0 && (NTW == 4 || NTW == 6), "fragment loads are dealt evenly to the four waves");
   __shared__ uint4 ring[kR][kFr][64];
   __shared__ int s_pos[kRowsTM], s_crow[kRowsTM];
