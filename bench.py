@@ -19,13 +19,22 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = 2500.0           # dense bf16
-# HBM-side bytes per launch of the dominant kernel, from the two rocprofv3 --pmc runs (FETCH_SIZE
-# calibrated with a 1 GiB copy in the same run, then WRITE_SIZE) whose summaries are under
-# profiles/: average over the four GEMM launches of a layer.  None where no such summary exists.
+# HBM-side bytes per launch of the dominant kernel, from the two rocprofv3 --pmc runs (FETCH_SIZE,
+# then WRITE_SIZE, each calibrated with a transfer of known size in the same run) whose summaries
+# are under profiles/: fetched + written bytes, averaged over the four products of a layer (for
+# the many-row kernels with the split / row-norm / reduction launches that belong to a product).
 TRAFFIC_BYTES_PER_LAUNCH = {
-    ("C3", "bf16"): (211.68 + 25.30 + 121.97 + 14.64 + 117.04 + 5.20 + 47.08 + 5.20) / 4 * 1e6,
+    ("C3", "bf16"): 137.02e6,
+    ("C3", "w8"): 86.46e6,
+    ("C4", "bf16"): 479.19e6,
+    ("C5", "bf16"): 185.86e6,
 }
-TRAFFIC_SOURCE = {("C3", "bf16"): "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/c3_step_hbm_traffic.txt"}
+TRAFFIC_SOURCE = {
+    ("C3", "bf16"): "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/c3_step_hbm_traffic.txt",
+    ("C3", "w8"): "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/c3_w8_step_hbm_traffic.txt",
+    ("C4", "bf16"): "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/c4_step_hbm_traffic.txt",
+    ("C5", "bf16"): "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/c5_step_hbm_traffic.txt",
+}
 
 
 def log(msg):
@@ -305,6 +314,7 @@ def main():
                     "achieved": mfma_tflops, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": mfma_tflops / MFMA_PEAK_TFLOPS,
                     "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(key),
+                    "traffic_source": TRAFFIC_SOURCE.get(key),
                     "flops_counted": "matrix-core flops as issued: hi and lo halves of the activations, rows padded to 128",
                     "algorithmic_frac": step_flops / (gemm_ms_raw * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
                     "flops_per_launch_avg": issued_flops / (4 * L),
