@@ -165,9 +165,10 @@ def main():
                     help="C3 is the benchmark workload; C4 (16 episodes) and C5 (prefix 2048, 128 "
                          "nodes) are parity configurations that can be timed and profiled the "
                          "same way (no CPU baseline)")
-    ap.add_argument("--weights", choices=("bf16", "w8"), default="bf16",
-                    help="w8: the same workload with 8-bit (E4M3 + row scale) matrices, a variant "
-                         "of its own: half the weight bytes, not the headline configuration")
+    ap.add_argument("--weights", choices=("bf16", "w8", "w4"), default="bf16",
+                    help="w8 / w4: the same workload with 8-bit (E4M3) or 4-bit integer matrices "
+                         "(+ a scale per output row), variants of their own: half / a quarter of "
+                         "the weight bytes, not the headline configuration")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (calibrates rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters in the same profile)")
@@ -187,9 +188,10 @@ def main():
 
     base = {"C3": wl.C3, "C4": wl.C4, "C5": wl.C5}[args.config]
     cfg = base if args.layers is None else base.scaled(n_layers=args.layers)
-    w8 = args.weights == "w8"
+    w8 = args.weights != "bf16"          # low-precision weight storage (8-bit E4M3 or 4-bit integer codes)
+    w4 = args.weights == "w4"
     if w8:
-        cfg = cfg.scaled(dtype="bf16_w8")
+        cfg = cfg.scaled(dtype="bf16_w4" if w4 else "bf16_w8")
     headline = args.config == "C3" and not w8 and args.layers is None
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
@@ -201,7 +203,8 @@ def main():
 
     t0 = time.time()
     with ThreadPoolExecutor(max_workers=8) as ex:
-        futs = [ex.submit(wl.layer_weights_w8 if w8 else wl.layer_weights, cfg, l) for l in range(L)]
+        futs = [ex.submit(wl.layer_weights_w4 if w4 else (wl.layer_weights_w8 if w8 else wl.layer_weights), cfg, l)
+                for l in range(L)]
         for l, f in enumerate(futs):
             vp.load_layer(l, f.result())
             futs[l] = None
@@ -289,7 +292,7 @@ def main():
     scale = layers_ms / sum(raw_ms.values())
     per_step_ms = {k: v * scale for k, v in raw_ms.items()}
     H, D, F = cfg.hidden, cfg.n_heads * cfg.head_dim, cfg.mlp_dim
-    wb = 1 if w8 else 2                  # bytes per weight (the row scales of w8 are 0.1 % more)
+    wb = 0.5 if w4 else (1 if w8 else 2)   # bytes per weight (the row scales of w8 / w4 are 0.1 % more)
     gemm_bytes = {"qkv": 3 * D * H * wb, "o": H * D * wb, "gate_up": 2 * F * H * wb, "down": H * F * wb}
     gemm_flops = {k: 2.0 * M * v / wb for k, v in gemm_bytes.items()}          # algorithmic, per layer
     gemm_ms_raw = sum(raw_ms[k] for k in gemm_bytes)
@@ -338,12 +341,12 @@ def main():
         "value": tokens_per_s, "unit": "verified tree tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 (8-bit E4M3 weights)" if w8 else "bf16",
+        "dtype": "bf16 (4-bit integer weights)" if w4 else ("bf16 (8-bit E4M3 weights)" if w8 else "bf16"),
         "data": "synthetic",
         "config": {"workload": f"{args.config}: {L}-layer 7B-shaped verify pass + 256-bin action head + "
                                f"relaxed accept (r={args.r}), tree {T} nodes depth 7, prefix "
                                f"{int(prefix_len.min())}" + (f"..{int(prefix_len.max())}" if B > 1 else "") +
-                               f", {B} episode" + ("s" if B > 1 else "") + (", 8-bit weights" if w8 else ""),
+                               f", {B} episode" + ("s" if B > 1 else "") + (", 4-bit weights" if w4 else (", 8-bit weights" if w8 else "")),
                    "hidden": H, "layers": L, "tree_nodes": T, "prefix": int(prefix_len[0]),
                    "episodes": B,
                    "launch": "HIP graph replay" if graph is not None else "host launches"},

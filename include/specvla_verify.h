@@ -44,7 +44,7 @@ extern "C" {
 #define SV_ERR_TREE (-3)      /* parent array is not a tree in the stated form, or too deep */
 #define SV_ERR_TOKEN (-4)     /* action range / threshold arguments are inconsistent */
 #define SV_ERR_WORKSPACE (-5) /* workspace or packed buffer too small or misaligned */
-#define SV_ERR_DTYPE (-6)     /* cfg->dtype is none of SV_F32, SV_BF16, SV_BF16_W8 (or the wrong one for the call) */
+#define SV_ERR_DTYPE (-6)     /* cfg->dtype is none of SV_F32, SV_BF16, SV_BF16_W8, SV_BF16_W4 (or the wrong one for the call) */
 #define SV_ERR_LAUNCH (-7)    /* the HIP runtime reported an error at launch */
 
 #define SV_F32 0
@@ -55,13 +55,19 @@ extern "C" {
  * App. C runs the verifier on weights held in fewer bits; on a path bound by the bytes of the
  * weights this halves them.  Packed with sv_pack_layer_w8; every other call is the same. */
 #define SV_BF16_W8 2
+/* The same with 4-bit integer codes (App. C, Tables 5 and 6: int4 weights): a code c in 0 .. 15
+ * stands for the integer c - 8, W[n][k] = (code[n][k] - 8) * scale[n] with one float32 scale per
+ * output row; a raw matrix holds two codes per byte, the code of the even k in the low four
+ * bits.  Packed with sv_pack_layer_w4 (K of every matrix must be a multiple of 256, as for
+ * SV_BF16); every other call is the same. */
+#define SV_BF16_W4 3
 
 #define SV_MAX_TREE_NODES 128 /* T <= 128: the ancestor mask has at most two 64-bit words */
 #define SV_MAX_DEPTH 31       /* depth of a node, in edges */
 
 /* Shape of the verifier (Sec. 4.1, 5.1: OpenVLA = Llama-2 backbone). */
 typedef struct sv_model_cfg {
-  int32_t dtype;      /* SV_F32, SV_BF16 or SV_BF16_W8: storage type of weights and KV cache */
+  int32_t dtype;      /* SV_F32, SV_BF16, SV_BF16_W8 or SV_BF16_W4: storage type of weights and KV cache */
   int32_t hidden;     /* H */
   int32_t n_heads;    /* nh (multi-head attention, n_kv_heads = n_heads) */
   int32_t head_dim;   /* d; nh * d is the attention width (need not equal H) */
@@ -129,7 +135,7 @@ int sv_packed_layer_bytes(const sv_model_cfg *cfg, size_t *bytes);
 int sv_pack_layer(const sv_model_cfg *cfg, const sv_layer_weights *raw, void *packed,
                   size_t packed_bytes, void *stream);
 
-/* The row scales of a layer's matrices for SV_BF16_W8: [device] float32, sq, sk, sv: [nh*d];
+/* The row scales of a layer's matrices for SV_BF16_W8 and SV_BF16_W4: [device] float32, sq, sk, sv: [nh*d];
  * so, sd: [H]; sg, su: [F]. */
 typedef struct sv_layer_scales {
   const float *sq, *sk, *sv, *so, *sg, *su, *sd;
@@ -140,6 +146,15 @@ typedef struct sv_layer_scales {
  * row scales.  Same size rules as SV_BF16; packed_bytes >= sv_packed_layer_bytes(cfg).
  * SV_ERR_DTYPE for any other dtype (and sv_pack_layer returns it for SV_BF16_W8). */
 int sv_pack_layer_w8(const sv_model_cfg *cfg, const sv_layer_weights *raw,
+                     const sv_layer_scales *scales, void *packed, size_t packed_bytes,
+                     void *stream);
+
+/* sv_pack_layer for cfg->dtype = SV_BF16_W4 (App. C: int4 weights): raw->g1, g2 are bf16 gains,
+ * raw->wq .. wd the int4 codes, [device] uint8 [out][in / 2] (two codes per byte, even k in the
+ * low four bits), scales their row scales as for sv_pack_layer_w8.  Same size rules as SV_BF16;
+ * packed_bytes >= sv_packed_layer_bytes(cfg).  SV_ERR_DTYPE for any other dtype (and
+ * sv_pack_layer returns it for SV_BF16_W4). */
+int sv_pack_layer_w4(const sv_model_cfg *cfg, const sv_layer_weights *raw,
                      const sv_layer_scales *scales, void *packed, size_t packed_bytes,
                      void *stream);
 

@@ -15,7 +15,7 @@ import torch
 
 from .build import LIB_PATH
 
-SV_F32, SV_BF16, SV_BF16_W8 = 0, 1, 2
+SV_F32, SV_BF16, SV_BF16_W8, SV_BF16_W4 = 0, 1, 2, 3
 (SV_OK, SV_ERR_NULL, SV_ERR_SHAPE, SV_ERR_TREE, SV_ERR_TOKEN, SV_ERR_WORKSPACE, SV_ERR_DTYPE,
  SV_ERR_LAUNCH) = (0, -1, -2, -3, -4, -5, -6, -7)
 SV_MAX_TREE_NODES = 128
@@ -23,7 +23,7 @@ SV_MAX_DEPTH = 31
 SV_WS_ATTN_OUT, SV_WS_Q, SV_WS_STATUS = 0, 1, 2
 
 EXPORTS = ("sv_version", "sv_strerror", "sv_tree_build_masks", "sv_packed_layer_bytes",
-           "sv_pack_layer", "sv_pack_layer_w8", "sv_workspace_bytes", "sv_workspace_init", "sv_workspace_region",
+           "sv_pack_layer", "sv_pack_layer_w8", "sv_pack_layer_w4", "sv_workspace_bytes", "sv_workspace_init", "sv_workspace_region",
            "sv_verify_layer",
            "sv_verify_layer_timed", "sv_verify_stack",
            "sv_action_head_argmax", "sv_action_head_argmax_noalloc", "sv_packed_head_bytes", "sv_pack_head",
@@ -82,6 +82,7 @@ def lib() -> C.CDLL:
                                     C.c_size_t, C.c_void_p]
         l.sv_pack_layer_w8.argtypes = [C.POINTER(ModelCfg), C.POINTER(LayerWeights),
                                        C.POINTER(LayerScales), C.c_void_p, C.c_size_t, C.c_void_p]
+        l.sv_pack_layer_w4.argtypes = l.sv_pack_layer_w8.argtypes
         l.sv_workspace_bytes.argtypes = [C.POINTER(ModelCfg), C.c_int, C.c_int, C.c_int,
                                          C.POINTER(C.c_size_t)]
         l.sv_workspace_init.argtypes = [C.POINTER(ModelCfg), C.c_int, C.c_int, C.c_int, C.c_void_p,
@@ -145,7 +146,7 @@ def _stream(stream) -> int:
 
 def model_cfg(dtype: str, hidden: int, n_heads: int, head_dim: int, mlp_dim: int, vocab: int,
               rms_eps: float = 1e-5, rope_theta: float = 1e4) -> ModelCfg:
-    code = {"f32": SV_F32, "bf16": SV_BF16, "bf16_w8": SV_BF16_W8}.get(dtype, dtype)
+    code = {"f32": SV_F32, "bf16": SV_BF16, "bf16_w8": SV_BF16_W8, "bf16_w4": SV_BF16_W4}.get(dtype, dtype)
     return ModelCfg(int(code), hidden, n_heads, head_dim, mlp_dim, vocab, rms_eps, rope_theta)
 
 
@@ -201,6 +202,18 @@ def sv_pack_layer_w8(cfg: ModelCfg, raw: Dict[str, torch.Tensor], packed: torch.
     _check(lib().sv_pack_layer_w8(C.byref(cfg), C.byref(w), C.byref(sc),
                                   _dev(packed, torch.uint8, "packed"), packed.numel(),
                                   _stream(stream)), "sv_pack_layer_w8")
+
+
+def sv_pack_layer_w4(cfg: ModelCfg, raw: Dict[str, torch.Tensor], packed: torch.Tensor,
+                     stream=None) -> None:
+    """raw: gains g1, g2 (bf16), int4 codes wq .. wd (uint8 [out, in / 2], two codes per byte, even
+    k in the low four bits) and row scales wq_scale .. wd_scale (float32)."""
+    w = LayerWeights(*[_dev(raw[n], torch.bfloat16 if n.startswith("g") else torch.uint8, n)
+                       for n, _ in LayerWeights._fields_])
+    sc = LayerScales(*[_dev(raw["w" + n[1] + "_scale"], torch.float32, n) for n, _ in LayerScales._fields_])
+    _check(lib().sv_pack_layer_w4(C.byref(cfg), C.byref(w), C.byref(sc),
+                                  _dev(packed, torch.uint8, "packed"), packed.numel(),
+                                  _stream(stream)), "sv_pack_layer_w4")
 
 
 def sv_workspace_bytes(cfg: ModelCfg, B: int, T: int, n_scored: int) -> int:

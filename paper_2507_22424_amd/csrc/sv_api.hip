@@ -21,7 +21,8 @@ namespace sv {
 
 static int check_cfg(const sv_model_cfg* c) {
   if (!c) return SV_ERR_NULL;
-  if (c->dtype != SV_F32 && c->dtype != SV_BF16 && c->dtype != SV_BF16_W8) return SV_ERR_DTYPE;
+  if (c->dtype != SV_F32 && c->dtype != SV_BF16 && c->dtype != SV_BF16_W8 && c->dtype != SV_BF16_W4)
+    return SV_ERR_DTYPE;
   if (c->hidden < 1 || c->n_heads < 1 || c->head_dim < 2 || c->mlp_dim < 1 || c->vocab < 1)
     return SV_ERR_SHAPE;
   if ((c->head_dim & 1) || c->head_dim > 128) return SV_ERR_SHAPE;
@@ -339,20 +340,23 @@ static int verify_layer_bf16(const sv_model_cfg& c, const char* packed, float* x
     multi = p.multi;
   };
   // the kernel form for the shape just planned: single- or multi-chunk K slices
-#define SV_LAUNCH_GEMM2(PRO, EPI, W8, ROWS)                                             \
+#define SV_LAUNCH_GEMM2(PRO, EPI, WF, ROWS)                                             \
   do {                                                                                 \
-    if (multi) gemm_stream_bf16<PRO, EPI, true, W8, ROWS><<<grid, 256, 0, st>>>(a);    \
-    else gemm_stream_bf16<PRO, EPI, false, W8, ROWS><<<grid, 256, 0, st>>>(a);         \
+    if (multi) gemm_stream_bf16<PRO, EPI, true, WF, ROWS><<<grid, 256, 0, st>>>(a);    \
+    else gemm_stream_bf16<PRO, EPI, false, WF, ROWS><<<grid, 256, 0, st>>>(a);         \
   } while (0)
 #define SV_LAUNCH_GEMM(PRO, EPI)                                                       \
   do {                                                                                 \
-    if (w8 && rows) SV_LAUNCH_GEMM2(PRO, EPI, true, true);                             \
-    else if (w8) SV_LAUNCH_GEMM2(PRO, EPI, true, false);                               \
-    else if (rows) SV_LAUNCH_GEMM2(PRO, EPI, false, true);                             \
-    else SV_LAUNCH_GEMM2(PRO, EPI, false, false);                                      \
+    if (wf == 2 && rows) SV_LAUNCH_GEMM2(PRO, EPI, 2, true);                           \
+    else if (wf == 2) SV_LAUNCH_GEMM2(PRO, EPI, 2, false);                             \
+    else if (wf == 1 && rows) SV_LAUNCH_GEMM2(PRO, EPI, 1, true);                      \
+    else if (wf == 1) SV_LAUNCH_GEMM2(PRO, EPI, 1, false);                             \
+    else if (rows) SV_LAUNCH_GEMM2(PRO, EPI, 0, true);                                 \
+    else SV_LAUNCH_GEMM2(PRO, EPI, 0, false);                                          \
   } while (0)
 
-  const bool w8 = c.dtype == SV_BF16_W8;
+  const int wf = c.dtype == SV_BF16_W8 ? 1 : (c.dtype == SV_BF16_W4 ? 2 : 0);   // weight format of the kernels
+  const bool w8 = wf != 0;                                                        // row scales present
   a.X = x; a.gain = (const float*)(packed + pl.g1); a.Wp = (const uint4*)(packed + pl.wqkv);
   a.wscale = w8 ? (const float*)(packed + pl.sqkv) : nullptr;
   shape(3 * D, H);
@@ -663,17 +667,17 @@ int sv_pack_layer(const sv_model_cfg* cfg, const sv_layer_weights* raw, void* pa
     return SV_ERR_NULL;
   if (packed_bytes < packed_layout(*cfg).total || ((uintptr_t)packed % kAlign))
     return SV_ERR_WORKSPACE;
-  if (cfg->dtype == SV_BF16_W8) return SV_ERR_DTYPE;      // sv_pack_layer_w8 takes the scales
+  if (cfg->dtype == SV_BF16_W8 || cfg->dtype == SV_BF16_W4) return SV_ERR_DTYPE;   // sv_pack_layer_w8 / _w4 take the scales
   if (cfg->dtype == SV_F32) return pack_layer_t<float>(*cfg, *raw, (char*)packed, (hipStream_t)stream);
   return pack_layer_t<bf16_t>(*cfg, *raw, (char*)packed, (hipStream_t)stream);
 }
 
-int sv_pack_layer_w8(const sv_model_cfg* cfg, const sv_layer_weights* raw,
-                     const sv_layer_scales* sc, void* packed_v, size_t packed_bytes,
-                     void* stream) {
+static int pack_layer_codes(const sv_model_cfg* cfg, const sv_layer_weights* raw,
+                            const sv_layer_scales* sc, void* packed_v, size_t packed_bytes,
+                            void* stream, int dtype) {
   const int rc = check_cfg(cfg);
   if (rc != SV_OK) return rc;
-  if (cfg->dtype != SV_BF16_W8) return SV_ERR_DTYPE;
+  if (cfg->dtype != dtype) return SV_ERR_DTYPE;
   if (!raw || !sc || !packed_v || !raw->g1 || !raw->wq || !raw->wk || !raw->wv || !raw->wo ||
       !raw->g2 || !raw->wg || !raw->wu || !raw->wd || !sc->sq || !sc->sk || !sc->sv || !sc->so ||
       !sc->sg || !sc->su || !sc->sd)
@@ -699,12 +703,28 @@ int sv_pack_layer_w8(const sv_model_cfg* cfg, const sv_layer_weights* raw,
       {raw->wd, sc->sd, pl.wd, pl.sd, H, F, PACK_PLAIN, 0}};
   for (const Piece& p : pieces) {
     const size_t n8 = (size_t)p.rows * (p.k / 8);
-    pack_rows_mfma_w8<<<(unsigned)((n8 + 255) / 256), 256, 0, st>>>(
-        (const uint2*)p.src, (uint2*)(packed + p.dst), p.rows, p.k, p.mode, p.off);
+    if (dtype == SV_BF16_W4)
+      pack_rows_mfma_w4<<<(unsigned)((n8 + 255) / 256), 256, 0, st>>>(
+          (const uint32_t*)p.src, (uint32_t*)(packed + p.dst), p.rows, p.k, p.mode, p.off);
+    else
+      pack_rows_mfma_w8<<<(unsigned)((n8 + 255) / 256), 256, 0, st>>>(
+          (const uint2*)p.src, (uint2*)(packed + p.dst), p.rows, p.k, p.mode, p.off);
     pack_row_scales<<<ceil_div(p.rows, 256), 256, 0, st>>>(p.scale, (float*)(packed + p.sdst), p.rows,
                                                            p.mode, p.off);
   }
   return launch_status();
+}
+
+int sv_pack_layer_w8(const sv_model_cfg* cfg, const sv_layer_weights* raw,
+                     const sv_layer_scales* sc, void* packed_v, size_t packed_bytes,
+                     void* stream) {
+  return pack_layer_codes(cfg, raw, sc, packed_v, packed_bytes, stream, SV_BF16_W8);
+}
+
+int sv_pack_layer_w4(const sv_model_cfg* cfg, const sv_layer_weights* raw,
+                     const sv_layer_scales* sc, void* packed_v, size_t packed_bytes,
+                     void* stream) {
+  return pack_layer_codes(cfg, raw, sc, packed_v, packed_bytes, stream, SV_BF16_W4);
 }
 
 int sv_workspace_bytes(const sv_model_cfg* cfg, int B, int T, int n_scored, size_t* bytes) {

@@ -114,6 +114,18 @@ __global__ void pack_rows_mfma_w8(const uint2* __restrict__ src, uint2* __restri
   const size_t load = (size_t)(n / kFragRows) * (K / 32) + (kc8 >> 2);
   dst[(load * 64 + (n % kFragRows) + 32 * (kc8 & 1)) * 2 + ((kc8 >> 1) & 1)] = src[i];
 }
+// int4 codes: `src` holds a row's K codes two per byte (even k in the low nibble), i.e. 8 codes
+// per 32-bit word in k order.  A 16-byte load of the packed form carries a lane's 8 codes of four
+// consecutive k-steps: word s of lane (n % 32) + 32 * (k-half) is k-step s of the load.
+__global__ void pack_rows_mfma_w4(const uint32_t* __restrict__ src, uint32_t* __restrict__ dst, int rows,
+                                  int K, int mode, int off) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int per_row = K / 8;
+  if (i >= (size_t)rows * per_row) return;
+  const int n = packed_row((int)(i / per_row), mode, off), kc8 = (int)(i % per_row);
+  const size_t load = (size_t)(n / kFragRows) * (K / 64) + (kc8 >> 3);
+  dst[(load * 64 + (n % kFragRows) + 32 * (kc8 & 1)) * 4 + ((kc8 >> 1) & 3)] = src[i];
+}
 __global__ void pack_row_scales(const float* __restrict__ src, float* __restrict__ dst, int rows,
                                 int mode, int off) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -318,6 +330,27 @@ __device__ inline void w8_to_frags(const u32x4_t raw, bf16x8_t& f0, bf16x8_t& f1
   f1 = __builtin_bit_cast(bf16x8_t, b);
 }
 
+// One 16-byte load of int4 codes (a lane's 8 codes of four consecutive k-steps, one 32-bit word
+// per k-step, code i of a word in bits 4i .. 4i+3) -> four bf16 operand fragments.  A code c
+// stands for the integer c - 8 (-8 .. 7): the code with its top bit flipped is that integer in
+// 4-bit two's complement, which a signed bit-field extract widens; integer -> float32 ->
+// bf16 is exact for these values.
+__device__ inline void w4_to_frags(const u32x4_t raw, bf16x8_t (&f)[4]) {
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    const int w = (int)(raw[d] ^ 0x88888888u);
+    u32x4_t o;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      // (the builtin's result type is unsigned: the cast to int comes first)
+      const float lo = (float)(int)__builtin_amdgcn_sbfe(w, 8 * j, 4);
+      const float hi = (float)(int)__builtin_amdgcn_sbfe(w, 8 * j + 4, 4);
+      o[j] = pack_bf16x2(lo, hi);
+    }
+    f[d] = __builtin_bit_cast(bf16x8_t, o);
+  }
+}
+
 // 16-byte load of four floats from global memory
 __device__ inline float4 ldg_f4(const __attribute__((address_space(1))) float* p) {
   const f32x4_t v = *(const __attribute__((address_space(1))) f32x4_t*)p;
@@ -341,7 +374,7 @@ __device__ inline int frag_slot(int l, int s) { return ((l & 31) ^ (((s & 7) << 
 // loop, where spilled scalars cost stalls between the matrix instructions.
 typedef const __attribute__((address_space(4))) GemmArgs* gemm_args_ptr_t;
 typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
-template <int PRO, int EPI, bool W8>
+template <int PRO, int EPI, int WF>
 __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos, int* s_crow,
                                                   int tid, int lane, int wave, int xcd, int u, int mt) {
   GemmArgs a;                                // one batch of scalar loads; registers from here on
@@ -483,7 +516,7 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
           for (int j = 0; j < 4; ++j)
             xres[bi][j] = x_res[(size_t)min(m0 + row0 + j, a.M - 1) * a.N + tile * 32 + ln];
         }
-        if (W8) wsc[bi] = wscale[tile * 32 + ln];
+        if (WF) wsc[bi] = wscale[tile * 32 + ln];
       }
       // The phase is bound by the round trips of these loads, not by arithmetic: keep the whole
       // batch in flight together (left alone, the compiler sinks loads towards their uses).
@@ -550,7 +583,7 @@ __device__ __forceinline__ void gemm_reduce_phase(gemm_args_ptr_t ap, int* s_pos
 #pragma unroll
           for (int j = 0; j < 4; ++j) v[j] *= rstd4[j];
         }
-        if (W8) {
+        if (WF) {
 #pragma unroll
           for (int j = 0; j < 4; ++j) v[j] *= wsc[bi];
         }
@@ -643,16 +676,17 @@ constexpr size_t kGemmLdsAlloc = kGemmLdsBytes;
 // of X in LDS holds up to two pieces.
 // MULTI: a K slice may span several LDS chunks (the host knows from its plan); the single-chunk
 // form carries no re-staging code and nothing of it in registers through the main loop.
-// W8: the weights are E4M3 codes (four loads per piece, converted to bf16 fragments in
-// registers; the row scales are applied in the reduction).
+// WF (weight format): 0 = bf16 fragments as they are; 1 = E4M3 codes (four loads per piece), 2 =
+// int4 codes (two loads per piece), both converted to bf16 fragments in registers, the row scales
+// applied in the reduction.
 // KEEP: the weights are read again, shortly afterwards, by the workgroups that multiply the
 // same tiles with the other row tiles (more than 64 rows): the loads are ordinary ones, which the
 // XCD's L2 keeps, instead of the non-temporal ones of the single-row-tile case.
-template <int PRO, int EPI, bool MULTI, bool W8, bool KEEP>
+template <int PRO, int EPI, bool MULTI, int WF, bool KEEP>
 __device__ __forceinline__ void gemm_stream_body(gemm_args_ptr_t ap, const int xcd, const int u,
                                                  const int mt, const GemmLds lds) {
   const __attribute__((address_space(4))) GemmArgs& a = *ap;
-  constexpr int kLoads = W8 ? kPieceFrags / 2 : kPieceFrags;   // 16-byte loads per piece and lane
+  constexpr int kLoads = kPieceFrags >> WF;   // 16-byte loads per piece and lane: 8 (bf16), 4 (E4M3), 2 (int4)
   uint4* const xs = lds.xs;
   int* const s_pos = lds.s_pos;
   int* const s_crow = lds.s_crow;
@@ -701,7 +735,7 @@ __device__ __forceinline__ void gemm_stream_body(gemm_args_ptr_t ap, const int x
     const size_t xbase = (size_t)mt * a.n_xcd + xcd;     // this XCD's share of the scratch regions
     const size_t unit_id = xbase * a.ucap + u;
     const int t0x = xcd * a.gpx * tq + min(xcd * a.gpx, trem);   // first tile of this XCD
-    const size_t tile_stride = (size_t)(K / (W8 ? 2 * kFragK : kFragK)) * 64;   // uint4 per tile
+    const size_t tile_stride = (size_t)(K / (kFragK << WF)) * 64;   // uint4 per tile
     typedef const __attribute__((address_space(1))) u32x4_t* wptr_t;
     const wptr_t wbase = (wptr_t)a.Wp + (size_t)(t_begin + ft) * tile_stride +
                          (size_t)(p_begin + cj0) * (kLoads * 64);
@@ -939,10 +973,15 @@ __device__ __forceinline__ void gemm_stream_body(gemm_args_ptr_t ap, const int x
             bf16x8_t wf[kPieceFrags];                    // the piece's eight weight fragments
 #pragma unroll
             for (int l = 0; l < kLoads; ++l) {
-              if (W8)
+              if (WF == 2) {
+                bf16x8_t f4[4];
+                w4_to_frags(buf[l], f4);
+                wf[4 * l] = f4[0]; wf[4 * l + 1] = f4[1]; wf[4 * l + 2] = f4[2]; wf[4 * l + 3] = f4[3];
+              } else if (WF == 1) {
                 w8_to_frags(buf[l], wf[2 * l], wf[2 * l + 1]);
-              else
+              } else {
                 wf[l] = __builtin_bit_cast(bf16x8_t, buf[l]);
+              }
             }
 #pragma unroll
             for (int f = 0; f < kPieceFrags; ++f) {
@@ -963,7 +1002,8 @@ __device__ __forceinline__ void gemm_stream_body(gemm_args_ptr_t ap, const int x
               acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0l, w, acc0, 0, 0, 0);
               acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1l, w, acc1, 0, 0, 0);
             }
-            if (W8) __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);   // conversion of fragment 0
+            if (WF == 1) __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);   // conversion of fragment 0
+            if (WF == 2) __builtin_amdgcn_sched_group_barrier(0x002, 21, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);       // LDS reads of fragment 0
 #pragma unroll
             for (int f = 0; f < kPieceFrags - 1; ++f) {
@@ -971,7 +1011,8 @@ __device__ __forceinline__ void gemm_stream_body(gemm_args_ptr_t ap, const int x
               for (int q = 0; q < 4; ++q) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA of fragment f
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read of fragment f + 1
-                if (W8) __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   // a quarter of fragment f + 1's conversion
+                if (WF == 1) __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   // a quarter of fragment f + 1's conversion
+                if (WF == 2) __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
               }
             }
             __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
@@ -1053,7 +1094,7 @@ __device__ __forceinline__ void gemm_stream_body(gemm_args_ptr_t ap, const int x
     // ---- second half: group barrier, reduction, epilogue (arguments read afresh) ----
     gemm_args_ptr_t ap2 = ap;
     asm volatile("" : "+s"(ap2));
-    gemm_reduce_phase<PRO, EPI, W8>(ap2, s_pos, s_crow, tid, lane, wave, xcd, u, mt);
+    gemm_reduce_phase<PRO, EPI, WF>(ap2, s_pos, s_crow, tid, lane, wave, xcd, u, mt);
   }
 }
 
@@ -1065,7 +1106,7 @@ __device__ __forceinline__ void gemm_stream_body(gemm_args_ptr_t ap, const int x
 //    other on the same XCD: they stream the same weights at about the same time, so that all but
 //    the first find them in that XCD's L2 and the matrix leaves HBM about once per launch however
 //    many rows there are.
-template <int PRO, int EPI, bool MULTI, bool W8, bool ROWS>
+template <int PRO, int EPI, bool MULTI, int WF, bool ROWS>
 __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
   __shared__ uint4 lds_raw[(kGemmLdsAlloc + 15) / 16];
   gemm_args_ptr_t ap = (gemm_args_ptr_t)__builtin_amdgcn_kernarg_segment_ptr();
@@ -1076,7 +1117,7 @@ __global__ __launch_bounds__(256, 1) void gemm_stream_bf16(const GemmArgs a) {
     mt = gm % m_tiles;
     u = (gm / m_tiles) * a.S + sp;
   }
-  gemm_stream_body<PRO, EPI, MULTI, W8, ROWS>(ap, blockIdx.x, u, mt, carve_gemm_lds(lds_raw));
+  gemm_stream_body<PRO, EPI, MULTI, WF, ROWS>(ap, blockIdx.x, u, mt, carve_gemm_lds(lds_raw));
 }
 
 }  // namespace sv

@@ -72,22 +72,23 @@ __device__ inline float block_sum_256(float v, float* scratch) {
 // Where the pieces of a packed layer live (bytes from the start of the blob).
 struct PackedLayout {
   size_t g1, g2, wqkv, wo, wgu, wd, total;
-  size_t sqkv, so, sgu, sd;      // SV_BF16_W8: float32 row scales in packed row order
+  size_t sqkv, so, sgu, sd;      // SV_BF16_W8 / SV_BF16_W4: float32 row scales in packed row order
 };
 
 inline PackedLayout packed_layout(const sv_model_cfg& c) {
-  const size_t es = c.dtype == SV_F32 ? 4 : (c.dtype == SV_BF16_W8 ? 1 : 2);
+  // half bytes per matrix element: float32 8, bf16 4, E4M3 2, int4 1
+  const size_t eh = c.dtype == SV_F32 ? 8 : (c.dtype == SV_BF16_W8 ? 2 : (c.dtype == SV_BF16_W4 ? 1 : 4));
   const size_t H = c.hidden, D = (size_t)c.n_heads * c.head_dim, F = c.mlp_dim;
   PackedLayout L;
   size_t o = 0;
   L.g1 = o;   o = align_up(o + H * 4, kAlign);
   L.g2 = o;   o = align_up(o + H * 4, kAlign);
-  L.wqkv = o; o = align_up(o + 3 * D * H * es, kAlign);
-  L.wo = o;   o = align_up(o + H * D * es, kAlign);
-  L.wgu = o;  o = align_up(o + 2 * F * H * es, kAlign);
-  L.wd = o;   o = align_up(o + H * F * es, kAlign);
+  L.wqkv = o; o = align_up(o + 3 * D * H * eh / 2, kAlign);
+  L.wo = o;   o = align_up(o + H * D * eh / 2, kAlign);
+  L.wgu = o;  o = align_up(o + 2 * F * H * eh / 2, kAlign);
+  L.wd = o;   o = align_up(o + H * F * eh / 2, kAlign);
   L.sqkv = L.so = L.sgu = L.sd = 0;
-  if (c.dtype == SV_BF16_W8) {
+  if (c.dtype == SV_BF16_W8 || c.dtype == SV_BF16_W4) {
     L.sqkv = o; o = align_up(o + 3 * D * 4, kAlign);
     L.so = o;   o = align_up(o + H * 4, kAlign);
     L.sgu = o;  o = align_up(o + 2 * F * 4, kAlign);

@@ -66,6 +66,8 @@ class VerifyPass:
         packed = torch.empty(self.packed_bytes, dtype=torch.uint8, device=self.device)
         if self.cfg.dtype == sv.SV_BF16_W8:
             sv.sv_pack_layer_w8(self.cfg, dev, packed)
+        elif self.cfg.dtype == sv.SV_BF16_W4:
+            sv.sv_pack_layer_w4(self.cfg, dev, packed)
         else:
             sv.sv_pack_layer(self.cfg, dev, packed)
         torch.cuda.current_stream().synchronize()

@@ -151,6 +151,29 @@ def layer_weights_w8(cfg: VerifyConfig, layer: int) -> Dict[str, torch.Tensor]:
     return out
 
 
+def layer_weights_w4(cfg: VerifyConfig, layer: int) -> Dict[str, torch.Tensor]:
+    """Decoder layer `layer` with 4-bit integer matrices: gains as in layer_weights; every matrix
+    `w*` as uint8 [out, in / 2] holding two codes per byte (the code of the even k in the low four
+    bits; a code c in 0 .. 15 stands for the integer c - 8: a normal draw of standard deviation 2.5,
+    rounded and clipped to -8 .. 7) plus `w*_scale`, float32 [out], about 0.008 with a spread of a
+    few tens of percent per row - so the dequantised matrix has the scale of the bf16 one."""
+    H, F, D = cfg.hidden, cfg.mlp_dim, cfg.n_heads * cfg.head_dim
+    shapes = {"g1": (H,), "wq": (D, H), "wk": (D, H), "wv": (D, H), "wo": (H, D),
+              "g2": (H,), "wg": (F, H), "wu": (F, H), "wd": (H, F)}
+    seed = seed_for(cfg, 0, layer) + 4444
+    out = {}
+    for i, name in enumerate(LAYER_TENSORS):
+        if name.startswith("g"):
+            out[name] = _normal(shapes[name], seed, i, torch.bfloat16, 0.02, 1.0)
+        else:
+            z = _normal(shapes[name], seed, i, torch.float32, 2.5)
+            code = (torch.clamp(torch.round(z), -8, 7) + 8).to(torch.uint8)
+            out[name] = (code[:, 0::2] | (code[:, 1::2] << 4)).contiguous()
+            u = torch.rand(shapes[name][0], generator=_gen(seed, 100 + i), dtype=torch.float32)
+            out[name + "_scale"] = 0.008 * (0.75 + 0.5 * u)
+    return out
+
+
 def all_layer_weights(cfg: VerifyConfig, workers: int = 8) -> List[Dict[str, torch.Tensor]]:
     """All layers; the draws are independent per layer so they run in threads."""
     with ThreadPoolExecutor(max_workers=max(1, workers)) as ex:

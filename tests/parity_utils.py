@@ -12,6 +12,7 @@ import numpy as np
 import torch
 
 from oracle import fp8_weights as f8
+from oracle import int4_weights as i4
 from oracle import verify_oracle as vo
 from paper_2507_22424_amd import binding as sv
 from paper_2507_22424_amd import workload as wl
@@ -100,6 +101,12 @@ class SideBySide:
                 self.gpu.load_layer(l, w)
                 w64 = {k: (f64(v) if k.startswith("g") else
                            f8.dequantise(v.numpy(), w[k + "_scale"].numpy()))
+                       for k, v in w.items() if not k.endswith("_scale")}
+            elif cfg.dtype == "bf16_w4":     # 4-bit integer matrices: likewise
+                w = wl.layer_weights_w4(cfg, l)
+                self.gpu.load_layer(l, w)
+                w64 = {k: (f64(v) if k.startswith("g") else
+                           i4.dequantise(v.numpy(), w[k + "_scale"].numpy()))
                        for k, v in w.items() if not k.endswith("_scale")}
             else:
                 w = wl.layer_weights(cfg, l)

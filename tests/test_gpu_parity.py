@@ -180,6 +180,32 @@ def test_w8_full_pass_32_layers():
     say(f"[C3-w8] logit err {s.logit_err.max():.3e}, tolerated argmax near-ties: {n_ties} of {len(s.ref_token)} nodes")
 
 
+# ---- 4-bit integer weight storage (codes + row scales), same bar as bf16 ---------------------
+
+@pytest.mark.parametrize("T,B,P", [(26, 2, 90), (60, 1, 280), (70, 2, 40)])
+def test_w4_small_model(T, B, P):
+    cfg = wl.C2.scaled(name=f"w4-small-T{T}-B{B}", index=60 + B, dtype="bf16_w4", n_layers=3,
+                       hidden=512, n_heads=4, head_dim=128, mlp_dim=1536, vocab=1024, n_bins=256,
+                       tree_nodes=T, n_episodes=B, prefix_lo=max(1, P - 50), prefix_hi=P,
+                       max_children=6, r_values=(0, 4))
+    s = SideBySide(cfg)
+    check_forward(s, TOL["bf16"])
+    check_accept_paths(s, (0, 4))
+
+
+def test_w4_one_7b_layer():
+    s = SideBySide(wl.C2.scaled(name="C2-w4", vocab=32000, dtype="bf16_w4"))
+    check_forward(s, TOL["bf16"])
+
+
+def test_w4_full_pass_32_layers():
+    """The benchmark's workload with 4-bit integer matrices, all 32 layers deep."""
+    s = SideBySide(wl.C3.scaled(name="C3-w4", dtype="bf16_w4"), per_layer=False)
+    n_ties = check_forward(s, TOL["bf16"])
+    check_accept_paths(s, wl.C3.r_values)
+    say(f"[C3-w4] logit err {s.logit_err.max():.3e}, tolerated argmax near-ties: {n_ties} of {len(s.ref_token)} nodes")
+
+
 # ---- configuration 2: one 7B-shaped layer, bf16 ------------------------------------------
 
 def test_c2_one_7b_layer_bf16():

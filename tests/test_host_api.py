@@ -159,6 +159,34 @@ def test_eight_bit_weight_packing_checks_its_arguments_before_any_launch():
     assert lib.sv_pack_layer_w8(C.byref(odd), C.byref(raw), C.byref(sc), one, 1 << 30, None) == -2
 
 
+def test_four_bit_weight_packing_checks_its_arguments_before_any_launch():
+    """SV_BF16_W4: a quarter of the bf16 matrix bytes plus the row scales; each pack call refuses
+    the dtypes of the others; nothing is launched on bad arguments."""
+    lib = sv.lib()
+    bf = sv.model_cfg("bf16", 512, 4, 128, 1536, 1024, 1e-5, 10000.0)
+    w8 = sv.model_cfg("bf16_w8", 512, 4, 128, 1536, 1024, 1e-5, 10000.0)
+    w4 = sv.model_cfg("bf16_w4", 512, 4, 128, 1536, 1024, 1e-5, 10000.0)
+    n8, n4 = sv.sv_packed_layer_bytes(w8), sv.sv_packed_layer_bytes(w4)
+    H, D, F = 512, 512, 1536
+    matrix_elems = 3 * D * H + H * D + 2 * F * H + H * F
+    scales = 4 * (3 * D + 2 * H + 2 * F)
+    assert matrix_elems // 2 + scales <= n4 <= matrix_elems // 2 + scales + 2 * 512 * 4 + 12 * 256
+    assert n8 - n4 >= matrix_elems // 2 - 8 * 256
+    one = C.c_void_p(256)
+    raw = sv.LayerWeights(*([256] * 9))
+    sc = sv.LayerScales(*([256] * 7))
+    assert lib.sv_pack_layer_w4(C.byref(bf), C.byref(raw), C.byref(sc), one, 1 << 30, None) == -6
+    assert lib.sv_pack_layer_w4(C.byref(w8), C.byref(raw), C.byref(sc), one, 1 << 30, None) == -6
+    assert lib.sv_pack_layer_w8(C.byref(w4), C.byref(raw), C.byref(sc), one, 1 << 30, None) == -6
+    assert lib.sv_pack_layer(C.byref(w4), C.byref(raw), one, 1 << 30, None) == -6
+    assert lib.sv_pack_layer_w4(C.byref(w4), None, C.byref(sc), one, 1 << 30, None) == -1
+    assert lib.sv_pack_layer_w4(C.byref(w4), C.byref(raw), None, one, 1 << 30, None) == -1
+    assert lib.sv_pack_layer_w4(C.byref(w4), C.byref(raw), C.byref(sc), one, n4 - 1, None) == -5
+    assert lib.sv_pack_layer_w4(C.byref(w4), C.byref(raw), C.byref(sc), C.c_void_p(260), n4, None) == -5
+    odd = sv.model_cfg("bf16_w4", 384, 4, 128, 1536, 1024, 1e-5, 10000.0)      # hidden not a multiple of 256
+    assert lib.sv_pack_layer_w4(C.byref(odd), C.byref(raw), C.byref(sc), one, 1 << 30, None) == -2
+
+
 def test_packed_head_checks_its_arguments_before_any_launch():
     """Packed head: gain + rows in bytes; bf16 only; scored range a multiple of 32 inside the
     vocabulary; buffers aligned and large enough; workspace grows with the scored rows."""
