@@ -64,8 +64,7 @@ __device__ inline void split8(const float* v, bf16x8_t& hi, bf16x8_t& lo) {
 
 // Work of one workgroup of NW waves: query block bx = (episode, block of 16 nodes), head by.
 // lds_raw: NW * 128 * kVtPitch bytes; s_m, s_l: [NW][16] floats; sync(): barrier of the waves
-// that run this body (called twice).  DEV_OUT: the result is written with device-scope stores
-// (for readers on other XCDs inside the same launch).
+// that run this body (called twice).
 // head_dim = 128.
 // q: float32 [M, nh*128] (rotated);  kc, vc: bf16 [B][nh][cap][128];  out: float32 [M, nh*128].
 // Long prefixes: the key tiles can be dealt to n_split workgroups (split = which of them this
@@ -73,7 +72,7 @@ __device__ inline void split8(const float* v, bf16x8_t& hi, bf16x8_t& lo) {
 // `part` ([n_split][M][nh][kAttPartStride] floats) and attention_merge_kernel combines them in
 // split order.  With n_split = 1 the result goes straight to `out`.
 constexpr int kAttPartStride = 132;   // 128 outputs, maximum, sum, padding
-template <int NW, bool DEV_OUT, typename Sync>
+template <int NW, typename Sync>
 __device__ inline void tree_attention_body(
     const float* __restrict__ q, const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc,
     const int32_t* __restrict__ prefix_len, int p_max, const uint64_t* __restrict__ anc,
@@ -270,12 +269,7 @@ __device__ inline void tree_attention_body(
             dst[129] = den;
           }
         } else {
-          float* dst = out + ((size_t)b * T + tnode) * D + h * 128 + d;
-          if (DEV_OUT)
-            __hip_atomic_store((__attribute__((address_space(1))) float*)dst, num / den, __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
-          else
-            *dst = num / den;
+          out[((size_t)b * T + tnode) * D + h * 128 + d] = num / den;
         }
       }
     }
@@ -304,7 +298,7 @@ __global__ __launch_bounds__(64 * NW) void tree_attention_mfma(
   const unsigned item = (total & 7u) ? lin : (lin & 7u) * (total >> 3) + (lin >> 3);
   const unsigned task = item / ns, split = item - task * ns;
   const unsigned head = task / gridDim.x;
-  tree_attention_body<NW, false>(q, kc, vc, prefix_len, p_max, anc, n_words, T, nh, cap, out,
+  tree_attention_body<NW>(q, kc, vc, prefix_len, p_max, anc, n_words, T, nh, cap, out,
                                  (int)(task - head * gridDim.x), (int)head, lds_raw, s_m, s_l,
                                  (int)threadIdx.x, [] { __syncthreads(); }, (int)split, (int)ns, part,
                                  M_total);
