@@ -174,7 +174,7 @@ def test_w8_one_7b_layer():
 
 def test_w8_full_pass_32_layers():
     """The benchmark's workload with 8-bit matrices, all 32 layers deep."""
-    s = SideBySide(wl.C3.scaled(name="C3-w8", dtype="bf16_w8"), per_layer=False)
+    s = SideBySide(wl.C3.scaled(name="C3-w8", dtype="bf16_w8"))
     n_ties = check_forward(s, TOL["bf16"])
     check_accept_paths(s, wl.C3.r_values)
     say(f"[C3-w8] logit err {s.logit_err.max():.3e}, tolerated argmax near-ties: {n_ties} of {len(s.ref_token)} nodes")
@@ -200,7 +200,7 @@ def test_w4_one_7b_layer():
 
 def test_w4_full_pass_32_layers():
     """The benchmark's workload with 4-bit integer matrices, all 32 layers deep."""
-    s = SideBySide(wl.C3.scaled(name="C3-w4", dtype="bf16_w4"), per_layer=False)
+    s = SideBySide(wl.C3.scaled(name="C3-w4", dtype="bf16_w4"))
     n_ties = check_forward(s, TOL["bf16"])
     check_accept_paths(s, wl.C3.r_values)
     say(f"[C3-w4] logit err {s.logit_err.max():.3e}, tolerated argmax near-ties: {n_ties} of {len(s.ref_token)} nodes")
@@ -234,7 +234,7 @@ def test_c5_long_prefix_two_layers():
 @pytest.mark.timeout(1500)
 def test_c4_full_pass_32_layers():
     """Configuration 4 as stated: 16 episodes, ragged prefixes, all 32 layers, head, acceptance."""
-    s = SideBySide(wl.C4, per_layer=False)
+    s = SideBySide(wl.C4)
     n_ties = check_forward(s, TOL["bf16"])
     check_accept_paths(s, wl.C4.r_values)
     say(f"[C4] 32 layers: logit err {s.logit_err.max():.3e}, tolerated near-ties {n_ties} of {len(s.ref_token)}")
@@ -243,7 +243,7 @@ def test_c4_full_pass_32_layers():
 @pytest.mark.timeout(1500)
 def test_c5_full_pass_32_layers():
     """Configuration 5 as stated: prefix 2048, 128 nodes (two mask words), all 32 layers."""
-    s = SideBySide(wl.C5, per_layer=False)
+    s = SideBySide(wl.C5)
     n_ties = check_forward(s, TOL["bf16"])
     check_accept_paths(s, wl.C5.r_values)
     say(f"[C5] 32 layers: logit err {s.logit_err.max():.3e}, tolerated near-ties {n_ties} of {len(s.ref_token)}")
