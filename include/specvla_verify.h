@@ -200,9 +200,12 @@ int sv_tree_build_device(const int32_t *cand_parent, const float *cand_logp,
  *   kv, tree:  [host] structs of [device] pointers, see above; tree->n_nodes = T
  *   workspace: [device], 256-byte aligned, ws_bytes >= sv_workspace_bytes(cfg, B, T, *),
  *              prepared once with sv_workspace_init; calls sharing a workspace must not overlap
- * bf16 models, up to 128 rows: the projections are split along K and their partial sums travel
+ * bf16 models (also with 8-bit or 4-bit weights): up to 64 rows, and any number of rows with
+ * 8-bit or 4-bit weights, the projections are split along K and their partial sums travel
  * in 16 bits with one scale per 64-row x 32-column tile (error <= 2^-14 of the tile's largest
- * partial sum, each row first brought to a common size).  A partial sum that is not finite
+ * partial sum, each row first brought to a common size); with more than 64 rows and bf16
+ * weights the projections run on kernels bound by the matrix cores whose partial sums, where K
+ * is split at all, are float32.  A partial sum that is not finite
  * travels as a code of its own and comes back as NaN: a NaN or infinity reaches exactly the
  * outputs it reaches by the layer's own arithmetic, one exception aside - inside the tree
  * attention a NaN in the value row of a tree node also reaches the other nodes of that episode
