@@ -237,3 +237,14 @@ def test_stream_read_checks_its_arguments_before_any_launch():
     assert lib.sv_stream_read(a, 4100, a, None) == -2
     assert lib.sv_stream_read(C.c_void_p(4100), 4096, a, None) == -2
     assert lib.sv_stream_read(a, 4096, C.c_void_p(4104), None) == -2
+
+
+def test_bench_refuses_more_than_one_gpu_with_a_message():
+    """Nothing here uses a second GPU: `bench.py --gpus N` with N > 1 exits with a message (before
+    anything touches a GPU)."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=300)
+    assert r.returncode != 0
+    assert "--gpus must be 1" in (r.stderr + r.stdout)
