@@ -141,10 +141,13 @@ def test_f32_odd_shapes(T, B, P):
 
 # ---- bf16, small model: several tiles, ragged prefixes, 2e-2 -------------------------------
 
-@pytest.mark.parametrize("T,B,P", [(26, 3, 90), (60, 1, 280), (128, 1, 300), (70, 2, 40), (26, 1, 1200)])
+@pytest.mark.parametrize("T,B,P", [(26, 3, 90), (60, 1, 280), (128, 1, 300), (70, 2, 40), (26, 1, 1200),
+                                   (100, 3, 150), (128, 2, 64)])
 def test_bf16_small_model(T, B, P):
-    """Several row tiles, ragged prefixes; the last case has so few (episode, head, query block)
-    tasks and so long a prefix that the tree attention splits its keys across workgroups."""
+    """Several row tiles, ragged prefixes: 64 rows and fewer on the streaming kernel, more on the
+    many-row kernels with one, two or three 128-row blocks (with and without K split across
+    workgroups); the case (26, 1, 1200) has so few (episode, head, query block) tasks and so long
+    a prefix that the tree attention splits its keys across workgroups."""
     cfg = wl.C2.scaled(name=f"bf16-small-T{T}-B{B}", index=20 + B, n_layers=3, hidden=512,
                        n_heads=4, head_dim=128, mlp_dim=1536, vocab=1024, n_bins=256,
                        tree_nodes=T, n_episodes=B, prefix_lo=max(1, P - 50), prefix_hi=P,
