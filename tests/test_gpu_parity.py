@@ -272,10 +272,13 @@ def _small_bf16(T=26, B=2, P=70, layers=2, name="bf16-robust"):
                         prefix_lo=max(0, P - 20), prefix_hi=P, max_children=4, r_values=(0, 4))
 
 
-def test_results_are_bit_reproducible_and_independent_of_workspace_contents():
+@pytest.mark.parametrize("T,B", [(26, 2), (40, 2), (100, 3)])
+def test_results_are_bit_reproducible_and_independent_of_workspace_contents(T, B):
     """Split-K partial sums are added in a fixed order: two runs give identical bits, also after
-    the scratch workspace was filled with NaN patterns (only sv_workspace_init's counters count)."""
-    s = SideBySide(_small_bf16(), per_layer=False)
+    the scratch workspace was filled with NaN patterns (only sv_workspace_init's counters count).
+    52 rows run on the streaming kernel, 80 and 300 on the many-row kernels (K split across
+    workgroups, float32 partial blocks)."""
+    s = SideBySide(_small_bf16(T=T, B=B, name=f"bf16-robust-T{T}-B{B}"), per_layer=False)
     first = (s.gpu_logits.copy(), s.gpu_x.copy(), s.gpu_token.copy())
     s.gpu.workspace.fill_(0xFF)                      # NaN everywhere, counters included
     sv.sv_workspace_init(s.gpu.cfg, s.gpu.B, s.gpu.T, s.gpu.n_scored, s.gpu.workspace)
@@ -306,11 +309,13 @@ def test_bf16_rows_of_very_different_size_keep_their_relative_precision():
     check_forward(s, TOL["bf16"])
 
 
-def test_bf16_nan_in_one_episode_stays_in_that_episode():
+@pytest.mark.parametrize("T", [24, 40])
+def test_bf16_nan_in_one_episode_stays_in_that_episode(T):
     """A NaN in an input row of episode 1: episode 0, which shares the row tile, the partial
     tiles and the launches with it, is unaffected and still matches the oracle; the poisoned
-    row itself comes out as NaN on both sides."""
-    cfg = _small_bf16(T=24, B=2, P=50, name="bf16-nan-row")
+    row itself comes out as NaN on both sides.  (48 rows: streaming kernel; 80 rows: many-row
+    kernels.)"""
+    cfg = _small_bf16(T=T, B=2, P=50, name=f"bf16-nan-row-T{T}")
     T = cfg.tree_nodes
 
     def poison(b, h):
