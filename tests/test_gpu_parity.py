@@ -300,11 +300,13 @@ def test_bf16_degenerate_trees_and_prefixes(T, B, P):
     check_accept_paths(s, (0, 2))
 
 
-def test_bf16_rows_of_very_different_size_keep_their_relative_precision():
+@pytest.mark.parametrize("T", [30, 45])
+def test_bf16_rows_of_very_different_size_keep_their_relative_precision(T):
     """Rows that share a 64-row tile and differ by up to 10^8 in size: every row still meets the
     bar measured against its own size (the split-K partial sums travel as 16-bit fixed point, so
-    this holds only because each row is normalised before the tile's scale is chosen)."""
-    cfg = _small_bf16(T=30, B=2, P=60, name="bf16-row-sizes")
+    this holds only because each row is normalised before the tile's scale is chosen; with 90
+    rows the many-row kernels run, whose activations are normalised before they are split)."""
+    cfg = _small_bf16(T=T, B=2, P=60, name=f"bf16-row-sizes-T{T}")
     s = SideBySide(cfg, hidden_transform=lambda b, h: h * wl.row_magnitudes(cfg, b, 4.0)[:, None])
     check_forward(s, TOL["bf16"])
 
