@@ -462,11 +462,13 @@ def test_stream_read_aid_runs_on_ragged_sizes_and_leaves_memory_alone():
         assert torch.equal(buf, keep) and int(sink.sum()) == 0
 
 
-def test_graph_replays_match_host_launched_steps():
+@pytest.mark.parametrize("T", [26, 48])
+def test_graph_replays_match_host_launched_steps(T):
     """One step recorded into a HIP graph and replayed: every replay - with new hidden rows and
     draft tokens written between replays, host-launched steps and synchronisations in between -
-    gives bit for bit what the host-launched step gives on the same inputs."""
-    cfg = _small_bf16(T=26, B=2, P=40, name="bf16-graph")
+    gives bit for bit what the host-launched step gives on the same inputs.  (52 rows: streaming
+    kernel; 96 rows: the many-row kernels with their split, row-norm and reduction launches.)"""
+    cfg = _small_bf16(T=T, B=2, P=40, name=f"bf16-graph-T{T}")
     B, T = cfg.n_episodes, cfg.tree_nodes
     pl = wl.prefix_lengths(cfg)
     parents = [wl.episode_tree(cfg, b) for b in range(B)]
